@@ -1,0 +1,141 @@
+/*
+ * fge.h - C ABI of the fused GEMM + activation + row-normalisation library for MI355X (gfx950).
+ *
+ * The operation is the fused operator chain that a kernel generator emits for a dense layer
+ * followed by an activation and a row-wise reduction / normalisation (the paper's "fused
+ * operations" and "normalization operations" categories, Section 4; the reason for fusing -
+ * no intermediate memory traffic, one launch instead of several - is its Section 5.3):
+ *
+ *     Y   = post_scale * (alpha * X . W^T + b)          X: rows x K,  W: N x K,  b: N
+ *     A   = act(Y)                                      elementwise
+ *     out = rowop_N(A)                                  over the N columns of each row
+ *
+ * Layout.  X and W are row-major with the contraction axis K contiguous (row strides ldx,
+ * ldw in elements); out is row-major rows x N (row stride ldo).  b, gamma, beta are fp32
+ * vectors of length N; aux_out is an fp32 vector with one entry per row.  With batch > 1 the
+ * library processes `batch` problems of M rows each that share W, b, gamma, beta; problem z
+ * reads X + z*batch_stride_x, writes out + z*batch_stride_o and aux_out + z*M.
+ *
+ * Ownership.  Every pointer except `p` and the returned strings is DEVICE memory owned by
+ * the caller.  The library allocates nothing, frees nothing and keeps no pointer after a call
+ * returns.  `workspace` is caller-provided device scratch of at least fge_workspace_bytes().
+ *
+ * Asynchrony.  Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
+ * the default stream) and return; they never synchronise the device.
+ *
+ * Errors.  Every function returning int returns an fge_status.  All argument checks are done
+ * on the host before anything is launched, so a non-zero status other than FGE_ERR_HIP means
+ * that no work was enqueued.  A shape the kernels cannot handle yields FGE_ERR_UNSUPPORTED,
+ * never a wrong result (the paper's benchmark section names silent divisibility assumptions
+ * as the typical failure of generated kernels under dynamic shapes).
+ *
+ * Supported set.  in_dtype, out_dtype in {FGE_F32, FGE_BF16} (accumulation and all epilogue
+ * arithmetic in fp32; bf16 stores round to nearest even).  Any M >= 1, batch >= 1.  K, N
+ * >= 1 with K*sizeof(in) and N*sizeof(out) multiples of 16 bytes; ldx, ldw, ldo and the batch
+ * strides likewise multiples of 16 bytes; base pointers 16-byte aligned (else FGE_ERR_ALIGN).
+ * Row operations need N <= 65536.  out must not alias X or W.
+ */
+#ifndef FGE_H
+#define FGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FGE_OK = 0,
+    FGE_ERR_NULL = 1,         /* a required pointer is NULL                                  */
+    FGE_ERR_BAD_ENUM = 2,     /* act / norm / dtype code out of range                        */
+    FGE_ERR_BAD_SHAPE = 3,    /* M, N, K, batch <= 0, or a stride smaller than the extent    */
+    FGE_ERR_UNSUPPORTED = 4,  /* valid request outside the supported set                     */
+    FGE_ERR_ALIGN = 5,        /* pointer or stride not 16-byte aligned                       */
+    FGE_ERR_WORKSPACE = 6,    /* workspace NULL or smaller than fge_workspace_bytes()        */
+    FGE_ERR_HIP = 7           /* a launch failed; see fge_last_hip_error()                   */
+} fge_status;
+
+typedef enum { FGE_F32 = 0, FGE_BF16 = 1 } fge_dtype;
+
+/* Activations (step A = act(Y)).  GELU_TANH: 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3)));
+ * GELU_ERF: 0.5 y (1 + erf(y / sqrt 2)); SILU: y / (1 + exp(-y)); CLAMP: min(max(y, lo), hi). */
+typedef enum {
+    FGE_ACT_NONE = 0, FGE_ACT_RELU = 1, FGE_ACT_GELU_TANH = 2, FGE_ACT_GELU_ERF = 3,
+    FGE_ACT_SILU = 4, FGE_ACT_CLAMP = 5
+} fge_act;
+
+/* Row operations over N.
+ *   SOFTMAX   : out_j = exp(a_j - m) / sum_l exp(a_l - m),  m = max_j a_j
+ *   LAYERNORM : out_j = (a_j - mu) / sqrt(var + eps) * gamma_j + beta_j, biased variance
+ *   RMSNORM   : out_j = a_j / sqrt(mean_j(a_j^2) + eps) * gamma_j   (eps inside the root, as in
+ *               the paper's RMSNorm sketch, Fig. 2)
+ *   LOGSUMEXP : out = A unchanged, aux_out[row] = m + ln sum_j exp(a_j - m)               */
+typedef enum {
+    FGE_NORM_NONE = 0, FGE_NORM_SOFTMAX = 1, FGE_NORM_LAYERNORM = 2, FGE_NORM_RMSNORM = 3,
+    FGE_NORM_LOGSUMEXP = 4
+} fge_norm;
+
+typedef struct fge_params {
+    int32_t M, N, K, batch;        /* rows per problem, columns, contraction length, problems  */
+    int64_t ldx, ldw, ldo;         /* row strides in elements (K, K, N when dense)             */
+    int64_t batch_stride_x;        /* elements between problems in X (M*ldx when dense)        */
+    int64_t batch_stride_o;        /* elements between problems in out (M*ldo when dense)      */
+    int32_t in_dtype, out_dtype;   /* fge_dtype of X and W / of out and unfused intermediates  */
+    float   alpha, post_scale;     /* Y = post_scale * (alpha * X.W^T + b)                     */
+    float   clamp_lo, clamp_hi;    /* FGE_ACT_CLAMP bounds                                     */
+    float   eps;                   /* LAYERNORM / RMSNORM                                      */
+    const float *gamma, *beta;     /* device, length N; NULL means all ones / all zeros        */
+    float  *aux_out;               /* device, batch*M floats; required for LOGSUMEXP only      */
+    void   *workspace;             /* device scratch, 16-byte aligned                          */
+    size_t  workspace_bytes;       /* its size                                                 */
+} fge_params;
+
+/* The fused path: one tile kernel that keeps the accumulators in registers through scale,
+ * bias, activation and the in-tile row reduction, followed - only when a row spans several
+ * column tiles - by a light second kernel that merges the per-tile row statistics and
+ * finishes the normalisation in place in `out`.  b may be NULL (no bias). */
+int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
+                        const fge_params *p, void *out, void *stream);
+
+/* The unfused reference sequence built from the same device pieces: K1 Y = post_scale*(alpha*
+ * X.W^T + b) -> workspace, K2 A = act(Y) -> workspace (-> out for NONE / LOGSUMEXP), K3
+ * out = rowop(A).  Intermediates are stored in out_dtype, as an eager framework would. */
+int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
+                          const fge_params *p, void *out, void *stream);
+
+/* Bytes of workspace the fused (fused != 0) or unfused (fused == 0) path needs for these
+ * arguments; 0 is a valid answer.  Returns (size_t)-1 when the arguments are invalid. */
+size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p);
+
+/* ---- the individual stages, callable on their own (the two paths above are built from them) */
+
+/* Fused stage 1: the tile kernel.  When the chosen tile spans N it produces the final out. */
+int fge_fused_tiles(const void *X, const void *W, const float *b, int act, int norm,
+                    const fge_params *p, void *out, void *stream);
+/* Fused stage 2: merge per-tile row statistics from the workspace and finish `out` in place.
+ * A no-op (FGE_OK, nothing enqueued) when stage 1 already produced the final result. */
+int fge_fused_finish(int act, int norm, const fge_params *p, void *out, void *stream);
+/* 1 if fge_fused_finish has work to do for these arguments, 0 if not, negative on bad args. */
+int fge_fused_needs_finish(int act, int norm, const fge_params *p);
+
+/* Unfused K1: Y (rows x N, out_dtype, row stride ldo) = post_scale * (alpha * X.W^T + b). */
+int fge_gemm_bias(const void *X, const void *W, const float *b, const fge_params *p,
+                  void *Y, void *stream);
+/* Unfused K2: A = act(Y), both rows x N in out_dtype with row stride ldo; A may equal Y. */
+int fge_activation(const void *Y, int act, const fge_params *p, void *A, void *stream);
+/* Unfused K3: out = rowop(A), both rows x N in out_dtype with row stride ldo; out may equal A. */
+int fge_row_op(const void *A, int norm, const fge_params *p, void *out, void *stream);
+
+/* Static description of a status code. */
+const char *fge_status_string(int status);
+/* hipError_t (as int) recorded by the calling thread's last FGE_ERR_HIP, else 0. */
+int fge_last_hip_error(void);
+/* Name of the tile configuration the fused path picks for these arguments (static string,
+ * e.g. "256x256x64_w2x4"); NULL on invalid arguments.  For reports and tests. */
+const char *fge_tile_name(int fused, int act, int norm, const fge_params *p);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FGE_H */

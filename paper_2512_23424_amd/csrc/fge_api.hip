@@ -1,0 +1,317 @@
+// Host side of the C ABI declared in include/fge.h: argument validation (before anything is
+// launched), tile selection, workspace layout and the kernel launches on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include "fge_launch.h"
+#include "fge_rowops.h"
+
+using namespace fge;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 CUs
+constexpr int MAX_ROWOP_N = 8192;    // a row must fit the register-resident row kernels
+constexpr int MAX_SPLIT = 64;        // column tiles per row the second pass can merge (one per lane)
+
+inline size_t esize(int dt) { return dt == FGE_BF16 ? 2 : 4; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Shape after folding a dense batch into the row count.
+struct Problem {
+    int M, N, K, batch;
+    int64_t ldx, ldw, ldo, bsx, bso;
+};
+
+struct Plan {
+    Problem pr;
+    int tile;
+    int tiles_m, tiles_n;
+    bool needs_finish;           // rows split over several column tiles and a row op is requested
+    size_t ws_stats;             // bytes of per-tile statistics (fused)
+    size_t ws_buf;               // bytes of one out-shaped intermediate (unfused)
+    int n_bufs;                  // intermediates the unfused path needs
+};
+
+// Checks everything that does not depend on the path (fused / stage) being run.
+int check_common(const fge_params *p, int act, int norm, bool need_in) {
+    if (p == nullptr) return FGE_ERR_NULL;
+    if (act < FGE_ACT_NONE || act > FGE_ACT_CLAMP) return FGE_ERR_BAD_ENUM;
+    if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
+    if ((p->in_dtype != FGE_F32 && p->in_dtype != FGE_BF16) ||
+        (p->out_dtype != FGE_F32 && p->out_dtype != FGE_BF16))
+        return FGE_ERR_BAD_ENUM;
+    if (p->M <= 0 || p->N <= 0 || p->K <= 0 || p->batch <= 0) return FGE_ERR_BAD_SHAPE;
+    if (p->ldo < p->N) return FGE_ERR_BAD_SHAPE;
+    if (need_in && (p->ldx < p->K || p->ldw < p->K)) return FGE_ERR_BAD_SHAPE;
+    if (p->batch > 1) {
+        if (p->batch_stride_o < (int64_t)(p->M - 1) * p->ldo + p->N) return FGE_ERR_BAD_SHAPE;
+        if (need_in && p->batch_stride_x < (int64_t)(p->M - 1) * p->ldx + p->K) return FGE_ERR_BAD_SHAPE;
+    }
+    const size_t is = esize(p->in_dtype), os = esize(p->out_dtype);
+    if ((p->N * os) % 16 || (p->ldo * os) % 16) return FGE_ERR_ALIGN;
+    if (p->batch > 1 && (p->batch_stride_o * os) % 16) return FGE_ERR_ALIGN;
+    if (need_in) {
+        if ((p->K * is) % 16 || (p->ldx * is) % 16 || (p->ldw * is) % 16) return FGE_ERR_ALIGN;
+        if (p->batch > 1 && (p->batch_stride_x * is) % 16) return FGE_ERR_ALIGN;
+    }
+    if (!aligned16(p->gamma) || !aligned16(p->beta) || !aligned16(p->aux_out) || !aligned16(p->workspace))
+        return FGE_ERR_ALIGN;
+    if (norm != FGE_NORM_NONE && p->N > MAX_ROWOP_N) return FGE_ERR_UNSUPPORTED;
+    if ((int64_t)p->M * p->batch > (int64_t)INT32_MAX / 2) return FGE_ERR_UNSUPPORTED;
+    return FGE_OK;
+}
+
+int pick_tile(const Problem &pr, int in_dtype, int norm) {
+    // A tile spanning the whole row finishes the row operation without a second pass.
+    if (norm != FGE_NORM_NONE) {
+        if (pr.N <= 64) return TILE_64x64;
+        if (pr.N <= 512) return TILE_64x512;
+    }
+    // Otherwise the largest tile that still gives every CU at least one workgroup.  fp32 is
+    // bound by the MFMA rate, not by operand traffic, so it stops at 128x128.
+    const int order[3] = {TILE_256x256, TILE_128x128, TILE_64x64};
+    for (int t = (in_dtype == FGE_BF16 ? 0 : 1); t < 3; ++t) {
+        const TileInfo &ti = tile_info(order[t]);
+        const int64_t n = (int64_t)((pr.M + ti.bm - 1) / ti.bm) * ((pr.N + ti.bn - 1) / ti.bn) * pr.batch;
+        if (n >= NUM_CU || order[t] == TILE_64x64) return order[t];
+    }
+    return TILE_64x64;
+}
+
+Plan make_plan(const fge_params *p, int norm) {
+    Plan pl{};
+    Problem &pr = pl.pr;
+    pr = Problem{p->M, p->N, p->K, p->batch, p->ldx, p->ldw, p->ldo,
+                 p->batch > 1 ? p->batch_stride_x : 0, p->batch > 1 ? p->batch_stride_o : 0};
+    if (pr.batch > 1 && pr.bsx == (int64_t)pr.M * pr.ldx && pr.bso == (int64_t)pr.M * pr.ldo) {
+        pr.M *= pr.batch;            // dense batch: one tall problem (W, b, gamma, beta are shared)
+        pr.batch = 1;
+        pr.bsx = pr.bso = 0;
+    }
+    pl.tile = pick_tile(pr, p->in_dtype, norm);
+    const TileInfo &ti = tile_info(pl.tile);
+    pl.tiles_m = (pr.M + ti.bm - 1) / ti.bm;
+    pl.tiles_n = (pr.N + ti.bn - 1) / ti.bn;
+    pl.needs_finish = norm != FGE_NORM_NONE && pl.tiles_n > 1;
+    pl.ws_stats = pl.needs_finish ? round256((size_t)pr.M * pr.batch * pl.tiles_n * sizeof(float2)) : 0;
+    const size_t extent = (size_t)(pr.batch - 1) * pr.bso + (size_t)(pr.M - 1) * pr.ldo + pr.N;
+    pl.ws_buf = round256(extent * esize(p->out_dtype));
+    // K2 writes straight into `out` when the row op leaves the activated values in place
+    pl.n_bufs = (norm == FGE_NORM_NONE || norm == FGE_NORM_LOGSUMEXP) ? 1 : 2;
+    return pl;
+}
+
+int hip_status(hipError_t e) {
+    if (e == hipSuccess) return FGE_OK;
+    g_last_hip = (int)e;
+    return FGE_ERR_HIP;
+}
+
+TileArgs tile_args(const void *X, const void *W, const float *b, int act, int norm,
+                   const fge_params *p, const Plan &pl, void *out) {
+    TileArgs a{};
+    a.X = X; a.W = W; a.b = b; a.gamma = p->gamma; a.beta = p->beta;
+    a.out = out; a.aux = p->aux_out; a.ws = reinterpret_cast<float2 *>(p->workspace);
+    a.M = pl.pr.M; a.N = pl.pr.N; a.K = pl.pr.K;
+    a.ldx = pl.pr.ldx; a.ldw = pl.pr.ldw; a.ldo = pl.pr.ldo; a.bsx = pl.pr.bsx; a.bso = pl.pr.bso;
+    a.alpha = p->alpha; a.post = p->post_scale; a.lo = p->clamp_lo; a.hi = p->clamp_hi; a.eps = p->eps;
+    a.act = act; a.norm = norm;
+    a.tiles_m = pl.tiles_m; a.tiles_n = pl.tiles_n;
+    a.group_m = pl.tiles_m < 8 ? pl.tiles_m : 8;
+    return a;
+}
+
+int launch_tiles(const TileArgs &a, const fge_params *p, const Plan &pl, hipStream_t s) {
+    const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n), 1, (unsigned)pl.pr.batch);
+    const hipError_t e = p->in_dtype == FGE_BF16 ? launch_tile_bf16(pl.tile, p->out_dtype, grid, s, a)
+                                                 : launch_tile_f32(pl.tile, p->out_dtype, grid, s, a);
+    return hip_status(e);
+}
+
+RowArgs row_args(const void *in, void *out, int act, int norm, const fge_params *p, const Plan &pl) {
+    RowArgs r{};
+    r.in = in; r.out = out; r.gamma = p->gamma; r.beta = p->beta; r.aux = p->aux_out;
+    r.ws = reinterpret_cast<const float2 *>(p->workspace);
+    r.M = pl.pr.M; r.N = pl.pr.N; r.batch = pl.pr.batch; r.ldo = pl.pr.ldo; r.bso = pl.pr.bso;
+    r.lo = p->clamp_lo; r.hi = p->clamp_hi; r.eps = p->eps; r.act = act; r.norm = norm;
+    r.tiles_n = pl.tiles_n; r.bn = tile_info(pl.tile).bn;
+    return r;
+}
+
+template <typename T> int launch_rownorm(const RowArgs &r, hipStream_t s) {
+    const int cpr = r.N / Store<T>::CW;
+    const int ch = (cpr + 63) / 64;
+    const int64_t rows = (int64_t)r.batch * r.M;
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    if (ch <= 1)       hipLaunchKernelGGL((rownorm_kernel<T, 1>), grid, block, 0, s, r);
+    else if (ch <= 2)  hipLaunchKernelGGL((rownorm_kernel<T, 2>), grid, block, 0, s, r);
+    else if (ch <= 4)  hipLaunchKernelGGL((rownorm_kernel<T, 4>), grid, block, 0, s, r);
+    else if (ch <= 8)  hipLaunchKernelGGL((rownorm_kernel<T, 8>), grid, block, 0, s, r);
+    else if (ch <= 16) hipLaunchKernelGGL((rownorm_kernel<T, 16>), grid, block, 0, s, r);
+    else if (ch <= 32) hipLaunchKernelGGL((rownorm_kernel<T, 32>), grid, block, 0, s, r);
+    else return FGE_ERR_UNSUPPORTED;
+    return hip_status(hipGetLastError());
+}
+
+int do_fused_tiles(const void *X, const void *W, const float *b, int act, int norm,
+                   const fge_params *p, void *out, hipStream_t s, Plan *plan_out) {
+    int rc = check_common(p, act, norm, true);
+    if (rc) return rc;
+    if (!X || !W || !out) return FGE_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(out) || !aligned16(b)) return FGE_ERR_ALIGN;
+    if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
+    const Plan pl = make_plan(p, norm);
+    if (pl.needs_finish) {
+        if (pl.tiles_n > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
+        if (!p->workspace || p->workspace_bytes < pl.ws_stats) return FGE_ERR_WORKSPACE;
+    }
+    if (plan_out) *plan_out = pl;
+    return launch_tiles(tile_args(X, W, b, act, norm, p, pl, out), p, pl, s);
+}
+
+int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream_t s) {
+    int rc = check_common(p, act, norm, true);
+    if (rc) return rc;
+    if (!out) return FGE_ERR_NULL;
+    if (!aligned16(out)) return FGE_ERR_ALIGN;
+    if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
+    const Plan pl = make_plan(p, norm);
+    if (!pl.needs_finish) return FGE_OK;
+    if (pl.tiles_n > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
+    if (!p->workspace || p->workspace_bytes < pl.ws_stats) return FGE_ERR_WORKSPACE;
+    const RowArgs r = row_args(out, out, act, norm, p, pl);
+    const int64_t rows = (int64_t)r.batch * r.M;
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    if (p->out_dtype == FGE_BF16) hipLaunchKernelGGL((finish_kernel<bf16_t>), grid, block, 0, s, r);
+    else                          hipLaunchKernelGGL((finish_kernel<float>), grid, block, 0, s, r);
+    return hip_status(hipGetLastError());
+}
+
+int do_gemm_bias(const void *X, const void *W, const float *b, const fge_params *p, void *Y, hipStream_t s) {
+    int rc = check_common(p, FGE_ACT_NONE, FGE_NORM_NONE, true);
+    if (rc) return rc;
+    if (!X || !W || !Y) return FGE_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(b)) return FGE_ERR_ALIGN;
+    const Plan pl = make_plan(p, FGE_NORM_NONE);
+    return launch_tiles(tile_args(X, W, b, FGE_ACT_NONE, FGE_NORM_NONE, p, pl, Y), p, pl, s);
+}
+
+int do_act(const void *Y, int act, const fge_params *p, void *A, hipStream_t s) {
+    int rc = check_common(p, act, FGE_NORM_NONE, false);
+    if (rc) return rc;
+    if (!Y || !A) return FGE_ERR_NULL;
+    if (!aligned16(Y) || !aligned16(A)) return FGE_ERR_ALIGN;
+    const Plan pl = make_plan(p, FGE_NORM_NONE);
+    const RowArgs r = row_args(Y, A, act, FGE_NORM_NONE, p, pl);
+    const int cw = p->out_dtype == FGE_BF16 ? 8 : 4;
+    const int64_t chunks = (int64_t)r.batch * r.M * (r.N / cw);
+    int64_t blocks = (chunks + 255) / 256;
+    if (blocks > NUM_CU * 32) blocks = NUM_CU * 32;      // grid-stride beyond that
+    const dim3 grid((unsigned)blocks), block(256);
+    if (p->out_dtype == FGE_BF16) hipLaunchKernelGGL((act_kernel<bf16_t>), grid, block, 0, s, r);
+    else                          hipLaunchKernelGGL((act_kernel<float>), grid, block, 0, s, r);
+    return hip_status(hipGetLastError());
+}
+
+int do_rownorm(const void *A, int norm, const fge_params *p, void *out, hipStream_t s) {
+    int rc = check_common(p, FGE_ACT_NONE, norm, false);
+    if (rc) return rc;
+    if (!A || !out) return FGE_ERR_NULL;
+    if (!aligned16(A) || !aligned16(out)) return FGE_ERR_ALIGN;
+    if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
+    const Plan pl = make_plan(p, norm);
+    const RowArgs r = row_args(A, out, FGE_ACT_NONE, norm, p, pl);
+    if (norm == FGE_NORM_NONE) {
+        if (A == out) return FGE_OK;
+        return do_act(A, FGE_ACT_NONE, p, out, s);       // plain copy
+    }
+    return p->out_dtype == FGE_BF16 ? launch_rownorm<bf16_t>(r, s) : launch_rownorm<float>(r, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int fge_fused_tiles(const void *X, const void *W, const float *b, int act, int norm,
+                    const fge_params *p, void *out, void *stream) {
+    return do_fused_tiles(X, W, b, act, norm, p, out, (hipStream_t)stream, nullptr);
+}
+
+int fge_fused_finish(int act, int norm, const fge_params *p, void *out, void *stream) {
+    return do_fused_finish(act, norm, p, out, (hipStream_t)stream);
+}
+
+int fge_fused_needs_finish(int act, int norm, const fge_params *p) {
+    const int rc = check_common(p, act, norm, true);
+    if (rc) return -rc;
+    return make_plan(p, norm).needs_finish ? 1 : 0;
+}
+
+int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
+                        const fge_params *p, void *out, void *stream) {
+    Plan pl{};
+    int rc = do_fused_tiles(X, W, b, act, norm, p, out, (hipStream_t)stream, &pl);
+    if (rc || !pl.needs_finish) return rc;
+    return do_fused_finish(act, norm, p, out, (hipStream_t)stream);
+}
+
+int fge_gemm_bias(const void *X, const void *W, const float *b, const fge_params *p, void *Y, void *stream) {
+    return do_gemm_bias(X, W, b, p, Y, (hipStream_t)stream);
+}
+
+int fge_activation(const void *Y, int act, const fge_params *p, void *A, void *stream) {
+    return do_act(Y, act, p, A, (hipStream_t)stream);
+}
+
+int fge_row_op(const void *A, int norm, const fge_params *p, void *out, void *stream) {
+    return do_rownorm(A, norm, p, out, (hipStream_t)stream);
+}
+
+int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
+                          const fge_params *p, void *out, void *stream) {
+    int rc = check_common(p, act, norm, true);
+    if (rc) return rc;
+    if (!X || !W || !out) return FGE_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(out) || !aligned16(b)) return FGE_ERR_ALIGN;
+    if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
+    const Plan pl = make_plan(p, norm);
+    if (!p->workspace || p->workspace_bytes < pl.ws_buf * pl.n_bufs) return FGE_ERR_WORKSPACE;
+    void *Y = p->workspace;
+    void *A = pl.n_bufs == 2 ? static_cast<void *>(static_cast<char *>(p->workspace) + pl.ws_buf) : out;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = do_gemm_bias(X, W, b, p, Y, s))) return rc;
+    if ((rc = do_act(Y, act, p, A, s))) return rc;
+    return do_rownorm(A, norm, p, out, s);
+}
+
+size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p) {
+    if (check_common(p, act, norm, true)) return (size_t)-1;
+    const Plan pl = make_plan(p, norm);
+    return fused ? pl.ws_stats : pl.ws_buf * pl.n_bufs;
+}
+
+const char *fge_status_string(int status) {
+    switch (status) {
+    case FGE_OK:              return "ok";
+    case FGE_ERR_NULL:        return "a required pointer is NULL";
+    case FGE_ERR_BAD_ENUM:    return "activation, row-op or dtype code out of range";
+    case FGE_ERR_BAD_SHAPE:   return "non-positive extent or stride smaller than the extent";
+    case FGE_ERR_UNSUPPORTED: return "valid request outside the supported set";
+    case FGE_ERR_ALIGN:       return "pointer or stride not 16-byte aligned";
+    case FGE_ERR_WORKSPACE:   return "workspace missing or too small";
+    case FGE_ERR_HIP:         return "HIP launch failed";
+    default:                  return "unknown status";
+    }
+}
+
+int fge_last_hip_error(void) { return g_last_hip; }
+
+const char *fge_tile_name(int fused, int act, int norm, const fge_params *p) {
+    if (check_common(p, act, norm, true)) return nullptr;
+    return tile_info(make_plan(p, fused ? norm : FGE_NORM_NONE).tile).name;
+}
+
+}  // extern "C"

@@ -1,0 +1,143 @@
+// Device-side building blocks shared by every kernel of the library (gfx950 only):
+// storage-type conversion, the activations, and wavefront reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/fge.h"
+
+namespace fge {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct bf16_t { uint16_t bits; };   // storage only; arithmetic is always fp32
+
+// ---------------------------------------------------------------- storage conversion
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+// fp32 -> bf16, round to nearest even (the hardware conversion of gfx950).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));
+}
+
+template <typename T> struct Store;
+template <> struct Store<float> {
+    static constexpr int CW = 4;                       // elements per 16-byte chunk
+    __device__ static __forceinline__ void put(float *p, float v) { *p = v; }
+    __device__ static __forceinline__ float get(const float *p) { return *p; }
+    // one 16-byte chunk <-> CW floats
+    __device__ static __forceinline__ void unpack(const uint4 &u, float *v) {
+        v[0] = __builtin_bit_cast(float, u.x); v[1] = __builtin_bit_cast(float, u.y);
+        v[2] = __builtin_bit_cast(float, u.z); v[3] = __builtin_bit_cast(float, u.w);
+    }
+    __device__ static __forceinline__ uint4 pack(const float *v) {
+        uint4 u;
+        u.x = __builtin_bit_cast(uint32_t, v[0]); u.y = __builtin_bit_cast(uint32_t, v[1]);
+        u.z = __builtin_bit_cast(uint32_t, v[2]); u.w = __builtin_bit_cast(uint32_t, v[3]);
+        return u;
+    }
+};
+template <> struct Store<bf16_t> {
+    static constexpr int CW = 8;
+    __device__ static __forceinline__ void put(bf16_t *p, float v) { p->bits = f32_to_bf16(v); }
+    __device__ static __forceinline__ float get(const bf16_t *p) { return bf16_to_f32(p->bits); }
+    __device__ static __forceinline__ void unpack(const uint4 &u, float *v) {
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i]     = __builtin_bit_cast(float, w[i] << 16);
+            v[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ static __forceinline__ uint4 pack(const float *v) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+// ---------------------------------------------------------------- activations (fp32)
+// exp and reciprocal use the hardware transcendental units (about 1 ulp each); the forms
+// below avoid cancellation so the relative error stays near 1e-6 for every input.
+__device__ __forceinline__ float fast_exp(float x) { return __expf(x); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+template <int ACT> __device__ __forceinline__ float activate(float y, float lo, float hi) {
+    if constexpr (ACT == FGE_ACT_RELU) {
+        return fmaxf(y, 0.0f);
+    } else if constexpr (ACT == FGE_ACT_GELU_TANH) {
+        // 0.5 y (1 + tanh u) == y * sigmoid(2u),  u = sqrt(2/pi) (y + 0.044715 y^3)
+        const float u2 = 1.5957691216057308f * (y + 0.044715f * y * y * y);
+        return y * fast_rcp(1.0f + fast_exp(-u2));
+    } else if constexpr (ACT == FGE_ACT_GELU_ERF) {
+        // 0.5 y (1 + erf(y/sqrt2)) == 0.5 y erfc(-y/sqrt2): no cancellation for y << 0
+        return 0.5f * y * erfcf(-0.7071067811865476f * y);
+    } else if constexpr (ACT == FGE_ACT_SILU) {
+        return y * fast_rcp(1.0f + fast_exp(-y));
+    } else if constexpr (ACT == FGE_ACT_CLAMP) {
+        return fminf(fmaxf(y, lo), hi);
+    } else {
+        return y;
+    }
+}
+
+// Calls f.template operator()<ACT>() with the runtime activation code turned into a constant,
+// so the per-element loop inside f carries no branch.
+template <typename F> __device__ __forceinline__ void dispatch_act(int act, F &&f) {
+    switch (act) {
+    case FGE_ACT_RELU:      f.template operator()<FGE_ACT_RELU>(); break;
+    case FGE_ACT_GELU_TANH: f.template operator()<FGE_ACT_GELU_TANH>(); break;
+    case FGE_ACT_GELU_ERF:  f.template operator()<FGE_ACT_GELU_ERF>(); break;
+    case FGE_ACT_SILU:      f.template operator()<FGE_ACT_SILU>(); break;
+    case FGE_ACT_CLAMP:     f.template operator()<FGE_ACT_CLAMP>(); break;
+    default:                f.template operator()<FGE_ACT_NONE>(); break;
+    }
+}
+
+// Compile-time loop: f.template operator()<I>() for I in [I0, N).  Used where an unrolled
+// runtime loop would leave register arrays indexed by a variable.
+template <int I0, int N, typename F> __device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I0 < N) {
+        f.template operator()<I0>();
+        static_for<I0 + 1, N>(f);
+    }
+}
+
+// ---------------------------------------------------------------- wavefront reductions
+struct OpSum { __device__ static __forceinline__ float f(float a, float b) { return a + b; }
+               static constexpr float ident() { return 0.0f; } };
+struct OpMax { __device__ static __forceinline__ float f(float a, float b) { return fmaxf(a, b); }
+               static constexpr float ident() { return -__builtin_inff(); } };
+
+template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+        0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// All-reduce over the 32 lanes that share lane/32 (the lanes holding one accumulator row of a
+// 32x32 MFMA tile).  Steps: quad swaps (xor 1, xor 2), mirror within 8, mirror within 16 -
+// valid because after each step the value is uniform inside the smaller group - and a
+// swizzle exchanging lanes i and i^16.
+template <typename Op> __device__ __forceinline__ float allreduce32(float v) {
+    v = Op::f(v, dpp_mov<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = Op::f(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = Op::f(v, dpp_mov<0x141>(v));   // row_half_mirror
+    v = Op::f(v, dpp_mov<0x140>(v));   // row_mirror
+    v = Op::f(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(
+                     __builtin_bit_cast(int, v), 0x401F)));   // bit mode: and 0x1f, xor 0x10
+    return v;
+}
+
+// All-reduce over the whole 64-lane wavefront.
+template <typename Op> __device__ __forceinline__ float allreduce64(float v) {
+    v = allreduce32<Op>(v);
+    return Op::f(v, __shfl_xor(v, 32, 64));
+}
+
+}  // namespace fge

@@ -1,0 +1,97 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function
+the header declares, and rejects bad arguments with the documented status before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_23424_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = open(os.path.join(ROOT, "include", "fge.h")).read()
+
+
+def declared_functions():
+    body = re.sub(r"/\*.*?\*/", "", HEADER, flags=re.S)
+    return sorted(set(re.findall(r"\b(\w+)\s*\([^;{}]*\)\s*;", body)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert {"fused_gemm_epilogue", "unfused_gemm_epilogue", "fge_workspace_bytes", "fge_fused_tiles",
+            "fge_fused_finish", "fge_gemm_bias", "fge_activation", "fge_row_op",
+            "fge_status_string", "fge_last_hip_error", "fge_tile_name",
+            "fge_fused_needs_finish"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(B.FgeParams) == 128
+    assert B.FgeParams.ldx.offset == 16 and B.FgeParams.in_dtype.offset == 56
+    assert B.FgeParams.gamma.offset == 88 and B.FgeParams.workspace_bytes.offset == 120
+
+
+def _params(**kw):
+    p = B.FgeParams()
+    p.M, p.N, p.K, p.batch = 128, 256, 64, 1
+    p.ldx, p.ldw, p.ldo = 64, 64, 256
+    p.in_dtype = p.out_dtype = 0
+    p.alpha = p.post_scale = 1.0
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+FAKE = 0x10000          # 16-byte aligned non-null address; never dereferenced on these paths
+
+
+def _call(p, act=1, norm=1, X=FAKE, W=FAKE, out=FAKE, b=None):
+    return B.lib().fused_gemm_epilogue(X, W, b, act, norm, ctypes.byref(p), out, None)
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    assert B.lib().fused_gemm_epilogue(FAKE, FAKE, None, 1, 1, None, FAKE, None) == 1      # NULL params
+    assert _call(_params(), X=None) == 1
+    assert _call(_params(), out=None) == 1
+    assert _call(_params(), act=6) == 2 and _call(_params(), act=-1) == 2
+    assert _call(_params(), norm=5) == 2
+    assert _call(_params(in_dtype=2)) == 2
+    assert _call(_params(M=0)) == 3 and _call(_params(K=-8)) == 3 and _call(_params(batch=0)) == 3
+    assert _call(_params(ldo=128)) == 3                       # stride smaller than the row
+    assert _call(_params(ldx=32)) == 3
+    assert _call(_params(N=250, ldo=250)) == 5                # N*4 not a multiple of 16
+    assert _call(_params(K=62, ldx=64, ldw=64)) == 5
+    assert _call(_params(ldo=258)) == 5
+    assert _call(_params(), X=FAKE + 4) == 5                  # misaligned base pointer
+    assert _call(_params(N=16384, ldo=16384)) == 4            # row op over too wide a row
+    assert _call(_params(), norm=4) == 1                      # logsumexp without aux_out
+    # split rows need a workspace
+    p = _params(M=4096, N=1024, K=1024, ldx=1024, ldw=1024, ldo=1024)
+    need = B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p))
+    assert need == 4096 * 8 * 8
+    assert _call(p, act=2, norm=2) == 6
+    p.workspace, p.workspace_bytes = FAKE, need - 1
+    assert _call(p, act=2, norm=2) == 6
+    # unfused path: workspace for two intermediates
+    assert B.lib().fge_workspace_bytes(0, 2, 2, ctypes.byref(p)) == 2 * 4096 * 1024 * 4
+    assert B.lib().unfused_gemm_epilogue(FAKE, FAKE, None, 2, 2, ctypes.byref(p), FAKE, None) == 6
+    assert B.lib().fge_workspace_bytes(1, 9, 2, ctypes.byref(p)) == ctypes.c_size_t(-1).value
+
+
+def test_status_strings_and_tile_names():
+    L = B.lib()
+    seen = {L.fge_status_string(i) for i in range(8)}
+    assert len(seen) == 8 and all(seen)
+    assert L.fge_status_string(99) == b"unknown status"
+    assert L.fge_last_hip_error() == 0
+    assert B.fge_tile_name(True, 1, 1, _params(N=64, ldo=64)) == "64x64_w2x2"
+    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512)) == "64x512_w1x4"
+    big = _params(M=8192, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, in_dtype=1, out_dtype=1)
+    assert B.fge_tile_name(True, 4, 3, big) == "256x256_w2x2"
+    assert B.fge_fused_needs_finish(4, 3, big) is True
+    assert B.fge_fused_needs_finish(1, 1, _params(N=64, ldo=64)) is False
+    with pytest.raises(B.FgeError):
+        B.fge_fused_needs_finish(1, 1, _params(M=0))

@@ -1,0 +1,201 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 oracle on the same seeded
+inputs.  Tolerances: max rel err (row-floored) 1e-4 for fp32, 2e-2 for bf16-in / fp32-accumulate;
+integer-valued problems must match bit for bit."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_23424_amd import binding as B
+from paper_2512_23424_amd import inputs as I
+from tests import _harness as H
+
+pytestmark = pytest.mark.gpu
+WL = I.WORKLOADS
+
+
+def _parity(w, path, rows=None, label=""):
+    t = I.generate(w)
+    got, gaux = H.run_gpu(w, t, path)
+    if rows is not None:                           # oracle on sampled complete rows
+        t = dict(t, X=np.ascontiguousarray(t["X"][rows]))
+        got = got[rows]
+        gaux = None if gaux is None else gaux[rows]
+    ref, raux = H.oracle_chain(w, t)
+    return H.check(w, got, gaux, ref, raux, label or path)
+
+
+# ---- layout / indexing: exact integers must match bit for bit whatever the summation order
+@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+@pytest.mark.parametrize("shape", [(64, 64, 64), (96, 128, 160), (200, 72, 328), (300, 1024, 520)])
+def test_exact_integer_gemm(dt, shape):
+    M, K, N = shape
+    w = I.Workload(name="int", M=M, K=K, N=N, in_dtype=dt, out_dtype=I.F32,
+                   dist={"X": ("int", -2, 2), "W": ("int", -2, 2), "b": ("int", -3, 3)})
+    t = I.generate(w)
+    for path in ("fused", "unfused"):
+        got, _ = H.run_gpu(w, t, path)
+        ref, _ = H.oracle_chain(w, t)
+        bad = np.argwhere(got != ref)
+        assert bad.size == 0, f"{path} {shape}: {len(bad)} mismatches, first at {bad[:5].tolist()}"
+
+
+# ---- the five workloads at sizes the oracle finishes in seconds (several tiles, ragged tails)
+SMALL = {
+    "cfg1": dict(),
+    "cfg2": dict(M=300, K=1024, N=1024),
+    "cfg3": dict(M=520, K=1024, N=4096),
+    "cfg4": dict(M=136, K=512, N=2048, batch=3),
+    "cfg5": dict(M=1000, K=64, N=512),
+}
+
+
+@pytest.mark.parametrize("path", ["fused", "unfused"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_workload_small(name, path):
+    _parity(I.scaled(WL[name], **SMALL[name]), path)
+
+
+# ---- every activation x row op, both storage types, ragged M / N / K
+ACTS = [I.ACT_NONE, I.ACT_RELU, I.ACT_GELU_TANH, I.ACT_GELU_ERF, I.ACT_SILU, I.ACT_CLAMP]
+NORMS = [I.NORM_NONE, I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP]
+
+
+@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+@pytest.mark.parametrize("norm", NORMS)
+@pytest.mark.parametrize("N", [40, 328, 1032])          # whole-row 64, whole-row 512, split
+def test_all_chains(dt, norm, N):
+    for act in ACTS:
+        w = I.Workload(name=f"a{act}n{norm}", M=77, K=136, N=N, in_dtype=dt, out_dtype=dt, act=act,
+                       norm=norm, alpha=0.5, post_scale=1.5, clamp_lo=-1.0, clamp_hi=2.0, eps=1e-5,
+                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1),
+                             "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1),
+                             "beta": ("normal", 0.0, 0.1)})
+        for path in ("fused", "unfused"):
+            _parity(w, path, label=f"{path} act{act} norm{norm}")
+
+
+def test_mixed_dtypes_and_no_optional_vectors():
+    for (i, o) in [(I.F32, I.BF16), (I.BF16, I.F32)]:
+        w = I.Workload(name="mix", M=130, K=256, N=520, in_dtype=i, out_dtype=o, act=I.ACT_SILU,
+                       norm=I.NORM_LAYERNORM, eps=1e-5,
+                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 1.0 / 16)})
+        for path in ("fused", "unfused"):
+            t = I.generate(w)
+            got, _ = H.run_gpu(w, t, path)
+            ref, _ = H.oracle_chain(w, t)
+            err = H.C.max_rel_err(got, ref)
+            assert err <= 2e-2 if I.BF16 in (i, o) else 1e-4, err
+
+
+def test_edge_shapes():
+    for (M, K, N) in [(1, 8, 8), (1, 64, 512), (63, 8, 72), (65, 40, 64), (257, 264, 264)]:
+        w = I.scaled(WL["cfg2"], M=M, K=K, N=N)
+        _parity(w, "fused", label=f"edge {M}x{K}x{N}")
+        _parity(w, "unfused", label=f"edge-unfused {M}x{K}x{N}")
+
+
+def test_strided_batch_not_flattened():
+    """Batch with padding between problems and padded row strides goes through grid.z."""
+    w = I.scaled(WL["cfg4"], M=70, K=64, N=264, batch=3)
+    t = I.generate(w)
+    Xd = torch.zeros(3, 80, 72, dtype=torch.bfloat16, device="cuda")
+    Xd[:, :70, :64] = H.to_device(t["X"]).view(3, 70, 64)
+    outd = torch.full((3, 80, 272), float("nan"), dtype=torch.bfloat16, device="cuda")
+    X, out = Xd[:, :70, :64], outd[:, :70, :264]
+    Wd, bd = H.to_device(t["W"]), H.to_device(t["b"])
+    ref, _ = H.oracle_chain(w, t)
+    for path, fn in (("fused", B.fused_gemm_epilogue), ("unfused", B.unfused_gemm_epilogue)):
+        outd.fill_(float("nan"))
+        p = B.make_params(X, Wd, out, alpha=w.alpha)
+        n = B.fge_workspace_bytes(path == "fused", w.act, w.norm, p)
+        ws = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), n
+        fn(X, Wd, bd, w.act, w.norm, p, out)
+        torch.cuda.synchronize()
+        got = H.to_host_f64(out).reshape(-1, 264)
+        H.check(w, got, None, ref, None, f"strided {path}")
+        assert torch.isnan(outd[:, 70:, :]).all() and torch.isnan(outd[:, :, 264:]).all()   # padding untouched
+
+
+def test_bf16_store_is_round_to_nearest_even():
+    """K=8 identity-like product reproduces chosen fp32 values; the bf16 store must round them
+    like the host RNE routine, ties included."""
+    vals = np.array([0x3F808000, 0x3F818000, 0x3F808001, 0x3F807FFF, 0xBF818000, 0x40490FDB,
+                     0x3EAAAAAB, 0x00000000], dtype=np.uint32).view(np.float32)
+    X = np.zeros((8, 8), np.float32); np.fill_diagonal(X, 1.0)
+    W = np.zeros((8, 8), np.float32); W[:, :] = np.diag(vals)
+    Xd, Wd = torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda()
+    out = torch.zeros(8, 8, dtype=torch.bfloat16, device="cuda")
+    p = B.make_params(Xd, Wd, out)
+    B.fused_gemm_epilogue(Xd, Wd, None, "none", "none", p, out)
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(np.diag(got), I.f32_to_bf16_bits(vals))
+
+
+def test_run_to_run_bitwise_determinism():
+    for name in ("cfg2", "cfg4"):
+        w = I.scaled(WL[name], **SMALL[name])
+        t = I.generate(w)
+        d = {k: H.to_device(v) for k, v in t.items()}
+        first, _ = H.run_gpu(w, t, "fused", dev=d)
+        for _ in range(5):
+            again, _ = H.run_gpu(w, t, "fused", dev=d)
+            assert np.array_equal(first, again)
+
+
+def test_stage_entry_points_compose_to_the_paths():
+    w = I.scaled(WL["cfg2"], M=300, K=256, N=1024)
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    full, _ = H.run_gpu(w, t, "fused", dev=d)
+    out = torch.full((w.M, w.N), float("nan"), device="cuda")
+    p = B.make_params(d["X"], d["W"], out, eps=w.eps, gamma=d["gamma"], beta=d["beta"])
+    ws = torch.empty(B.fge_workspace_bytes(True, w.act, w.norm, p), dtype=torch.uint8, device="cuda")
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+    assert B.fge_fused_needs_finish(w.act, w.norm, p)
+    B.fge_fused_tiles(d["X"], d["W"], d["b"], w.act, w.norm, p, out)
+    B.fge_fused_finish(w.act, w.norm, p, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.to_host_f64(out), full)
+    # unfused stages
+    Y = torch.empty_like(out); A = torch.empty_like(out); o2 = torch.empty_like(out)
+    B.fge_gemm_bias(d["X"], d["W"], d["b"], p, Y)
+    B.fge_activation(Y, w.act, p, A)
+    B.fge_row_op(A, w.norm, p, o2)
+    torch.cuda.synchronize()
+    unf, _ = H.run_gpu(w, t, "unfused", dev=d)
+    assert np.array_equal(H.to_host_f64(o2), unf)
+
+
+# ---- the full-size workloads, in the launch configuration the benchmark times; the oracle
+#      evaluates sampled complete rows (rows are independent, so those rows are checked exactly)
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
+def test_workload_full_size_sampled_rows(name):
+    w = WL[name]
+    rng = np.random.default_rng(7)
+    n = {"cfg2": 96, "cfg3": 24, "cfg4": 96, "cfg5": 512}[name]
+    rows = np.unique(np.concatenate([[0, w.rows - 1], rng.integers(0, w.rows, n)]))
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    sub = dict(t, X=np.ascontiguousarray(t["X"][rows]))
+    ref, raux = H.oracle_chain(w, sub)
+    for path in ("fused", "unfused"):
+        got, gaux = H.run_gpu(w, t, path, dev=d)
+        assert np.isfinite(got).all()
+        H.check(w, got[rows], None if gaux is None else gaux[rows], ref, raux, f"full {path}")
+        # properties that hold for every row at any size
+        if w.norm == I.NORM_SOFTMAX:
+            s = got.sum(axis=1)
+            assert np.abs(s - 1.0).max() < (4e-3 if w.out_dtype == I.BF16 else 1e-5)
+            assert (got >= 0).all() and (got <= 1).all()
+        if w.norm == I.NORM_LOGSUMEXP:
+            assert got.min() >= -5.0 and got.max() <= 5.0
+            assert (gaux >= got.max(axis=1) - 1e-5).all()
+            assert (gaux <= got.max(axis=1) + math.log(w.N) + 1e-5).all()
+        if w.norm == I.NORM_RMSNORM:
+            g = t["gamma"].astype(np.float64)
+            ms = ((got / g) ** 2).mean(axis=1)
+            assert np.abs(ms - 1.0).max() < 2e-2
