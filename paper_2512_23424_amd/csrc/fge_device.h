@@ -15,6 +15,9 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct bf16_t { uint16_t bits; };   // storage only; arithmetic is always fp32
 
+__device__ __forceinline__ float as_f32(uint32_t v) { return __builtin_bit_cast(float, v); }
+__device__ __forceinline__ uint32_t as_u32(float v) { return __builtin_bit_cast(uint32_t, v); }
+
 // ---------------------------------------------------------------- storage conversion
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
     return __builtin_bit_cast(float, (uint32_t)b << 16);
@@ -31,13 +34,11 @@ template <> struct Store<float> {
     __device__ static __forceinline__ float get(const float *p) { return *p; }
     // one 16-byte chunk <-> CW floats
     __device__ static __forceinline__ void unpack(const uint4 &u, float *v) {
-        v[0] = __builtin_bit_cast(float, u.x); v[1] = __builtin_bit_cast(float, u.y);
-        v[2] = __builtin_bit_cast(float, u.z); v[3] = __builtin_bit_cast(float, u.w);
+        v[0] = as_f32(u.x); v[1] = as_f32(u.y); v[2] = as_f32(u.z); v[3] = as_f32(u.w);
     }
     __device__ static __forceinline__ uint4 pack(const float *v) {
         uint4 u;
-        u.x = __builtin_bit_cast(uint32_t, v[0]); u.y = __builtin_bit_cast(uint32_t, v[1]);
-        u.z = __builtin_bit_cast(uint32_t, v[2]); u.w = __builtin_bit_cast(uint32_t, v[3]);
+        u.x = as_u32(v[0]); u.y = as_u32(v[1]); u.z = as_u32(v[2]); u.w = as_u32(v[3]);
         return u;
     }
 };
@@ -49,8 +50,8 @@ template <> struct Store<bf16_t> {
         const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            v[2 * i]     = __builtin_bit_cast(float, w[i] << 16);
-            v[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
+            v[2 * i]     = as_f32(w[i] << 16);
+            v[2 * i + 1] = as_f32(w[i] & 0xFFFF0000u);
         }
     }
     __device__ static __forceinline__ uint4 pack(const float *v) {

@@ -60,11 +60,13 @@ template <> struct Mma<bf16_t> {
 template <> struct Mma<float> {
     // A 16-byte fragment holds 4 consecutive k of one row; lanes 0-31 and 32-63 hold different
     // chunks.  The k pairing is the same for both operands, so the sum over k is complete.
+    // (as_f32 takes the element by value: a bit cast applied directly to a vector-element
+    // lvalue reads element 0 whichever element is named.)
     __device__ static __forceinline__ void run(const u32x4 &a, const u32x4 &b, floatx16 &c) {
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.x), __builtin_bit_cast(float, b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.y), __builtin_bit_cast(float, b.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.z), __builtin_bit_cast(float, b.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.w), __builtin_bit_cast(float, b.w), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(as_f32(a.x), as_f32(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(as_f32(a.y), as_f32(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(as_f32(a.z), as_f32(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(as_f32(a.w), as_f32(b.w), c, 0, 0, 0);
     }
 };
 
