@@ -13,7 +13,7 @@ inline const TileInfo &tile_info(int id) {
         {64, 64, 256, "64x64_w2x2"},
         {64, 512, 256, "64x512_w1x4"},
         {128, 128, 256, "128x128_w2x2"},
-        {256, 256, 256, "256x256_w2x2"},
+        {256, 256, 512, "256x256_w2x4"},
     };
     return t[id];
 }
@@ -37,7 +37,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     case TILE_64x64:   FGE_LAUNCH(64, 64, 2, 2); break;
     case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4); break;
     case TILE_128x128: FGE_LAUNCH(128, 128, 2, 2); break;
-    case TILE_256x256: FGE_LAUNCH(256, 256, 2, 2); break;
+    case TILE_256x256: FGE_LAUNCH(256, 256, 2, 4); break;
     default: return hipErrorInvalidValue;
     }
 #undef FGE_LAUNCH

@@ -11,8 +11,12 @@
 // wave's column blocks, then 5 cross-lane steps, then one LDS exchange between waves.
 //
 // LDS panel layout (both operands): row-major, 128 bytes of K per row (64 bf16 / 32 fp32),
-// the eight 16-byte chunks of a row stored at chunk ^ (row & 7) so that the 16-byte fragment
-// reads of 8 neighbouring rows touch all 32 banks.
+// the eight 16-byte chunks of a row stored at chunk ^ ((row >> 1) & 7): the 16-byte fragment
+// reads of 16 neighbouring rows then touch each of the 64 LDS banks exactly once (measured:
+// zero bank-conflict cycles; the 8-row variant chunk ^ (row & 7) conflicts two-way).
+// Full K tiles are copied global -> LDS directly (no staging registers): a wave's load
+// instruction fills 1024 contiguous LDS bytes, lane l at base + 16*l, so each lane fetches
+// the global chunk that belongs at its LDS position.
 #pragma once
 #include "fge_device.h"
 
@@ -50,6 +54,9 @@ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, i
     tn = idx / gm;
 }
 
+// XOR pattern of the panel swizzle for a panel row.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
 template <typename InT> struct Mma;
 template <> struct Mma<bf16_t> {
     __device__ static __forceinline__ void run(const u32x4 &a, const u32x4 &b, floatx16 &c) {
@@ -82,7 +89,7 @@ void tile_kernel(const TileArgs a) {
     constexpr int A_LD = BM * 8 / NT, B_LD = BN * 8 / NT;
     constexpr int RSTEP = NT / 8;                    // rows between a thread's successive chunks
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile");
-    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 8 == 0, "load plan");
+    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 16 == 0, "load plan");
     constexpr int STAGE = (BM + BN) * ROWB;
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
@@ -101,50 +108,63 @@ void tile_kernel(const TileArgs a) {
     const InT *W = reinterpret_cast<const InT *>(a.W);
     OutT *out = reinterpret_cast<OutT *>(a.out) + (int64_t)z * a.bso;
 
-    // ---------------- global -> register -> LDS staging plan
-    // Thread t stages chunk (t & 7) of rows (t >> 3) + i*RSTEP.  Rows past the end of X / W are
-    // clamped to the last valid row: they only feed outputs that are never stored or counted.
-    // Only a partial last K tile needs zero fill.
+    // ---------------- global -> LDS staging plan
+    // Thread t stages rows (t >> 3) + i*RSTEP.  Rows past the end of X / W are clamped to the
+    // last valid row: they only feed outputs that are never stored or counted.  Only a partial
+    // last K tile needs zero fill; it goes through registers.
     const int ld_row = tid >> 3, ld_c = tid & 7;
-    const int ld_soff = ld_row * ROWB + ((ld_c ^ (ld_row & 7)) << 4);
+    // The thread at (row ld_row, physical chunk ld_c) of the panel fetches global chunk
+    // ld_c ^ swizzle(row): the LDS image of a wave's 64 chunks is then 1024 contiguous bytes,
+    // which is what a direct global->LDS load writes (lane l lands at base + 16*l).
+    const int ld_gc = ld_c ^ swz(ld_row);          // global chunk of this thread
+    const int ld_soff = ld_row * ROWB + (ld_c << 4);
     const InT *gA[A_LD];
     const InT *gB[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-        gA[i] = X + (int64_t)min(m0 + ld_row + i * RSTEP, a.M - 1) * a.ldx + ld_c * CW;
+        gA[i] = X + (int64_t)min(m0 + ld_row + i * RSTEP, a.M - 1) * a.ldx + ld_gc * CW;
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
-        gB[i] = W + (int64_t)min(n0 + ld_row + i * RSTEP, a.N - 1) * a.ldw + ld_c * CW;
-    u32x4 rA[A_LD], rB[B_LD];
+        gB[i] = W + (int64_t)min(n0 + ld_row + i * RSTEP, a.N - 1) * a.ldw + ld_gc * CW;
 
-    auto load_global = [&]<bool TAIL>(int k0) __attribute__((always_inline)) {
-        const bool kok = !TAIL || k0 + ld_c * CW < a.K;   // K is a multiple of CW: chunks are whole
+    // full tile: asynchronous global -> LDS, no registers involved; completion is tracked by
+    // the vector-memory counter (wait for it, then barrier, before anyone reads the tile)
+    typedef __attribute__((address_space(1))) const void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    const int wave_soff = (tid >> 6) * 8 * ROWB;      // first byte of this wave's 8 rows
+    auto dma_tile = [&](int buf, int k0) __attribute__((always_inline)) {
+        unsigned char *sA = smem + buf * STAGE + wave_soff, *sB = sA + BM * ROWB;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(gA[i] + k0), (lptr_t)(sA + i * RSTEP * ROWB), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(gB[i] + k0), (lptr_t)(sB + i * RSTEP * ROWB), 16, 0, 0);
+    };
+    // partial last tile: through registers, zero filled past K
+    auto stage_tail = [&](int buf, int k0) __attribute__((always_inline)) {
+        const bool kok = k0 + ld_gc * CW < a.K;       // K is a multiple of CW: chunks are whole
+        unsigned char *sA = smem + buf * STAGE + ld_soff, *sB = sA + BM * ROWB;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
-            rA[i] = u32x4{0u, 0u, 0u, 0u};
-            if (kok) rA[i] = *reinterpret_cast<const u32x4 *>(gA[i] + k0);
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (kok) v = *reinterpret_cast<const u32x4 *>(gA[i] + k0);
+            *reinterpret_cast<u32x4 *>(sA + i * RSTEP * ROWB) = v;
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
-            rB[i] = u32x4{0u, 0u, 0u, 0u};
-            if (kok) rB[i] = *reinterpret_cast<const u32x4 *>(gB[i] + k0);
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (kok) v = *reinterpret_cast<const u32x4 *>(gB[i] + k0);
+            *reinterpret_cast<u32x4 *>(sB + i * RSTEP * ROWB) = v;
         }
     };
-    auto store_lds = [&](int buf) __attribute__((always_inline)) {
-        unsigned char *sA = smem + buf * STAGE, *sB = sA + BM * ROWB;
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i)
-            *reinterpret_cast<u32x4 *>(sA + ld_soff + i * RSTEP * ROWB) = rA[i];
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i)
-            *reinterpret_cast<u32x4 *>(sB + ld_soff + i * RSTEP * ROWB) = rB[i];
-    };
+    auto wait_dma = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     // ---------------- fragment read plan
     const int fa_row = wave_m * WTM + l32, fb_row = wave_n * WTN + l32;
     int fsw[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) fsw[t] = ((2 * t + h) ^ (l32 & 7)) << 4;
+    for (int t = 0; t < 4; ++t) fsw[t] = ((2 * t + h) ^ swz(l32)) << 4;
 
     floatx16 acc[MB][NB];
 #pragma unroll
@@ -155,37 +175,79 @@ void tile_kernel(const TileArgs a) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     // ---------------- mainloop
-    const int KT = (a.K + BK - 1) / BK;
-    const bool ragged_k = (a.K % BK) != 0;            // then the last tile is partial
-    if (KT == 1 && ragged_k) load_global.template operator()<true>(0);
-    else                     load_global.template operator()<false>(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) {
-            if (kt + 2 == KT && ragged_k) load_global.template operator()<true>((kt + 1) * BK);
-            else                          load_global.template operator()<false>((kt + 1) * BK);
-        }
+    // Per staged tile: 4 k-steps of NM MFMAs.  Fragments of the next k-step are read from LDS
+    // behind the first MFMAs of the current one (two register sets).  The single barrier of an
+    // iteration sits between k-steps 2 and 3, and k-step 3 already prefetches the next tile's
+    // first fragments, so no LDS or barrier latency is exposed.  sched_barrier pins this order:
+    // left alone, the compiler sinks every fragment read next to its first use.
+    constexpr int NM = MB * NB, NR = MB + NB;
+    u32x4 fr[2][NR];                                  // [0,MB): A fragments, [MB,NR): B fragments
+    auto read_frag = [&](int buf, int t, int q) __attribute__((always_inline)) {
         const unsigned char *sA = smem + buf * STAGE + fa_row * ROWB;
         const unsigned char *sB = smem + buf * STAGE + BM * ROWB + fb_row * ROWB;
+        fr[t & 1][q] = q < MB
+            ? *reinterpret_cast<const u32x4 *>(sA + q * 32 * ROWB + fsw[t & 3])
+            : *reinterpret_cast<const u32x4 *>(sB + (q - MB) * 32 * ROWB + fsw[t & 3]);
+    };
+    // prefetch order = order of first use: A0, B0..B(NB-1), A1..A(MB-1)
+    auto slot = [&](int s) __attribute__((always_inline)) { return s == 0 ? 0 : (s <= NB ? MB + s - 1 : s - NB); };
+    constexpr int RSPAN = NR < NM ? NR : NM;          // reads ride behind the first RSPAN MFMAs
+    // one k-step: MFMAs of step t on fragment set t&1; behind MFMA m: reads of (rbuf, t+1)
+    auto kstep = [&](int t, bool do_read, int rbuf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            u32x4 fa[MB], fb[NB];
+        for (int m = 0; m < NM; ++m) {
+            Mma<InT>::run(fr[t & 1][m / NB], fr[t & 1][MB + m % NB], acc[m / NB][m % NB]);
+            if (do_read) {
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
-                fa[i] = *reinterpret_cast<const u32x4 *>(sA + i * 32 * ROWB + fsw[t]);
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-                fb[j] = *reinterpret_cast<const u32x4 *>(sB + j * 32 * ROWB + fsw[t]);
-#pragma unroll
-            for (int i = 0; i < MB; ++i)
-#pragma unroll
-                for (int j = 0; j < NB; ++j) Mma<InT>::run(fa[i], fb[j], acc[i][j]);
+                for (int s = (m * NR) / RSPAN; s < ((m + 1) * NR) / RSPAN && s < NR; ++s) read_frag(rbuf, t + 1, slot(s));
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (kt + 1 < KT) store_lds(buf ^ 1);
-        __syncthreads();
+    };
+    auto read_t0 = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < NR; ++s) read_frag(buf, 0, slot(s));
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto compute_last = [&](int buf) __attribute__((always_inline)) {   // fr[0] holds k-step 0
+        kstep(0, true, buf);
+        kstep(1, true, buf);
+        kstep(2, true, buf);
+        kstep(3, false, 0);
+    };
+    const int KF = a.K / BK;                          // full K tiles
+    const bool ragged_k = (a.K % BK) != 0;            // plus one partial tile
+    // Tile kt lives in buffer kt & 1.  Its DMA is issued right after the barrier that ends the
+    // reads of tile kt-2 and is awaited just before the barrier in the middle of tile kt-1, a
+    // full tile of MFMAs later.
+    if (KF > 0) { dma_tile(0, 0); wait_dma(); }
+    else        stage_tail(0, 0);
+    __syncthreads();
+    if (KF > 1) dma_tile(1, BK);
+    __builtin_amdgcn_sched_barrier(0);
+    read_t0(0);
+    int kt = 0;
+    for (; kt + 1 < KF; ++kt) {                       // tile kt+1 is a full one, already in flight
+        const int buf = kt & 1;
+        kstep(0, true, buf);
+        kstep(1, true, buf);
+        kstep(2, true, buf);
+        wait_dma();                                   // tile kt+1 has landed in buf^1
+        __syncthreads();                              // ... for every wave; reads of buf are over
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 2 < KF) dma_tile(buf, (kt + 2) * BK);
+        __builtin_amdgcn_sched_barrier(0);
+        kstep(3, true, buf ^ 1);                      // t+1 == 4 -> fragment set 0, k-step 0
     }
+    if (KF > 0 && ragged_k) {                         // last full tile, then the partial tile
+        compute_last(kt & 1);
+        stage_tail((kt & 1) ^ 1, KF * BK);
+        __syncthreads();
+        ++kt;
+        read_t0(kt & 1);
+    }
+    compute_last(kt & 1);
+    if constexpr (WAVES_M * WAVES_N > 1) __syncthreads();
 
     // ---------------- epilogue: scale + bias + activation in registers
     // accumulator element (i, j, r): row = wave_m*WTM + i*32 + (r/4)*8 + h*4 + r%4,
@@ -209,16 +271,36 @@ void tile_kernel(const TileArgs a) {
         });
     };
     auto row_of = [&](int i, int r) __attribute__((always_inline)) { return wrow0 + i * 32 + (r >> 2) * 8 + (r & 3); };
+    // Store of one 32-row accumulator block through a wave-private LDS patch, so that global
+    // stores are 16 bytes per lane and cover whole rows segments: the block is written as fp32
+    // [32][WTN + 8] (the +8 keeps lanes 0-31 and 32-63, four rows apart, on different banks),
+    // read back row-wise, converted and stored.  The patch lives in the panel memory, which
+    // is free once the mainloop's last fragment reads are behind the barrier above.
+    constexpr int SSTR = WTN + 8;                     // floats per patch row
+    constexpr int VEC = 16 / (int)sizeof(OutT);       // elements per 16-byte store
+    constexpr int LPR = WTN / VEC, RPP = 64 / LPR;    // lanes per row, rows per pass
+    static_assert(WAVES_M * WAVES_N * 32 * SSTR * 4 <= 2 * STAGE, "store patch fits the panels");
+    float *patch = reinterpret_cast<float *>(smem) + wave * 32 * SSTR;
     auto store_block = [&]<int i>() __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int grow = m0 + row_of(i, r);
-            if (grow < a.M) {
-                OutT *o = out + (int64_t)grow * a.ldo + wcol0;
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    if (cok[j]) Store<OutT>::put(o + j * 32, acc[i][j][r]);
+            for (int r = 0; r < 16; ++r)
+                patch[((r >> 2) * 8 + h * 4 + (r & 3)) * SSTR + j * 32 + l32] = acc[i][j][r];
+        const int prow = lane / LPR, pcol = (lane % LPR) * VEC;
+        const int gcol = n0 + wave_n * WTN + pcol;
+#pragma unroll
+        for (int p = 0; p < 32 / RPP; ++p) {
+            const int row = p * RPP + prow;
+            const int grow = m0 + wave_m * WTM + i * 32 + row;
+            float v[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; e += 4) {
+                const floatx4 f = *reinterpret_cast<const floatx4 *>(patch + row * SSTR + pcol + e);
+                v[e] = f[0]; v[e + 1] = f[1]; v[e + 2] = f[2]; v[e + 3] = f[3];
             }
+            if (grow < a.M && gcol < a.N)             // N is a multiple of VEC: whole vector or none
+                *reinterpret_cast<uint4 *>(out + (int64_t)grow * a.ldo + gcol) = Store<OutT>::pack(v);
         }
     };
 
