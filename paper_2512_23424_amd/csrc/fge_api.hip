@@ -64,7 +64,12 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
     return FGE_OK;
 }
 
+constexpr int PANEL_MIN_ROWS = 4096;   // below this the persistent kernel cannot fill the chip
+
 int pick_tile(const Problem &pr, int in_dtype, int norm) {
+    // fp32, narrow K, row fits one tile, many rows: bound by the output stream
+    if (in_dtype == FGE_F32 && pr.K <= 64 && pr.N <= 512 && pr.batch == 1 && pr.M >= PANEL_MIN_ROWS)
+        return TILE_PANEL;
     // A tile spanning the whole row finishes the row operation without a second pass.
     if (norm != FGE_NORM_NONE) {
         if (pr.N <= 64) return TILE_64x64;
@@ -125,6 +130,10 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
 }
 
 int launch_tiles(const TileArgs &a, const fge_params *p, const Plan &pl, hipStream_t s) {
+    if (pl.tile == TILE_PANEL) {
+        const dim3 pgrid((unsigned)(pl.tiles_m < NUM_CU ? pl.tiles_m : NUM_CU));
+        return hip_status(launch_panel_f32(p->out_dtype, pgrid, s, a));
+    }
     const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n), 1, (unsigned)pl.pr.batch);
     const hipError_t e = p->in_dtype == FGE_BF16 ? launch_tile_bf16(pl.tile, p->out_dtype, grid, s, a)
                                                  : launch_tile_f32(pl.tile, p->out_dtype, grid, s, a);

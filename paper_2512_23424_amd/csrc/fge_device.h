@@ -77,8 +77,19 @@ template <int ACT> __device__ __forceinline__ float activate(float y, float lo, 
         const float u2 = 1.5957691216057308f * (y + 0.044715f * y * y * y);
         return y * fast_rcp(1.0f + fast_exp(-u2));
     } else if constexpr (ACT == FGE_ACT_GELU_ERF) {
-        // 0.5 y (1 + erf(y/sqrt2)) == 0.5 y erfc(-y/sqrt2): no cancellation for y << 0
-        return 0.5f * y * erfcf(-0.7071067811865476f * y);
+        // 0.5 y (1 + erf(y/sqrt2)) = y * Phi(y).  erfc(|x|) by the rational approximation 7.1.26
+        // of Abramowitz & Stegun (|error| <= 1.5e-7 on erf):  erfc(|x|) = poly(t) exp(-x^2),
+        // t = 1/(1 + p|x|).  Phi(y) = 0.5 erfc(|x|) for y < 0 and 1 - 0.5 erfc(|x|) otherwise,
+        // x = y/sqrt2, so the negative tail is formed without cancellation.
+        const float x = 0.7071067811865476f * fabsf(y);
+        const float t = fast_rcp(1.0f + 0.3275911f * x);
+        float q = 1.061405429f;
+        q = q * t - 1.453152027f;
+        q = q * t + 1.421413741f;
+        q = q * t - 0.284496736f;
+        q = q * t + 0.254829592f;
+        const float half_erfc = 0.5f * q * t * fast_exp(-x * x);
+        return y * (y < 0.0f ? half_erfc : 1.0f - half_erfc);
     } else if constexpr (ACT == FGE_ACT_SILU) {
         return y * fast_rcp(1.0f + fast_exp(-y));
     } else if constexpr (ACT == FGE_ACT_CLAMP) {

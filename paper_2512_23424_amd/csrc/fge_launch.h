@@ -4,7 +4,7 @@
 
 namespace fge {
 
-enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_COUNT = 4 };
+enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_COUNT = 5 };
 
 struct TileInfo { int bm, bn, threads; const char *name; };
 
@@ -14,6 +14,7 @@ inline const TileInfo &tile_info(int id) {
         {64, 512, 256, "64x512_w1x4"},
         {128, 128, 256, "128x128_w2x2"},
         {256, 256, 512, "256x256_w2x4"},
+        {64, 512, 512, "panel64x512_w1x8_splitbf16"},   // persistent narrow-K kernel, fp32 operands
     };
     return t[id];
 }
@@ -21,6 +22,8 @@ inline const TileInfo &tile_info(int id) {
 // Defined in fge_tiles_f32.hip / fge_tiles_bf16.hip (split so they compile in parallel).
 hipError_t launch_tile_f32(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_tile_bf16(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
+// Defined in fge_panel_f32.hip: the persistent narrow-K kernel (grid = number of workgroups).
+hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 
 template <typename InT>
 inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {

@@ -18,22 +18,9 @@
 // instruction fills 1024 contiguous LDS bytes, lane l at base + 16*l, so each lane fetches
 // the global chunk that belongs at its LDS position.
 #pragma once
-#include "fge_device.h"
+#include "fge_epilogue.h"
 
 namespace fge {
-
-struct TileArgs {
-    const void *X, *W;
-    const float *b, *gamma, *beta;
-    void *out;
-    float *aux;
-    float2 *ws;                 // [batch*M][tiles_n] per-tile row statistics (split rows only)
-    int M, N, K;
-    int64_t ldx, ldw, ldo, bsx, bso;
-    float alpha, post, lo, hi, eps;
-    int act, norm;
-    int tiles_m, tiles_n, group_m;
-};
 
 // Logical tile index for a hardware workgroup id.  Workgroups are handed to the 8 XCDs round
 // robin, so ids congruent mod 8 share an L2; give each XCD one contiguous range of logical
@@ -249,217 +236,15 @@ void tile_kernel(const TileArgs a) {
     compute_last(kt & 1);
     if constexpr (WAVES_M * WAVES_N > 1) __syncthreads();
 
-    // ---------------- epilogue: scale + bias + activation in registers
-    // accumulator element (i, j, r): row = wave_m*WTM + i*32 + (r/4)*8 + h*4 + r%4,
-    //                                col = wave_n*WTN + j*32 + l32
-    const int wrow0 = wave_m * WTM + h * 4;
-    const int wcol0 = n0 + wave_n * WTN + l32;
-    bool cok[NB];
-    float bias[NB];
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        cok[j] = wcol0 + j * 32 < a.N;
-        bias[j] = (a.b != nullptr && cok[j]) ? a.b[wcol0 + j * 32] : 0.0f;
-    }
-    auto act_block = [&]<int i>() __attribute__((always_inline)) {
-        dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) {
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    acc[i][j][r] = activate<ACT>(a.post * (a.alpha * acc[i][j][r] + bias[j]), a.lo, a.hi);
-        });
-    };
-    auto row_of = [&](int i, int r) __attribute__((always_inline)) { return wrow0 + i * 32 + (r >> 2) * 8 + (r & 3); };
-    // Store of one 32-row accumulator block through a wave-private LDS patch, so that global
-    // stores are 16 bytes per lane and cover whole rows segments: the block is written as fp32
-    // [32][WTN + 8] (the +8 keeps lanes 0-31 and 32-63, four rows apart, on different banks),
-    // read back row-wise, converted and stored.  The patch lives in the panel memory, which
-    // is free once the mainloop's last fragment reads are behind the barrier above.
-    constexpr int SSTR = WTN + 8;                     // floats per patch row
-    constexpr int VEC = 16 / (int)sizeof(OutT);       // elements per 16-byte store
-    constexpr int LPR = WTN / VEC, RPP = 64 / LPR;    // lanes per row, rows per pass
-    static_assert(WAVES_M * WAVES_N * 32 * SSTR * 4 <= 2 * STAGE, "store patch fits the panels");
-    float *patch = reinterpret_cast<float *>(smem) + wave * 32 * SSTR;
-    auto store_block = [&]<int i>() __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                patch[((r >> 2) * 8 + h * 4 + (r & 3)) * SSTR + j * 32 + l32] = acc[i][j][r];
-        const int prow = lane / LPR, pcol = (lane % LPR) * VEC;
-        const int gcol = n0 + wave_n * WTN + pcol;
-#pragma unroll
-        for (int p = 0; p < 32 / RPP; ++p) {
-            const int row = p * RPP + prow;
-            const int grow = m0 + wave_m * WTM + i * 32 + row;
-            float v[VEC];
-#pragma unroll
-            for (int e = 0; e < VEC; e += 4) {
-                const floatx4 f = *reinterpret_cast<const floatx4 *>(patch + row * SSTR + pcol + e);
-                v[e] = f[0]; v[e + 1] = f[1]; v[e + 2] = f[2]; v[e + 3] = f[3];
-            }
-            if (grow < a.M && gcol < a.N)             // N is a multiple of VEC: whole vector or none
-                *reinterpret_cast<uint4 *>(out + (int64_t)grow * a.ldo + gcol) = Store<OutT>::pack(v);
-        }
-    };
-
-    // ---------------- in-tile row statistics, one 32-row accumulator block at a time
-    const bool whole_row = a.tiles_n == 1;
-    const int ncols = min(BN, a.N - n0);              // valid columns of this tile
-    float gam[NB], bet[NB];
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        gam[j] = (a.gamma != nullptr && cok[j]) ? a.gamma[wcol0 + j * 32] : 1.0f;
-        bet[j] = (a.beta != nullptr && cok[j]) ? a.beta[wcol0 + j * 32] : 0.0f;
-    }
-    const bool writer = wave_n == 0 && l32 == 0;      // one lane per accumulator row
-
-    auto norm_block = [&]<int NORM, int i>() __attribute__((always_inline)) {
-        float st[16];
-        // All-reduce one value per accumulator row over the tile's BN columns: across the 32
-        // lanes of the row, then across the WAVES_N waves through LDS.
-        auto reduce_rows = [&]<typename Op>(Op) __attribute__((always_inline)) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) st[r] = allreduce32<Op>(st[r]);
-            if constexpr (WAVES_N > 1) {
-                __syncthreads();                      // previous use of `red` is over
-                if (l32 == 0) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) red[row_of(i, r) * WAVES_N + wave_n] = st[r];
-                }
-                __syncthreads();
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float *p = red + row_of(i, r) * WAVES_N;
-                    float v = p[0];
-#pragma unroll
-                    for (int w = 1; w < WAVES_N; ++w) v = Op::f(v, p[w]);
-                    st[r] = v;
-                }
-            }
-        };
-        // statistics of split rows: one float2 per (row, column tile)
-        auto put_stats = [&](int r, float s0, float s1) __attribute__((always_inline)) {
-            const int grow = m0 + row_of(i, r);
-            if (writer && grow < a.M)
-                a.ws[((int64_t)z * a.M + grow) * a.tiles_n + tn] = make_float2(s0, s1);
-        };
-
-        if constexpr (NORM == FGE_NORM_SOFTMAX || NORM == FGE_NORM_LOGSUMEXP) {
-            float mx[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float m = OpMax::ident();
-#pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    if (cok[j]) m = fmaxf(m, acc[i][j][r]);
-                st[r] = m;
-            }
-            reduce_rows(OpMax{});
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                mx[r] = st[r];
-                float s = 0.0f;
-#pragma unroll
-                for (int j = 0; j < NB; ++j) {
-                    const float e = cok[j] ? fast_exp(acc[i][j][r] - mx[r]) : 0.0f;
-                    if constexpr (NORM == FGE_NORM_SOFTMAX) acc[i][j][r] = e;
-                    s += e;
-                }
-                st[r] = s;
-            }
-            reduce_rows(OpSum{});
-            // (the whole_row test stays outside the unrolled loops: inside them the compiler
-            // keeps the accumulators in scratch memory)
-            if (!whole_row) {
-                // softmax parks exp(a - m_tile); the second pass rescales by exp(m_tile - m)/s
-#pragma unroll
-                for (int r = 0; r < 16; ++r) put_stats(r, mx[r], st[r]);
-            } else if constexpr (NORM == FGE_NORM_SOFTMAX) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float inv = fast_rcp(st[r]);
-#pragma unroll
-                    for (int j = 0; j < NB; ++j) acc[i][j][r] *= inv;
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int grow = m0 + row_of(i, r);
-                    if (writer && grow < a.M)
-                        a.aux[(int64_t)z * a.M + grow] = mx[r] + __logf(st[r]);
-                }
-            }
-        } else if constexpr (NORM == FGE_NORM_LAYERNORM) {
-            float mean[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float s = 0.0f;
-#pragma unroll
-                for (int j = 0; j < NB; ++j) s += cok[j] ? acc[i][j][r] : 0.0f;
-                st[r] = s;
-            }
-            reduce_rows(OpSum{});
-            const float inv_n = 1.0f / (float)ncols;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                mean[r] = st[r] * inv_n;
-                float s = 0.0f;
-#pragma unroll
-                for (int j = 0; j < NB; ++j) {
-                    const float d = acc[i][j][r] - mean[r];
-                    s += cok[j] ? d * d : 0.0f;
-                }
-                st[r] = s;
-            }
-            reduce_rows(OpSum{});
-            if (whole_row) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float rstd = rsqrtf(st[r] * inv_n + a.eps);
-#pragma unroll
-                    for (int j = 0; j < NB; ++j)
-                        acc[i][j][r] = (acc[i][j][r] - mean[r]) * rstd * gam[j] + bet[j];
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) put_stats(r, mean[r], st[r]);   // tile (mean, M2)
-            }
-        } else {  // FGE_NORM_RMSNORM
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float s = 0.0f;
-#pragma unroll
-                for (int j = 0; j < NB; ++j) s += cok[j] ? acc[i][j][r] * acc[i][j][r] : 0.0f;
-                st[r] = s;
-            }
-            reduce_rows(OpSum{});
-            if (whole_row) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float rr = rsqrtf(st[r] / (float)a.N + a.eps);
-#pragma unroll
-                    for (int j = 0; j < NB; ++j) acc[i][j][r] *= rr * gam[j];
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) put_stats(r, st[r], 0.0f);
-            }
-        }
-    };
-    // Each 32-row accumulator block goes through activation, statistics and store on its own,
-    // so only one block's values are live in the vector registers at a time.
+    // ---------------- epilogue, one 32-row accumulator block at a time, so that only one
+    // block's values are live in the vector registers.  The store patch lives in the panel
+    // memory, free once the mainloop's last fragment reads are behind the barrier above.
+    using Epi = TileEpilogue<OutT, NB, WAVES_N, BN, 32, false>;
+    static_assert(WAVES_M * WAVES_N * Epi::PATCH_FLOATS * 4 <= 2 * STAGE, "store patches fit the panels");
+    Epi epi(a, out, red, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, z, m0, n0, tn,
+            wave_n, lane);
     static_for<0, MB>([&]<int i>() __attribute__((always_inline)) {
-        act_block.template operator()<i>();
-        switch (a.norm) {
-        case FGE_NORM_NONE:      break;
-        case FGE_NORM_SOFTMAX:   norm_block.template operator()<FGE_NORM_SOFTMAX, i>(); break;
-        case FGE_NORM_LOGSUMEXP: norm_block.template operator()<FGE_NORM_LOGSUMEXP, i>(); break;
-        case FGE_NORM_LAYERNORM: norm_block.template operator()<FGE_NORM_LAYERNORM, i>(); break;
-        default:                 norm_block.template operator()<FGE_NORM_RMSNORM, i>(); break;
-        }
-        store_block.template operator()<i>();
+        epi.block(acc[i], wave_m * WTM + i * 32);
     });
 }
 

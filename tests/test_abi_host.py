@@ -88,7 +88,8 @@ def test_status_strings_and_tile_names():
     assert L.fge_status_string(99) == b"unknown status"
     assert L.fge_last_hip_error() == 0
     assert B.fge_tile_name(True, 1, 1, _params(N=64, ldo=64)) == "64x64_w2x2"
-    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512)) == "64x512_w1x4"
+    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512)) == "panel64x512_w1x8_splitbf16"
+    assert B.fge_tile_name(True, 5, 4, _params(M=1000, N=512, ldo=512)) == "64x512_w1x4"
     big = _params(M=8192, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, in_dtype=1, out_dtype=1)
     assert B.fge_tile_name(True, 4, 3, big) == "256x256_w2x4"
     assert B.fge_fused_needs_finish(4, 3, big) is True

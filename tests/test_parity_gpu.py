@@ -76,6 +76,44 @@ def test_all_chains(dt, norm, N):
             _parity(w, path, label=f"{path} act{act} norm{norm}")
 
 
+@pytest.mark.parametrize("norm", NORMS)
+@pytest.mark.parametrize("shape", [(4100, 64, 512), (5000, 40, 328), (4096, 8, 72)])
+def test_narrow_k_persistent_kernel(norm, shape):
+    """fp32, K <= 64, N <= 512, M >= 4096 takes the persistent narrow-K kernel (split-bf16
+    MFMA): every row op, ragged M / N / K, fp32 and bf16 stores, still inside the fp32 gate."""
+    M, K, N = shape
+    for act, odt in ((I.ACT_CLAMP, I.F32), (I.ACT_GELU_TANH, I.F32), (I.ACT_SILU, I.BF16)):
+        w = I.Workload(name=f"nk{norm}", M=M, K=K, N=N, in_dtype=I.F32, out_dtype=odt, act=act,
+                       norm=norm, alpha=0.75, post_scale=2.0, clamp_lo=-5.0, clamp_hi=5.0, eps=1e-5,
+                       dist={"X": ("uniform", -1.0, 1.0), "W": ("normal", 0.0, 0.125),
+                             "b": ("normal", 0.0, 0.5), "gamma": ("normal", 1.0, 0.1),
+                             "beta": ("normal", 0.0, 0.1)})
+        t = I.generate(w)
+        d = {k: H.to_device(v) for k, v in t.items()}
+        p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(odt), device="cuda"))
+        assert B.fge_tile_name(True, act, norm, p).startswith("panel")
+        ref, raux = H.oracle_chain(w, t)
+        for path in ("fused", "unfused"):
+            got, gaux = H.run_gpu(w, t, path, dev=d)
+            if odt == I.BF16:
+                # unfused keeps Y and A in bf16: |a| up to ~8 carries 2^-9*8 absolute error into
+                # the exponentials of a softmax, hence the wider gate for that path
+                tol = 2e-2 if path == "fused" else 8e-2
+                assert np.isfinite(got).all() and H.C.max_rel_err(got, ref) <= tol
+            else:
+                H.check(w, got, gaux, ref, raux, f"narrow-k {path} act{act}")
+
+
+def test_narrow_k_exact_integers():
+    """Small integers survive the bf16 split exactly: the result must match bit for bit."""
+    w = I.Workload(name="nkint", M=4500, K=64, N=512, in_dtype=I.F32, out_dtype=I.F32,
+                   dist={"X": ("int", -2, 2), "W": ("int", -2, 2), "b": ("int", -3, 3)})
+    t = I.generate(w)
+    got, _ = H.run_gpu(w, t, "fused")
+    ref, _ = H.oracle_chain(w, t)
+    assert np.array_equal(got, ref)
+
+
 def test_mixed_dtypes_and_no_optional_vectors():
     for (i, o) in [(I.F32, I.BF16), (I.BF16, I.F32)]:
         w = I.Workload(name="mix", M=130, K=256, N=520, in_dtype=i, out_dtype=o, act=I.ACT_SILU,
