@@ -132,24 +132,23 @@ template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
         0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
 
-// All-reduce over the 32 lanes that share lane/32 (the lanes holding one accumulator row of a
-// 32x32 MFMA tile).  Steps: quad swaps (xor 1, xor 2), mirror within 8, mirror within 16 -
-// valid because after each step the value is uniform inside the smaller group - and a
-// swizzle exchanging lanes i and i^16.
-template <typename Op> __device__ __forceinline__ float allreduce32(float v) {
-    v = Op::f(v, dpp_mov<0xB1>(v));    // quad_perm [1,0,3,2]
-    v = Op::f(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
-    v = Op::f(v, dpp_mov<0x141>(v));   // row_half_mirror
-    v = Op::f(v, dpp_mov<0x140>(v));   // row_mirror
-    v = Op::f(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(
-                     __builtin_bit_cast(int, v), 0x401F)));   // bit mode: and 0x1f, xor 0x10
+// All-reduce over groups of G neighbouring lanes (G a power of two, groups aligned to G).
+// Steps: quad swaps (xor 1, xor 2), mirror within 8, mirror within 16 - valid because after
+// each step the value is uniform inside the smaller group -, a swizzle exchanging lanes i and
+// i^16, and a shuffle across the two halves of the wave.
+template <typename Op, int G> __device__ __forceinline__ float allreduce_lanes(float v) {
+    if constexpr (G >= 2)  v = Op::f(v, dpp_mov<0xB1>(v));    // quad_perm [1,0,3,2]
+    if constexpr (G >= 4)  v = Op::f(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
+    if constexpr (G >= 8)  v = Op::f(v, dpp_mov<0x141>(v));   // row_half_mirror
+    if constexpr (G >= 16) v = Op::f(v, dpp_mov<0x140>(v));   // row_mirror
+    if constexpr (G >= 32) v = Op::f(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(
+                                            __builtin_bit_cast(int, v), 0x401F)));   // and 0x1f, xor 0x10
+    if constexpr (G >= 64) v = Op::f(v, __shfl_xor(v, 32, 64));
     return v;
 }
+template <typename Op> __device__ __forceinline__ float allreduce32(float v) { return allreduce_lanes<Op, 32>(v); }
 
 // All-reduce over the whole 64-lane wavefront.
-template <typename Op> __device__ __forceinline__ float allreduce64(float v) {
-    v = allreduce32<Op>(v);
-    return Op::f(v, __shfl_xor(v, 32, 64));
-}
+template <typename Op> __device__ __forceinline__ float allreduce64(float v) { return allreduce_lanes<Op, 64>(v); }
 
 }  // namespace fge

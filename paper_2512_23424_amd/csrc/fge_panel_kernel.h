@@ -54,7 +54,7 @@ void panel_kernel(const TileArgs a) {
     using Epi = TileEpilogue<OutT, NB, WAVES_N, BN, 16, true>;
 
     __shared__ __attribute__((aligned(16))) unsigned char xs[2 * XTILE];
-    __shared__ float red[BM * WAVES_N];
+    __shared__ __attribute__((aligned(16))) float red[2 * BM * WAVES_N];
     __shared__ __attribute__((aligned(16))) float patches[(NT / 64) * Epi::PATCH_FLOATS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -123,7 +123,7 @@ void panel_kernel(const TileArgs a) {
             for (int c = 0; c < 2; ++c)
                 fa_off[i][t][c] = (i * 32 + l32) * XROWB + (((4 * t + 2 * h + c) ^ (l32 & 15)) << 4);
 
-    Epi epi(a, out, red, patches + wave * Epi::PATCH_FLOATS, 0, 0, 0, 0, wave_n, lane);
+    Epi epi(a, out, red, patches + wave * Epi::PATCH_FLOATS, BM, 0, 0, 0, 0, wave_n, lane);
 
     // ---------------- persistent loop over 64-row tiles
     const int ntiles = a.tiles_m;

@@ -80,7 +80,7 @@ void tile_kernel(const TileArgs a) {
     constexpr int STAGE = (BM + BN) * ROWB;
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
-    __shared__ float red[BM * WAVES_N];
+    __shared__ __attribute__((aligned(16))) float red[2 * BM * WAVES_N];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
@@ -241,7 +241,7 @@ void tile_kernel(const TileArgs a) {
     // memory, free once the mainloop's last fragment reads are behind the barrier above.
     using Epi = TileEpilogue<OutT, NB, WAVES_N, BN, 32, false>;
     static_assert(WAVES_M * WAVES_N * Epi::PATCH_FLOATS * 4 <= 2 * STAGE, "store patches fit the panels");
-    Epi epi(a, out, red, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, z, m0, n0, tn,
+    Epi epi(a, out, red, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, BM, z, m0, n0, tn,
             wave_n, lane);
     static_for<0, MB>([&]<int i>() __attribute__((always_inline)) {
         epi.block(acc[i], wave_m * WTM + i * 32);
