@@ -13,7 +13,7 @@ thread_local int g_last_hip = 0;
 
 constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 CUs
 constexpr int MAX_ROWOP_N = 8192;    // a row must fit the register-resident row kernels
-constexpr int MAX_SPLIT = 64;        // column tiles per row the second pass can merge (one per lane)
+constexpr int MAX_SPLIT = 1024;      // column strips per row the second pass will merge
 
 inline size_t esize(int dt) { return dt == FGE_BF16 ? 2 : 4; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -29,6 +29,7 @@ struct Plan {
     Problem pr;
     int tile;
     int tiles_m, tiles_n;
+    int strips;                  // statistics slots per row: column tiles x waves across a tile
     bool needs_finish;           // rows split over several column tiles and a row op is requested
     size_t ws_stats;             // bytes of per-tile statistics (fused)
     size_t ws_buf;               // bytes of one out-shaped intermediate (unfused)
@@ -101,7 +102,8 @@ Plan make_plan(const fge_params *p, int norm) {
     pl.tiles_m = (pr.M + ti.bm - 1) / ti.bm;
     pl.tiles_n = (pr.N + ti.bn - 1) / ti.bn;
     pl.needs_finish = norm != FGE_NORM_NONE && pl.tiles_n > 1;
-    pl.ws_stats = pl.needs_finish ? round256((size_t)pr.M * pr.batch * pl.tiles_n * sizeof(float2)) : 0;
+    pl.strips = pl.tiles_n * ti.waves_n;
+    pl.ws_stats = pl.needs_finish ? round256((size_t)pr.M * pr.batch * pl.strips * sizeof(float2)) : 0;
     const size_t extent = (size_t)(pr.batch - 1) * pr.bso + (size_t)(pr.M - 1) * pr.ldo + pr.N;
     pl.ws_buf = round256(extent * esize(p->out_dtype));
     // K2 writes straight into `out` when the row op leaves the activated values in place
@@ -146,7 +148,7 @@ RowArgs row_args(const void *in, void *out, int act, int norm, const fge_params 
     r.ws = reinterpret_cast<const float2 *>(p->workspace);
     r.M = pl.pr.M; r.N = pl.pr.N; r.batch = pl.pr.batch; r.ldo = pl.pr.ldo; r.bso = pl.pr.bso;
     r.lo = p->clamp_lo; r.hi = p->clamp_hi; r.eps = p->eps; r.act = act; r.norm = norm;
-    r.tiles_n = pl.tiles_n; r.bn = tile_info(pl.tile).bn;
+    r.tiles_n = pl.strips; r.bn = tile_info(pl.tile).bn / tile_info(pl.tile).waves_n;
     return r;
 }
 
@@ -174,7 +176,7 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
     const Plan pl = make_plan(p, norm);
     if (pl.needs_finish) {
-        if (pl.tiles_n > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
+        if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
         if (!p->workspace || p->workspace_bytes < pl.ws_stats) return FGE_ERR_WORKSPACE;
     }
     if (plan_out) *plan_out = pl;
@@ -189,7 +191,7 @@ int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
     const Plan pl = make_plan(p, norm);
     if (!pl.needs_finish) return FGE_OK;
-    if (pl.tiles_n > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
+    if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
     if (!p->workspace || p->workspace_bytes < pl.ws_stats) return FGE_ERR_WORKSPACE;
     const RowArgs r = row_args(out, out, act, norm, p, pl);
     const int64_t rows = (int64_t)r.batch * r.M;

@@ -8,9 +8,15 @@
 // of the block.  Scale, bias and activation are applied in that layout.  The block then goes
 // through a wave-private LDS patch into a row-wise layout - a lane holds 16 bytes' worth of
 // neighbouring columns of one row, LPR neighbouring lanes hold a row segment - in which the row
-// statistics need only log2(LPR) cross-lane steps per row (plus one LDS exchange between the
-// WAVES_N waves sharing the rows) and the global stores are 16 bytes per lane over whole row
-// segments.
+// statistics need only log2(LPR) cross-lane steps per row and the global stores are 16 bytes
+// per lane over whole row segments.
+//
+// Every wave first reduces its own strip of WTN columns to a mergeable pair per row:
+//     softmax / logsumexp (m, s = sum exp(a - m)),  LayerNorm (mean, M2),  RMSNorm (sum a^2, -).
+// Rows split over several column tiles publish that pair per (row, strip) for the second
+// pass - no exchange between waves at all.  Rows that the tile spans are finished in place:
+// the WAVES_N pairs of a row meet in LDS (one barrier) and are merged by the same rules the
+// second pass uses (online-softmax merge, Chan's variance merge, plain sum).
 #pragma once
 #include "fge_device.h"
 
@@ -29,156 +35,160 @@ struct TileArgs {
     int tiles_m, tiles_n, group_m;
 };
 
-// OutT: storage type of out.  NB: 32-column blocks per wave.  WAVES_N: waves sharing a row.
-// BN: tile width.  PATCH_ROWS (32 or 16): rows staged at a time in the wave's LDS patch.
-// WAIT_VM: drain the wave's vector-memory counter before the first global store of a block
-// (for callers that have asynchronous global->LDS loads in flight and want them accounted for
-// before the stores are queued behind them).
-template <typename OutT, int NB, int WAVES_N, int BN, int PATCH_ROWS, bool WAIT_VM>
+// OutT: storage type of out.  MB x NB: 32x32 accumulator blocks per wave.  WAVES_N: waves
+// sharing a row.  PATCH_ROWS (32 or 16): rows staged at a time in the wave's LDS patch.
+// JOINT: all MB blocks of the wave go through one statistics step (one exchange per tile; for
+// tiles that span N) instead of one per block (less register pressure; split rows never
+// exchange anyway).  WAIT_VM: drain the wave's vector-memory counter before the first global
+// store of a group (for callers with asynchronous global->LDS loads in flight that want them
+// accounted for before stores are queued behind them).
+template <typename OutT, int MB, int NB, int WAVES_N, int PATCH_ROWS, bool JOINT, bool WAIT_VM>
 struct TileEpilogue {
-    static constexpr int WTN = NB * 32;
+    static constexpr int WTN = NB * 32;               // columns of a wave strip
     static constexpr int SSTR = WTN + 8;              // floats per patch row: +8 puts lanes 0-31
                                                       // and 32-63 (four rows apart) on other banks
-    static constexpr int VEC = 16 / (int)sizeof(OutT);
+    static constexpr int VEC = 8;                     // columns per lane in the row-wise layout, as
+                                                      // two groups of 4: neighbours for bf16 (one
+                                                      // 16-byte store), half a strip apart for fp32
+                                                      // (two 16-byte stores, each contiguous over
+                                                      // the lanes of a row segment)
+    static constexpr int G4STEP = sizeof(OutT) == 2 ? 4 : WTN / 2;   // columns between the groups
+    static constexpr int SUBW = sizeof(OutT) == 2 ? 8 : 4;           // columns between lanes
     static constexpr int LPR = WTN / VEC, RPP = 64 / LPR;   // lanes per row, rows per pass
-    static constexpr int NP = PATCH_ROWS / RPP;             // passes over the patch
+    static constexpr int NPH = PATCH_ROWS / RPP;            // passes per patch fill
+    static constexpr int NPB = 32 / RPP;                    // passes per 32-row block
+    static constexpr int G = JOINT ? MB : 1;                // blocks per statistics group
+    static constexpr int NPG = G * NPB;                     // passes per group
     static constexpr int PATCH_FLOATS = PATCH_ROWS * SSTR;  // per wave
     static_assert(PATCH_ROWS == 32 || PATCH_ROWS == 16, "patch");
-    static_assert(RPP >= 1 && PATCH_ROWS % RPP == 0 && LPR <= 64, "patch passes");
+    static_assert(RPP >= 1 && PATCH_ROWS % RPP == 0 && LPR <= 64 && LPR >= WAVES_N, "patch passes");
 
     const TileArgs &a;
     OutT *out;                  // base of this problem's output
-    float *red;                 // LDS, two buffers of [tile rows][WAVES_N], used alternately
+    float2 *xch;                // LDS, two buffers of [tile rows][WAVES_N] pairs, used alternately
     float *patch;               // LDS, this wave's PATCH_FLOATS
     int64_t row_base;           // z * M: offset of this problem in aux / ws
     int m0, n0, tn;             // tile origin and column-tile index
-    int tile_rows;              // rows of the tile (stride between the two red buffers)
+    int tile_rows;              // rows of the tile (stride between the two exchange buffers)
     int wave_n, lane, h, l32;
-    int prow, pcol, gcol;       // row-wise layout: row in a pass, first column in the wave tile / globally
-    bool vok;                   // this lane's column vector lies inside N (N is a multiple of VEC)
-    bool rlead;                 // first lane of a row segment
-    int red_par;                // which red buffer the next exchange uses
-    float bias[NB];
+    int prow, pcol, gcol;       // row-wise layout: row in a pass, first column (of group 0) in
+                                // the strip / globally; group 1 lies G4STEP columns further
+    int sub;                    // lane index inside its row segment
+    bool ok4[2];                // columns gcol..+3 / gcol+4..+7 lie inside N (N is a multiple of 4)
+    int xch_par;                // which exchange buffer the next exchange uses
+    float scale, bias[NB];      // y = scale * acc + bias  (scale = post*alpha, bias = post*b)
     bool whole_row;
-    int ncols;
 
-    __device__ __forceinline__ TileEpilogue(const TileArgs &a_, OutT *out_, float *red_, float *patch_,
+    __device__ __forceinline__ TileEpilogue(const TileArgs &a_, OutT *out_, float2 *xch_, float *patch_,
                                             int tile_rows_, int z, int m0_, int n0_, int tn_,
                                             int wave_n_, int lane_)
-        : a(a_), out(out_), red(red_), patch(patch_), row_base((int64_t)z * a_.M), m0(m0_), n0(n0_),
+        : a(a_), out(out_), xch(xch_), patch(patch_), row_base((int64_t)z * a_.M), m0(m0_), n0(n0_),
           tn(tn_), tile_rows(tile_rows_), wave_n(wave_n_), lane(lane_), h(lane_ >> 5), l32(lane_ & 31) {
         const int wcol0 = n0 + wave_n * WTN + l32;
+        scale = a.post * a.alpha;
 #pragma unroll
         for (int j = 0; j < NB; ++j)
-            bias[j] = (a.b != nullptr && wcol0 + j * 32 < a.N) ? a.b[wcol0 + j * 32] : 0.0f;
+            bias[j] = (a.b != nullptr && wcol0 + j * 32 < a.N) ? a.post * a.b[wcol0 + j * 32] : 0.0f;
         prow = lane / LPR;
-        pcol = (lane % LPR) * VEC;
+        sub = lane % LPR;
+        pcol = sub * SUBW;
         gcol = n0 + wave_n * WTN + pcol;
-        vok = gcol < a.N;
-        rlead = lane % LPR == 0;
-        red_par = 0;
+        ok4[0] = gcol < a.N;
+        ok4[1] = gcol + G4STEP < a.N;
+        xch_par = 0;
         whole_row = a.tiles_n == 1;
-        ncols = min(BN, a.N - n0);                    // valid columns of this tile
     }
 
-    // row of accumulator element r inside the block
+    // valid columns of strip w of this tile
+    __device__ __forceinline__ int strip_cols(int w) const { return max(0, min(WTN, a.N - (n0 + w * WTN))); }
+    // row of accumulator element r inside its block
     __device__ __forceinline__ int brow(int r) const { return (r >> 2) * 8 + h * 4 + (r & 3); }
+    // tile row of pass q of a group whose first block starts at tile row grow0
+    __device__ __forceinline__ int qrow(int grow0, int q) const { return grow0 + (q / NPB) * 32 + (q % NPB) * RPP + prow; }
 
     template <int ACT> __device__ __forceinline__ void act_block(floatx16 (&blk)[NB]) {
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                blk[j][r] = activate<ACT>(a.post * (a.alpha * blk[j][r] + bias[j]), a.lo, a.hi);
+            for (int r = 0; r < 16; ++r) blk[j][r] = activate<ACT>(scale * blk[j][r] + bias[j], a.lo, a.hi);
     }
 
-    // All-reduce st[p] (one value per row of pass p) over the tile's columns: across the LPR
-    // lanes of the row segment, then across the WAVES_N waves through LDS.  The two red buffers
-    // alternate, so one barrier per exchange is enough: a buffer is rewritten only after the
-    // barrier of the exchange in between.  trow0: tile row of patch row 0.
-    template <typename Op> __device__ __forceinline__ void reduce_rows(float (&st)[NP], int trow0) {
-#pragma unroll
-        for (int p = 0; p < NP; ++p) st[p] = allreduce_lanes<Op, LPR>(st[p]);
+    // Publish the strip pair of pass q for the second pass.
+    __device__ __forceinline__ void put_stats(int grow0, int q, float s0, float s1) {
+        const int grow = m0 + qrow(grow0, q);
+        if (sub == 0 && grow < a.M)
+            a.ws[(row_base + grow) * (a.tiles_n * WAVES_N) + tn * WAVES_N + wave_n] = make_float2(s0, s1);
+    }
+    // Whole rows: every strip's pair of every row of the group meets in LDS; afterwards lane
+    // `sub` of a row segment holds the pair of strip `sub` (identity beyond WAVES_N).  The two
+    // buffers alternate, so one barrier per exchange is enough: a buffer is rewritten only
+    // after the barrier of the exchange in between.
+    __device__ __forceinline__ void exchange(int grow0, float (&s0)[NPG], float (&s1)[NPG], float ident0) {
         if constexpr (WAVES_N > 1) {
-            float *rb = red + red_par * tile_rows * WAVES_N;
-            red_par ^= 1;
-            if (rlead) {
+            float2 *xb = xch + xch_par * tile_rows * WAVES_N;
+            xch_par ^= 1;
+            if (sub == 0) {
 #pragma unroll
-                for (int p = 0; p < NP; ++p) rb[(trow0 + p * RPP + prow) * WAVES_N + wave_n] = st[p];
+                for (int q = 0; q < NPG; ++q) xb[qrow(grow0, q) * WAVES_N + wave_n] = make_float2(s0[q], s1[q]);
             }
             __syncthreads();
 #pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                const float *q = rb + (trow0 + p * RPP + prow) * WAVES_N;
-                float v;
-                if constexpr (WAVES_N % 4 == 0) {     // 16-byte LDS reads (red is 16-byte aligned)
-                    floatx4 x = *reinterpret_cast<const floatx4 *>(q);
-#pragma unroll
-                    for (int w = 4; w < WAVES_N; w += 4) {
-                        const floatx4 y = *reinterpret_cast<const floatx4 *>(q + w);
-                        x[0] = Op::f(x[0], y[0]); x[1] = Op::f(x[1], y[1]);
-                        x[2] = Op::f(x[2], y[2]); x[3] = Op::f(x[3], y[3]);
-                    }
-                    v = Op::f(Op::f(x[0], x[1]), Op::f(x[2], x[3]));
-                } else {
-                    v = q[0];
-#pragma unroll
-                    for (int w = 1; w < WAVES_N; ++w) v = Op::f(v, q[w]);
-                }
-                st[p] = v;
+            for (int q = 0; q < NPG; ++q) {
+                float2 e = make_float2(ident0, 0.0f);
+                if (sub < WAVES_N) e = xb[qrow(grow0, q) * WAVES_N + sub];
+                s0[q] = e.x;
+                s1[q] = e.y;
             }
+        } else {
+#pragma unroll
+            for (int q = 0; q < NPG; ++q)
+                if (sub != 0) { s0[q] = ident0; s1[q] = 0.0f; }
         }
     }
 
-    // Row operation on PATCH_ROWS rows in the row-wise layout: v[p][e] is column gcol + e of
-    // patch row p*RPP + prow.  Whole rows are normalised in place; split rows keep the parked
-    // value and publish their per-tile statistics (one float2 per row and column tile).
-    template <int NORM> __device__ __forceinline__ void norm_rows(float (&v)[NP][VEC], int trow0) {
-        float st[NP];
-        const bool stat_writer = rlead && wave_n == 0;
-        auto put_stats = [&](int p, float s0, float s1) __attribute__((always_inline)) {
-            const int grow = m0 + trow0 + p * RPP + prow;
-            if (stat_writer && grow < a.M) a.ws[(row_base + grow) * a.tiles_n + tn] = make_float2(s0, s1);
-        };
+    // Row operation on one group in the row-wise layout: v[q][e] is column gcol + (e/4)*G4STEP + e%4 of tile row
+    // qrow(grow0, q).  Whole rows are normalised in place; split rows keep the parked value.
+    template <int NORM> __device__ __forceinline__ void norm_group(float (&v)[NPG][VEC], int grow0) {
+        float s0[NPG], s1[NPG];
         if constexpr (NORM == FGE_NORM_SOFTMAX || NORM == FGE_NORM_LOGSUMEXP) {
-            float mx[NP];
+            float ml[NPG];                            // strip maxima
 #pragma unroll
-            for (int p = 0; p < NP; ++p) {
+            for (int q = 0; q < NPG; ++q) {
                 float m = OpMax::ident();
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) m = fmaxf(m, v[p][e]);
-                st[p] = vok ? m : OpMax::ident();
+                for (int e = 0; e < VEC; ++e) m = fmaxf(m, ok4[e >> 2] ? v[q][e] : OpMax::ident());
+                ml[q] = allreduce_lanes<OpMax, LPR>(m);
             }
-            reduce_rows<OpMax>(st, trow0);
 #pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                mx[p] = st[p];
+            for (int q = 0; q < NPG; ++q) {
                 float s = 0.0f;
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    const float x = fast_exp(v[p][e] - mx[p]);
-                    if constexpr (NORM == FGE_NORM_SOFTMAX) v[p][e] = x;
-                    s += x;
+                    const float x = fast_exp(v[q][e] - ml[q]);
+                    if constexpr (NORM == FGE_NORM_SOFTMAX) v[q][e] = x;
+                    s += ok4[e >> 2] ? x : 0.0f;
                 }
-                st[p] = vok ? s : 0.0f;
+                s0[q] = ml[q];
+                s1[q] = allreduce_lanes<OpSum, LPR>(s);
             }
-            reduce_rows<OpSum>(st, trow0);
             if (!whole_row) {
-                // softmax parks exp(a - m_tile); the second pass rescales by exp(m_tile - m)/s
+                // softmax parks exp(a - m_strip); the second pass rescales by exp(m_strip - m)/s
 #pragma unroll
-                for (int p = 0; p < NP; ++p) put_stats(p, mx[p], st[p]);
-            } else if constexpr (NORM == FGE_NORM_SOFTMAX) {
+                for (int q = 0; q < NPG; ++q) put_stats(grow0, q, s0[q], s1[q]);
+                return;
+            }
+            exchange(grow0, s0, s1, OpMax::ident());
 #pragma unroll
-                for (int p = 0; p < NP; ++p) {
-                    const float inv = fast_rcp(st[p]);
+            for (int q = 0; q < NPG; ++q) {
+                const float m = allreduce_lanes<OpMax, LPR>(s0[q]);
+                const float s = allreduce_lanes<OpSum, LPR>(s1[q] * fast_exp(s0[q] - m));
+                if constexpr (NORM == FGE_NORM_SOFTMAX) {
+                    const float f = fast_exp(ml[q] - m) * fast_rcp(s);
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) v[p][e] *= inv;
-                }
-            } else {
-#pragma unroll
-                for (int p = 0; p < NP; ++p) {
-                    const int grow = m0 + trow0 + p * RPP + prow;
-                    if (stat_writer && grow < a.M) a.aux[row_base + grow] = mx[p] + __logf(st[p]);
+                    for (int e = 0; e < VEC; ++e) v[q][e] *= f;
+                } else {
+                    const int grow = m0 + qrow(grow0, q);
+                    if (sub == 0 && wave_n == 0 && grow < a.M) a.aux[row_base + grow] = m + __logf(s);
                 }
             }
             return;
@@ -188,71 +198,72 @@ struct TileEpilogue {
 #pragma unroll
         for (int e = 0; e < VEC; e += 4) {
             floatx4 g = {1.0f, 1.0f, 1.0f, 1.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (whole_row && vok && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + gcol + e);
-            if (whole_row && vok && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + gcol + e);
+            const int c = gcol + (e >> 2) * G4STEP;
+            if (whole_row && ok4[e >> 2] && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + c);
+            if (whole_row && ok4[e >> 2] && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + c);
             gam[e] = g[0]; gam[e + 1] = g[1]; gam[e + 2] = g[2]; gam[e + 3] = g[3];
             bet[e] = b[0]; bet[e + 1] = b[1]; bet[e + 2] = b[2]; bet[e + 3] = b[3];
         }
         if constexpr (NORM == FGE_NORM_LAYERNORM) {
-            float mean[NP];
+            const int nl = strip_cols(wave_n);
+            const float inv_nl = nl > 0 ? 1.0f / (float)nl : 0.0f;
 #pragma unroll
-            for (int p = 0; p < NP; ++p) {
+            for (int q = 0; q < NPG; ++q) {
                 float s = 0.0f;
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) s += v[p][e];
-                st[p] = vok ? s : 0.0f;
-            }
-            reduce_rows<OpSum>(st, trow0);
-            const float inv_n = 1.0f / (float)ncols;
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                mean[p] = st[p] * inv_n;
-                float s = 0.0f;
+                for (int e = 0; e < VEC; ++e) s += ok4[e >> 2] ? v[q][e] : 0.0f;
+                s0[q] = allreduce_lanes<OpSum, LPR>(s) * inv_nl;                  // strip mean
+                float d2 = 0.0f;
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    const float d = v[p][e] - mean[p];
-                    s += d * d;
+                    const float d = v[q][e] - s0[q];
+                    d2 += ok4[e >> 2] ? d * d : 0.0f;
                 }
-                st[p] = vok ? s : 0.0f;
+                s1[q] = allreduce_lanes<OpSum, LPR>(d2);                          // strip M2
             }
-            reduce_rows<OpSum>(st, trow0);
-            if (whole_row) {
+            if (!whole_row) {
 #pragma unroll
-                for (int p = 0; p < NP; ++p) {
-                    const float rstd = rsqrtf(st[p] * inv_n + a.eps);
+                for (int q = 0; q < NPG; ++q) put_stats(grow0, q, s0[q], s1[q]);
+                return;
+            }
+            exchange(grow0, s0, s1, 0.0f);
+            const float nw = sub < WAVES_N ? (float)strip_cols(sub) : 0.0f;       // columns behind this lane's pair
+            const float inv_n = 1.0f / (float)a.N;
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) v[p][e] = (v[p][e] - mean[p]) * rstd * gam[e] + bet[e];
-                }
-            } else {
+            for (int q = 0; q < NPG; ++q) {
+                const float mean = allreduce_lanes<OpSum, LPR>(nw * s0[q]) * inv_n;
+                const float d = s0[q] - mean;
+                const float m2 = allreduce_lanes<OpSum, LPR>(s1[q] + nw * d * d);
+                const float rstd = rsqrtf(m2 * inv_n + a.eps);
 #pragma unroll
-                for (int p = 0; p < NP; ++p) put_stats(p, mean[p], st[p]);   // tile (mean, M2)
+                for (int e = 0; e < VEC; ++e) v[q][e] = (v[q][e] - mean) * rstd * gam[e] + bet[e];
             }
         } else {  // FGE_NORM_RMSNORM
 #pragma unroll
-            for (int p = 0; p < NP; ++p) {
+            for (int q = 0; q < NPG; ++q) {
                 float s = 0.0f;
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) s += v[p][e] * v[p][e];
-                st[p] = vok ? s : 0.0f;
+                for (int e = 0; e < VEC; ++e) s += ok4[e >> 2] ? v[q][e] * v[q][e] : 0.0f;
+                s0[q] = allreduce_lanes<OpSum, LPR>(s);
+                s1[q] = 0.0f;
             }
-            reduce_rows<OpSum>(st, trow0);
-            if (whole_row) {
+            if (!whole_row) {
 #pragma unroll
-                for (int p = 0; p < NP; ++p) {
-                    const float rr = rsqrtf(st[p] / (float)a.N + a.eps);
+                for (int q = 0; q < NPG; ++q) put_stats(grow0, q, s0[q], 0.0f);
+                return;
+            }
+            exchange(grow0, s0, s1, 0.0f);
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) v[p][e] *= rr * gam[e];
-                }
-            } else {
+            for (int q = 0; q < NPG; ++q) {
+                const float rr = rsqrtf(allreduce_lanes<OpSum, LPR>(s0[q]) / (float)a.N + a.eps);
 #pragma unroll
-                for (int p = 0; p < NP; ++p) put_stats(p, st[p], 0.0f);
+                for (int e = 0; e < VEC; ++e) v[q][e] *= rr * gam[e];
             }
         }
     }
 
-    // activation -> LDS patch -> row-wise statistics -> 16-byte global stores, for one 32-row
-    // accumulator block; trow0 = first tile row of the block
-    __device__ __forceinline__ void block(floatx16 (&blk)[NB], int trow0) {
+    // activation (accumulator layout) -> LDS patch -> row-wise layout, for block B of a group
+    template <int B> __device__ __forceinline__ void to_rows(floatx16 (&blk)[NB], float (&v)[NPG][VEC]) {
         dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) { act_block<ACT>(blk); });
 #pragma unroll
         for (int half = 0; half < 32 / PATCH_ROWS; ++half) {
@@ -262,30 +273,48 @@ struct TileEpilogue {
                 for (int r = 0; r < 16; ++r)
                     if (PATCH_ROWS == 32 || (r >> 3) == half)
                         patch[(brow(r) - half * PATCH_ROWS) * SSTR + j * 32 + l32] = blk[j][r];
-            float v[NP][VEC];
 #pragma unroll
-            for (int p = 0; p < NP; ++p)
+            for (int p = 0; p < NPH; ++p)
 #pragma unroll
                 for (int e = 0; e < VEC; e += 4) {
-                    const floatx4 f = *reinterpret_cast<const floatx4 *>(patch + (p * RPP + prow) * SSTR + pcol + e);
-                    v[p][e] = f[0]; v[p][e + 1] = f[1]; v[p][e + 2] = f[2]; v[p][e + 3] = f[3];
+                    const floatx4 f = *reinterpret_cast<const floatx4 *>(patch + (p * RPP + prow) * SSTR + pcol +
+                                                                         (e >> 2) * G4STEP);
+                    v[B * NPB + half * NPH + p][e] = f[0];
+                    v[B * NPB + half * NPH + p][e + 1] = f[1];
+                    v[B * NPB + half * NPH + p][e + 2] = f[2];
+                    v[B * NPB + half * NPH + p][e + 3] = f[3];
                 }
-            const int hrow0 = trow0 + half * PATCH_ROWS;
+        }
+    }
+
+    // the whole epilogue of a wave's MB blocks; trow0 = tile row of the wave's first row
+    __device__ __forceinline__ void tile(floatx16 (&acc)[MB][NB], int trow0) {
+        static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+            float v[NPG][VEC];
+            static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
+            const int grow0 = trow0 + g * G * 32;
             switch (a.norm) {
             case FGE_NORM_NONE:      break;
-            case FGE_NORM_SOFTMAX:   norm_rows<FGE_NORM_SOFTMAX>(v, hrow0); break;
-            case FGE_NORM_LOGSUMEXP: norm_rows<FGE_NORM_LOGSUMEXP>(v, hrow0); break;
-            case FGE_NORM_LAYERNORM: norm_rows<FGE_NORM_LAYERNORM>(v, hrow0); break;
-            default:                 norm_rows<FGE_NORM_RMSNORM>(v, hrow0); break;
+            case FGE_NORM_SOFTMAX:   norm_group<FGE_NORM_SOFTMAX>(v, grow0); break;
+            case FGE_NORM_LOGSUMEXP: norm_group<FGE_NORM_LOGSUMEXP>(v, grow0); break;
+            case FGE_NORM_LAYERNORM: norm_group<FGE_NORM_LAYERNORM>(v, grow0); break;
+            default:                 norm_group<FGE_NORM_RMSNORM>(v, grow0); break;
             }
             if constexpr (WAIT_VM) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                const int grow = m0 + hrow0 + p * RPP + prow;
-                if (grow < a.M && vok)
-                    *reinterpret_cast<uint4 *>(out + (int64_t)grow * a.ldo + gcol) = Store<OutT>::pack(v[p]);
+            for (int q = 0; q < NPG; ++q) {
+                const int grow = m0 + qrow(grow0, q);
+                if (grow < a.M) {
+                    OutT *o = out + (int64_t)grow * a.ldo + gcol;
+                    if constexpr (sizeof(OutT) == 2) {     // N is a multiple of 8: all or nothing
+                        if (ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
+                    } else {
+                        if (ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
+                        if (ok4[1]) *reinterpret_cast<uint4 *>(o + G4STEP) = Store<OutT>::pack(v[q] + 4);
+                    }
+                }
             }
-        }
+        });
     }
 };
 

@@ -6,15 +6,15 @@ namespace fge {
 
 enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_COUNT = 5 };
 
-struct TileInfo { int bm, bn, threads; const char *name; };
+struct TileInfo { int bm, bn, threads, waves_n; const char *name; };
 
 inline const TileInfo &tile_info(int id) {
     static const TileInfo t[TILE_COUNT] = {
-        {64, 64, 256, "64x64_w2x2"},
-        {64, 512, 256, "64x512_w1x4"},
-        {128, 128, 256, "128x128_w2x2"},
-        {256, 256, 512, "256x256_w2x4"},
-        {64, 512, 512, "panel64x512_w1x8_splitbf16"},   // persistent narrow-K kernel, fp32 operands
+        {64, 64, 256, 2, "64x64_w2x2"},
+        {64, 512, 256, 4, "64x512_w1x4"},
+        {128, 128, 256, 2, "128x128_w2x2"},
+        {256, 256, 512, 4, "256x256_w2x4"},
+        {64, 512, 512, 8, "panel64x512_w1x8_splitbf16"},   // persistent narrow-K kernel, fp32 operands
     };
     return t[id];
 }

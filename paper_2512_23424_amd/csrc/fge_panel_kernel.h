@@ -37,6 +37,9 @@ __device__ __forceinline__ void mfma_bf16(const u32x4 &a, const u32x4 &b, floatx
                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+#ifndef PANEL_JOINT
+#define PANEL_JOINT false
+#endif
 struct PanelShape {
     static constexpr int BM = 64, BN = 512, WAVES_N = 8, MB = 2, NB = 2, KMAX = 64;
     static constexpr int THREADS = 64 * WAVES_N;
@@ -51,10 +54,10 @@ void panel_kernel(const TileArgs a) {
     constexpr int XROWB = 256;                        // LDS bytes per X row: 64 fp32
     constexpr int XTILE = BM * XROWB;                 // 16 KB
     constexpr int X_LD = BM * 16 / NT;                // 16-byte chunks per thread per tile (2)
-    using Epi = TileEpilogue<OutT, NB, WAVES_N, BN, 16, true>;
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, PANEL_JOINT, true>;
 
     __shared__ __attribute__((aligned(16))) unsigned char xs[2 * XTILE];
-    __shared__ __attribute__((aligned(16))) float red[2 * BM * WAVES_N];
+    __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];
     __shared__ __attribute__((aligned(16))) float patches[(NT / 64) * Epi::PATCH_FLOATS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -123,7 +126,7 @@ void panel_kernel(const TileArgs a) {
             for (int c = 0; c < 2; ++c)
                 fa_off[i][t][c] = (i * 32 + l32) * XROWB + (((4 * t + 2 * h + c) ^ (l32 & 15)) << 4);
 
-    Epi epi(a, out, red, patches + wave * Epi::PATCH_FLOATS, BM, 0, 0, 0, 0, wave_n, lane);
+    Epi epi(a, out, xch, patches + wave * Epi::PATCH_FLOATS, BM, 0, 0, 0, 0, wave_n, lane);
 
     // ---------------- persistent loop over 64-row tiles
     const int ntiles = a.tiles_m;
@@ -170,7 +173,7 @@ void panel_kernel(const TileArgs a) {
         }
         // the epilogue waits for the copy of the next tile before it queues its stores
         epi.m0 = tile * BM;
-        static_for<0, MB>([&]<int i>() __attribute__((always_inline)) { epi.block(acc[i], i * 32); });
+        epi.tile(acc, 0);
     }
 }
 

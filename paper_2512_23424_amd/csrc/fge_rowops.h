@@ -16,7 +16,7 @@ struct RowArgs {
     int64_t ldo, bso;
     float lo, hi, eps;
     int act, norm;
-    int tiles_n, bn;            // finish only: column tiles per row and their width
+    int tiles_n, bn;            // finish only: column strips per row and their width
 };
 
 // K2: A = act(Y), elementwise, 16 bytes per lane per step.
@@ -167,12 +167,13 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
     store_row();
 }
 
-// Second pass of the fused path for rows split over `tiles_n` column tiles of width `bn`.
-// Lane t merges tile t's statistics; the row parked in `out` by the tile kernel is then
-// finished in place.  Merge rules:
-//   softmax / logsumexp: m = max_t m_t, s = sum_t s_t exp(m_t - m); parked e_t*exp(m_t - m)/s
+// Second pass of the fused path for rows split over several column strips.  The tile kernel
+// left one pair per (row, strip) in the workspace - `tiles_n` strips of `bn` columns per row -
+// and the row itself parked in `out`; this kernel merges the pairs and finishes the row in
+// place.  One wavefront per row.  Merge rules:
+//   softmax / logsumexp: m = max_t m_t, s = sum_t s_t exp(m_t - m); parked e_t * exp(m_t - m)/s
 //   layernorm: mean = sum_t n_t mean_t / N, M2 = sum_t (M2_t + n_t (mean_t - mean)^2)
-//   rmsnorm:   sum of the per-tile sums of squares
+//   rmsnorm:   sum of the per-strip sums of squares
 template <typename T>
 __global__ __launch_bounds__(256) void finish_kernel(const RowArgs a) {
     constexpr int CW = Store<T>::CW;
@@ -181,43 +182,48 @@ __global__ __launch_bounds__(256) void finish_kernel(const RowArgs a) {
     if (rowg >= (int64_t)a.batch * a.M) return;           // wave-uniform
     T *out = reinterpret_cast<T *>(a.out) + (rowg / a.M) * a.bso + (rowg % a.M) * a.ldo;
     const int cpr = a.N / CW;
-    const bool has = lane < a.tiles_n;
-    const float2 st = has ? a.ws[rowg * a.tiles_n + lane] : make_float2(0.f, 0.f);
-    const float nt = has ? (float)min(a.bn, a.N - lane * a.bn) : 0.0f;
+    const int S = a.tiles_n, SW = a.bn;
+    const float2 *wr = a.ws + rowg * S;
     const float inv_n = 1.0f / (float)a.N;
 
     if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
-        const float m = allreduce64<OpMax>(has ? st.x : OpMax::ident());
-        const float w = has ? fast_exp(st.x - m) : 0.0f;
-        const float s = allreduce64<OpSum>(st.y * w);
+        float m = OpMax::ident();
+        for (int t = lane; t < S; t += 64) m = fmaxf(m, wr[t].x);
+        m = allreduce64<OpMax>(m);
+        float s = 0.0f;
+        for (int t = lane; t < S; t += 64) s += wr[t].y * fast_exp(wr[t].x - m);
+        s = allreduce64<OpSum>(s);
         if (a.norm == FGE_NORM_LOGSUMEXP) {
             if (lane == 0) a.aux[rowg] = m + __logf(s);
             return;
         }
-        const float fac = w * fast_rcp(s);
-        for (int q0 = 0; q0 < cpr; q0 += 64) {             // wave-uniform trip count: the
-            const int q = q0 + lane;                        // shuffle runs with all lanes active
-            const bool okq = q < cpr;
-            const float f = __shfl(fac, okq ? (q * CW) / a.bn : 0, 64);
-            if (okq) {
-                float v[CW];
-                Store<T>::unpack(*reinterpret_cast<const uint4 *>(out + (int64_t)q * CW), v);
+        const float inv = fast_rcp(s);
+        for (int q = lane; q < cpr; q += 64) {
+            const float f = fast_exp(wr[(q * CW) / SW].x - m) * inv;
+            float v[CW];
+            Store<T>::unpack(*reinterpret_cast<const uint4 *>(out + (int64_t)q * CW), v);
 #pragma unroll
-                for (int e = 0; e < CW; ++e) v[e] *= f;
-                *reinterpret_cast<uint4 *>(out + (int64_t)q * CW) = Store<T>::pack(v);
-            }
+            for (int e = 0; e < CW; ++e) v[e] *= f;
+            *reinterpret_cast<uint4 *>(out + (int64_t)q * CW) = Store<T>::pack(v);
         }
         return;
     }
     float scale, shift;
     if (a.norm == FGE_NORM_LAYERNORM) {
-        shift = allreduce64<OpSum>(nt * st.x) * inv_n;
-        const float d = st.x - shift;
-        const float m2 = allreduce64<OpSum>(has ? st.y + nt * d * d : 0.0f);
-        scale = rsqrtf(m2 * inv_n + a.eps);
+        float sm = 0.0f;
+        for (int t = lane; t < S; t += 64) sm += (float)max(0, min(SW, a.N - t * SW)) * wr[t].x;
+        shift = allreduce64<OpSum>(sm) * inv_n;
+        float m2 = 0.0f;
+        for (int t = lane; t < S; t += 64) {
+            const float d = wr[t].x - shift;
+            m2 += wr[t].y + (float)max(0, min(SW, a.N - t * SW)) * d * d;
+        }
+        scale = rsqrtf(allreduce64<OpSum>(m2) * inv_n + a.eps);
     } else {
+        float ss = 0.0f;
+        for (int t = lane; t < S; t += 64) ss += wr[t].x;
         shift = 0.0f;
-        scale = rsqrtf(allreduce64<OpSum>(st.x) * inv_n + a.eps);
+        scale = rsqrtf(allreduce64<OpSum>(ss) * inv_n + a.eps);
     }
     const bool use_beta = a.norm == FGE_NORM_LAYERNORM && a.beta != nullptr;
     for (int q = lane; q < cpr; q += 64) {

@@ -80,7 +80,7 @@ void tile_kernel(const TileArgs a) {
     constexpr int STAGE = (BM + BN) * ROWB;
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
-    __shared__ __attribute__((aligned(16))) float red[2 * BM * WAVES_N];
+    __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
@@ -236,16 +236,15 @@ void tile_kernel(const TileArgs a) {
     compute_last(kt & 1);
     if constexpr (WAVES_M * WAVES_N > 1) __syncthreads();
 
-    // ---------------- epilogue, one 32-row accumulator block at a time, so that only one
-    // block's values are live in the vector registers.  The store patch lives in the panel
-    // memory, free once the mainloop's last fragment reads are behind the barrier above.
-    using Epi = TileEpilogue<OutT, NB, WAVES_N, BN, 32, false>;
+    // ---------------- epilogue.  The store patches live in the panel memory, free once the
+    // mainloop's last fragment reads are behind the barrier above.  The 64-row tiles are the
+    // ones chosen to span N; they take the joint form (one exchange per tile).
+    constexpr bool JOINT = BM == 64;
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 32, JOINT, false>;
     static_assert(WAVES_M * WAVES_N * Epi::PATCH_FLOATS * 4 <= 2 * STAGE, "store patches fit the panels");
-    Epi epi(a, out, red, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, BM, z, m0, n0, tn,
+    Epi epi(a, out, xch, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, BM, z, m0, n0, tn,
             wave_n, lane);
-    static_for<0, MB>([&]<int i>() __attribute__((always_inline)) {
-        epi.block(acc[i], wave_m * WTM + i * 32);
-    });
+    epi.tile(acc, wave_m * WTM);
 }
 
 }  // namespace fge

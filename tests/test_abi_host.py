@@ -71,7 +71,7 @@ def test_argument_errors_are_reported_before_any_launch():
     # split rows need a workspace
     p = _params(M=4096, N=1024, K=1024, ldx=1024, ldw=1024, ldo=1024)
     need = B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p))
-    assert need == 4096 * 8 * 8
+    assert need == 4096 * (8 * 2) * 8          # 8 column tiles x 2 waves across = 16 strips per row
     assert _call(p, act=2, norm=2) == 6
     p.workspace, p.workspace_bytes = FAKE, need - 1
     assert _call(p, act=2, norm=2) == 6

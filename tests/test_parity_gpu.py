@@ -128,7 +128,8 @@ def test_mixed_dtypes_and_no_optional_vectors():
 
 
 def test_edge_shapes():
-    for (M, K, N) in [(1, 8, 8), (1, 64, 512), (63, 8, 72), (65, 40, 64), (257, 264, 264)]:
+    for (M, K, N) in [(1, 8, 8), (1, 64, 512), (63, 8, 72), (65, 40, 64), (257, 264, 264), (33, 16, 68),
+                      (130, 72, 260), (5000, 24, 132)]:
         w = I.scaled(WL["cfg2"], M=M, K=K, N=N)
         _parity(w, "fused", label=f"edge {M}x{K}x{N}")
         _parity(w, "unfused", label=f"edge-unfused {M}x{K}x{N}")
