@@ -77,12 +77,16 @@ int pick_tile(const Problem &pr, int in_dtype, int norm) {
         if (pr.N <= 512) return TILE_64x512;
     }
     // Otherwise the largest tile that still gives every CU at least one workgroup.  fp32 is
-    // bound by the MFMA rate, not by operand traffic, so it stops at 128x128.
-    const int order[3] = {TILE_256x256, TILE_128x128, TILE_64x64};
-    for (int t = (in_dtype == FGE_BF16 ? 0 : 1); t < 3; ++t) {
+    // bound by the MFMA rate, not by operand traffic: it takes 64x128 tiles, two or three of
+    // which share a CU so that one's epilogue hides behind another's MFMAs.
+    const int bf16_order[3] = {TILE_256x256, TILE_128x128, TILE_64x64};
+    const int f32_order[2] = {TILE_64x128, TILE_64x64};
+    const int *order = in_dtype == FGE_BF16 ? bf16_order : f32_order;
+    const int n_order = in_dtype == FGE_BF16 ? 3 : 2;
+    for (int t = 0; t < n_order; ++t) {
         const TileInfo &ti = tile_info(order[t]);
         const int64_t n = (int64_t)((pr.M + ti.bm - 1) / ti.bm) * ((pr.N + ti.bn - 1) / ti.bn) * pr.batch;
-        if (n >= NUM_CU || order[t] == TILE_64x64) return order[t];
+        if (n >= NUM_CU || t == n_order - 1) return order[t];
     }
     return TILE_64x64;
 }

@@ -18,6 +18,21 @@ struct bf16_t { uint16_t bits; };   // storage only; arithmetic is always fp32
 __device__ __forceinline__ float as_f32(uint32_t v) { return __builtin_bit_cast(float, v); }
 __device__ __forceinline__ uint32_t as_u32(float v) { return __builtin_bit_cast(uint32_t, v); }
 
+// ---------------------------------------------------------------- asynchronous global -> LDS copy
+// One 16-byte element per lane: lane l's data lands at lds_base + 16*l, lds_base being uniform
+// over the wave.  Completion is tracked by the wave's vector-memory counter only; callers wait
+// with lds_dma_wait() and then synchronise the workgroup before anyone reads the data.
+// Written in assembly on purpose: for the builtin form the compiler assumes that every later
+// LDS read may alias the copy and drains the vector-memory counter in front of it, which turns
+// a prefetch into a synchronous load.  m0 is not used by any compiler-generated code of these
+// kernels (no other LDS-direct, GWS or indexed-register instruction is emitted).
+__device__ __forceinline__ void lds_dma16(const void *g, void *lds_base) {
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds), "v"(g) : "memory");
+}
+__device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // ---------------------------------------------------------------- storage conversion
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
     return __builtin_bit_cast(float, (uint32_t)b << 16);

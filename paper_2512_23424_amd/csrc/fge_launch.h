@@ -4,7 +4,7 @@
 
 namespace fge {
 
-enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_COUNT = 5 };
+enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_64x128 = 5, TILE_COUNT = 6 };
 
 struct TileInfo { int bm, bn, threads, waves_n; const char *name; };
 
@@ -15,6 +15,7 @@ inline const TileInfo &tile_info(int id) {
         {128, 128, 256, 2, "128x128_w2x2"},
         {256, 256, 512, 4, "256x256_w2x4"},
         {64, 512, 512, 8, "panel64x512_w1x8_splitbf16"},   // persistent narrow-K kernel, fp32 operands
+        {64, 128, 256, 2, "64x128_w2x2"},
     };
     return t[id];
 }
@@ -41,6 +42,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4); break;
     case TILE_128x128: FGE_LAUNCH(128, 128, 2, 2); break;
     case TILE_256x256: FGE_LAUNCH(256, 256, 2, 4); break;
+    case TILE_64x128:  FGE_LAUNCH(64, 128, 2, 2); break;
     default: return hipErrorInvalidValue;
     }
 #undef FGE_LAUNCH

@@ -95,8 +95,6 @@ void panel_kernel(const TileArgs a) {
     // ---------------- X tile copy plan.  LDS image: row-major, 16 chunks of 16 bytes per row,
     // chunk c stored at c ^ (row & 15) so that the 16 rows read by a quarter wave hit all 64
     // banks.  A wave's copy instruction fills 1024 contiguous bytes (4 rows), lane l at +16*l.
-    typedef __attribute__((address_space(1))) const void *gptr_t;
-    typedef __attribute__((address_space(3))) void *lptr_t;
     int x_row[X_LD], x_gc[X_LD];
 #pragma unroll
     for (int i = 0; i < X_LD; ++i) {
@@ -109,11 +107,10 @@ void panel_kernel(const TileArgs a) {
             if (x_gc[i] * 4 < a.K) {
                 const float *g = X + (int64_t)min(m0 + x_row[i], a.M - 1) * a.ldx + x_gc[i] * 4;
                 unsigned char *s = xs + buf * XTILE + (i * (NT / 64) + wave) * 1024;
-                __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)s, 16, 0, 0);
+                lds_dma16(g, s);
             }
         }
     };
-    auto wait_vm = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     // A fragment (i, t): row i*32 + l32, k = 16t + 8h .. +7 = chunks 4t + 2h and 4t + 2h + 1
     // (every wave needs all 64 rows; the split of a fragment is recomputed per wave)
@@ -133,7 +130,7 @@ void panel_kernel(const TileArgs a) {
     int tile = blockIdx.x;
     __syncthreads();                                  // zero fill is complete
     if (tile < ntiles) dma_x(0, tile * BM);
-    wait_vm();
+    lds_dma_wait();
     for (int it = 0; tile < ntiles; tile += gridDim.x, ++it) {
         const int buf = it & 1;
         __syncthreads();    // tile `it` has landed for every wave; reads of the other buffer are over

@@ -116,17 +116,17 @@ void tile_kernel(const TileArgs a) {
 
     // full tile: asynchronous global -> LDS, no registers involved; completion is tracked by
     // the vector-memory counter (wait for it, then barrier, before anyone reads the tile)
-    typedef __attribute__((address_space(1))) const void *gptr_t;
-    typedef __attribute__((address_space(3))) void *lptr_t;
     const int wave_soff = (tid >> 6) * 8 * ROWB;      // first byte of this wave's 8 rows
-    auto dma_tile = [&](int buf, int k0) __attribute__((always_inline)) {
+    constexpr int NS = A_LD + B_LD;                  // copy instructions per thread per tile
+    static_assert(NS % 2 == 0, "copies are issued in two halves");
+    auto dma_chunk = [&](int buf, int k0, int w) __attribute__((always_inline)) {
         unsigned char *sA = smem + buf * STAGE + wave_soff, *sB = sA + BM * ROWB;
+        if (w < A_LD) lds_dma16(gA[w] + k0, sA + w * RSTEP * ROWB);
+        else          lds_dma16(gB[w - A_LD] + k0, sB + (w - A_LD) * RSTEP * ROWB);
+    };
+    auto dma_tile = [&](int buf, int k0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < A_LD; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(gA[i] + k0), (lptr_t)(sA + i * RSTEP * ROWB), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(gB[i] + k0), (lptr_t)(sB + i * RSTEP * ROWB), 16, 0, 0);
+        for (int w = 0; w < NS; ++w) dma_chunk(buf, k0, w);
     };
     // partial last tile: through registers, zero filled past K
     auto stage_tail = [&](int buf, int k0) __attribute__((always_inline)) {
@@ -145,7 +145,6 @@ void tile_kernel(const TileArgs a) {
             *reinterpret_cast<u32x4 *>(sB + i * RSTEP * ROWB) = v;
         }
     };
-    auto wait_dma = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     // ---------------- fragment read plan
     const int fa_row = wave_m * WTM + l32, fb_row = wave_n * WTN + l32;
@@ -180,13 +179,22 @@ void tile_kernel(const TileArgs a) {
     auto slot = [&](int s) __attribute__((always_inline)) { return s == 0 ? 0 : (s <= NB ? MB + s - 1 : s - NB); };
     constexpr int RSPAN = NR < NM ? NR : NM;          // reads ride behind the first RSPAN MFMAs
     // one k-step: MFMAs of step t on fragment set t&1; behind MFMA m: reads of (rbuf, t+1)
-    auto kstep = [&](int t, bool do_read, int rbuf) __attribute__((always_inline)) {
+    // dma_part: 0 none, 1 / 2: first / second half of the copy instructions of the tile at
+    // (dbuf, dk0), one behind each of the first MFMAs - a burst of copies would stall the
+    // wave's in-order issue, and with it its MFMAs, on the address unit
+    auto kstep = [&]<int DMA_PART>(int t, bool do_read, int rbuf, bool do_dma, int dbuf, int dk0) __attribute__((always_inline)) {
+        constexpr int HALF = NS / 2;
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             Mma<InT>::run(fr[t & 1][m / NB], fr[t & 1][MB + m % NB], acc[m / NB][m % NB]);
             if (do_read) {
 #pragma unroll
                 for (int s = (m * NR) / RSPAN; s < ((m + 1) * NR) / RSPAN && s < NR; ++s) read_frag(rbuf, t + 1, slot(s));
+            }
+            if constexpr (DMA_PART != 0) {
+#pragma unroll
+                for (int w = (m * HALF) / NM; w < ((m + 1) * HALF) / NM; ++w)
+                    if (do_dma) dma_chunk(dbuf, dk0, (DMA_PART - 1) * HALF + w);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -197,34 +205,35 @@ void tile_kernel(const TileArgs a) {
         __builtin_amdgcn_sched_barrier(0);
     };
     auto compute_last = [&](int buf) __attribute__((always_inline)) {   // fr[0] holds k-step 0
-        kstep(0, true, buf);
-        kstep(1, true, buf);
-        kstep(2, true, buf);
-        kstep(3, false, 0);
+        kstep.template operator()<0>(0, true, buf, false, 0, 0);
+        kstep.template operator()<0>(1, true, buf, false, 0, 0);
+        kstep.template operator()<0>(2, true, buf, false, 0, 0);
+        kstep.template operator()<0>(3, false, 0, false, 0, 0);
     };
     const int KF = a.K / BK;                          // full K tiles
     const bool ragged_k = (a.K % BK) != 0;            // plus one partial tile
-    // Tile kt lives in buffer kt & 1.  Its DMA is issued right after the barrier that ends the
-    // reads of tile kt-2 and is awaited just before the barrier in the middle of tile kt-1, a
-    // full tile of MFMAs later.
-    if (KF > 0) { dma_tile(0, 0); wait_dma(); }
+    // Tile kt lives in buffer kt & 1.  Its copy is issued in two halves - behind the MFMAs of
+    // k-step 3 of tile kt-2 (right after the barrier that ends the reads of that buffer) and of
+    // k-step 0 of tile kt-1 - and is awaited just before the barrier in the middle of tile kt-1.
+    if (KF > 0) { dma_tile(0, 0); lds_dma_wait(); }
     else        stage_tail(0, 0);
     __syncthreads();
-    if (KF > 1) dma_tile(1, BK);
+    if (KF > 1) {
+#pragma unroll
+        for (int w = 0; w < NS / 2; ++w) dma_chunk(1, BK, w);
+    }
     __builtin_amdgcn_sched_barrier(0);
     read_t0(0);
     int kt = 0;
-    for (; kt + 1 < KF; ++kt) {                       // tile kt+1 is a full one, already in flight
+    for (; kt + 1 < KF; ++kt) {                       // tile kt+1 is a full one
         const int buf = kt & 1;
-        kstep(0, true, buf);
-        kstep(1, true, buf);
-        kstep(2, true, buf);
-        wait_dma();                                   // tile kt+1 has landed in buf^1
+        kstep.template operator()<2>(0, true, buf, true, buf ^ 1, (kt + 1) * BK);
+        kstep.template operator()<0>(1, true, buf, false, 0, 0);
+        kstep.template operator()<0>(2, true, buf, false, 0, 0);
+        lds_dma_wait();                                   // tile kt+1 has landed in buf^1
         __syncthreads();                              // ... for every wave; reads of buf are over
         __builtin_amdgcn_sched_barrier(0);
-        if (kt + 2 < KF) dma_tile(buf, (kt + 2) * BK);
-        __builtin_amdgcn_sched_barrier(0);
-        kstep(3, true, buf ^ 1);                      // t+1 == 4 -> fragment set 0, k-step 0
+        kstep.template operator()<1>(3, true, buf ^ 1, kt + 2 < KF, buf, (kt + 2) * BK);   // t+1 == 4 -> k-step 0
     }
     if (KF > 0 && ragged_k) {                         // last full tile, then the partial tile
         compute_last(kt & 1);
