@@ -18,7 +18,9 @@
  *
  * Ownership.  Every pointer except `p` and the returned strings is DEVICE memory owned by
  * the caller.  The library allocates nothing, frees nothing and keeps no pointer after a call
- * returns.  `workspace` is caller-provided device scratch of at least fge_workspace_bytes().
+ * returns; its only state is a launch counter.  `workspace` is caller-provided device scratch
+ * of at least fge_workspace_bytes(); its contents need no initialisation and two launches that
+ * may overlap must not share one.
  *
  * Asynchrony.  Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
  * the default stream) and return; they never synchronise the device.
@@ -33,7 +35,7 @@
  * arithmetic in fp32; bf16 stores round to nearest even).  Any M >= 1, batch >= 1.  K, N
  * >= 1 with K*sizeof(in) and N*sizeof(out) multiples of 16 bytes; ldx, ldw, ldo and the batch
  * strides likewise multiples of 16 bytes; base pointers 16-byte aligned (else FGE_ERR_ALIGN).
- * Row operations need N <= 65536.  out must not alias X or W.
+ * Row operations need N <= 8192.  out must not alias X or W.
  */
 #ifndef FGE_H
 #define FGE_H
@@ -48,7 +50,7 @@ extern "C" {
 typedef enum {
     FGE_OK = 0,
     FGE_ERR_NULL = 1,         /* a required pointer is NULL                                  */
-    FGE_ERR_BAD_ENUM = 2,     /* act / norm / dtype code out of range                        */
+    FGE_ERR_BAD_ENUM = 2,     /* act / norm / dtype code or flag bit out of range            */
     FGE_ERR_BAD_SHAPE = 3,    /* M, N, K, batch <= 0, or a stride smaller than the extent    */
     FGE_ERR_UNSUPPORTED = 4,  /* valid request outside the supported set                     */
     FGE_ERR_ALIGN = 5,        /* pointer or stride not 16-byte aligned                       */
@@ -76,6 +78,14 @@ typedef enum {
     FGE_NORM_LOGSUMEXP = 4
 } fge_norm;
 
+/* fge_params.flags.
+ *   FGE_FLAG_TWO_PASS : always finish split rows with the second kernel.  Without it the tile
+ *   kernel of a large problem finishes its rows itself: the column tiles of a row block run at
+ *   the same time, exchange their row statistics through the workspace and wait for each other
+ *   (a bounded wait).  That form assumes the launch has the device to itself; set this flag when
+ *   several launches may overlap on the device (other streams, other processes). */
+enum { FGE_FLAG_TWO_PASS = 1 };
+
 typedef struct fge_params {
     int32_t M, N, K, batch;        /* rows per problem, columns, contraction length, problems  */
     int64_t ldx, ldw, ldo;         /* row strides in elements (K, K, N when dense)             */
@@ -85,6 +95,7 @@ typedef struct fge_params {
     float   alpha, post_scale;     /* Y = post_scale * (alpha * X.W^T + b)                     */
     float   clamp_lo, clamp_hi;    /* FGE_ACT_CLAMP bounds                                     */
     float   eps;                   /* LAYERNORM / RMSNORM                                      */
+    int32_t flags;                 /* FGE_FLAG_* bits, 0 for the defaults                      */
     const float *gamma, *beta;     /* device, length N; NULL means all ones / all zeros        */
     float  *aux_out;               /* device, batch*M floats; required for LOGSUMEXP only      */
     void   *workspace;             /* device scratch, 16-byte aligned                          */
@@ -92,9 +103,10 @@ typedef struct fge_params {
 } fge_params;
 
 /* The fused path: one tile kernel that keeps the accumulators in registers through scale,
- * bias, activation and the in-tile row reduction, followed - only when a row spans several
- * column tiles - by a light second kernel that merges the per-tile row statistics and
- * finishes the normalisation in place in `out`.  b may be NULL (no bias). */
+ * bias, activation and the in-tile row reduction.  When a row spans several column tiles the
+ * tiles publish mergeable row statistics to the workspace; large problems then finish their
+ * rows inside the same kernel (see FGE_FLAG_TWO_PASS), others with a light second kernel that
+ * merges the statistics and normalises `out` in place.  b may be NULL (no bias). */
 int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
                         const fge_params *p, void *out, void *stream);
 

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libfge.so")
 
 ACT = {"none": 0, "relu": 1, "gelu_tanh": 2, "gelu_erf": 3, "silu": 4, "clamp": 5}
 NORM = {"none": 0, "softmax": 1, "layernorm": 2, "rmsnorm": 3, "logsumexp": 4}
+FLAG_TWO_PASS = 1
 STATUS_OK = 0
 
 
@@ -29,6 +30,7 @@ class FgeParams(ctypes.Structure):
         ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
         ("alpha", ctypes.c_float), ("post_scale", ctypes.c_float),
         ("clamp_lo", ctypes.c_float), ("clamp_hi", ctypes.c_float), ("eps", ctypes.c_float),
+        ("flags", ctypes.c_int32),
         ("gamma", ctypes.c_void_p), ("beta", ctypes.c_void_p), ("aux_out", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
     ]
@@ -104,7 +106,7 @@ def _stream(stream) -> Optional[int]:
 
 def make_params(X: Optional[torch.Tensor], W: Optional[torch.Tensor], out: torch.Tensor, *,
                 alpha: float = 1.0, post_scale: float = 1.0, clamp_lo: float = 0.0,
-                clamp_hi: float = 0.0, eps: float = 0.0,
+                clamp_hi: float = 0.0, eps: float = 0.0, flags: int = 0,
                 gamma: Optional[torch.Tensor] = None, beta: Optional[torch.Tensor] = None,
                 aux_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                 K: Optional[int] = None, in_dtype: Optional[int] = None) -> FgeParams:
@@ -133,6 +135,7 @@ def make_params(X: Optional[torch.Tensor], W: Optional[torch.Tensor], out: torch
     p.out_dtype = _dt(out)
     p.alpha, p.post_scale = alpha, post_scale
     p.clamp_lo, p.clamp_hi, p.eps = clamp_lo, clamp_hi, eps
+    p.flags = flags
     p.gamma, p.beta, p.aux_out = _ptr(gamma), _ptr(beta), _ptr(aux_out)
     p.workspace = _ptr(workspace)
     p.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()

@@ -2,6 +2,9 @@
 // launched), tile selection, workspace layout and the kernel launches on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <chrono>
+
 #include "fge_launch.h"
 #include "fge_rowops.h"
 
@@ -10,6 +13,11 @@ using namespace fge;
 namespace {
 
 thread_local int g_last_hip = 0;
+
+// Launch counter: its value marks "arrived" in the cooperative form, so marks left in a
+// workspace by earlier launches (or by whatever the memory held before) never match.
+std::atomic<unsigned> g_generation{
+    (unsigned)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
 
 constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 CUs
 constexpr int MAX_ROWOP_N = 8192;    // a row must fit the register-resident row kernels
@@ -30,8 +38,12 @@ struct Plan {
     int tile;
     int tiles_m, tiles_n;
     int strips;                  // statistics slots per row: column tiles x waves across a tile
-    bool needs_finish;           // rows split over several column tiles and a row op is requested
-    size_t ws_stats;             // bytes of per-tile statistics (fused)
+    bool split;                  // rows split over several column tiles and a row op is requested
+    bool coop;                   // ... and the tiles finish their rows themselves (one kernel)
+    int coop_grid;               // workgroups of the cooperative launch
+    bool needs_finish;           // ... or a second pass does
+    size_t ws_stats;             // bytes of per-strip statistics (fused)
+    size_t ws_marks;             // bytes of arrival marks + fault word (cooperative form)
     size_t ws_buf;               // bytes of one out-shaped intermediate (unfused)
     int n_bufs;                  // intermediates the unfused path needs
 };
@@ -41,6 +53,7 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
     if (p == nullptr) return FGE_ERR_NULL;
     if (act < FGE_ACT_NONE || act > FGE_ACT_CLAMP) return FGE_ERR_BAD_ENUM;
     if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
+    if (p->flags & ~FGE_FLAG_TWO_PASS) return FGE_ERR_BAD_ENUM;
     if ((p->in_dtype != FGE_F32 && p->in_dtype != FGE_BF16) ||
         (p->out_dtype != FGE_F32 && p->out_dtype != FGE_BF16))
         return FGE_ERR_BAD_ENUM;
@@ -105,9 +118,21 @@ Plan make_plan(const fge_params *p, int norm) {
     const TileInfo &ti = tile_info(pl.tile);
     pl.tiles_m = (pr.M + ti.bm - 1) / ti.bm;
     pl.tiles_n = (pr.N + ti.bn - 1) / ti.bn;
-    pl.needs_finish = norm != FGE_NORM_NONE && pl.tiles_n > 1;
-    pl.strips = pl.tiles_n * ti.waves_n;
-    pl.ws_stats = pl.needs_finish ? round256((size_t)pr.M * pr.batch * pl.strips * sizeof(float2)) : 0;
+    pl.split = norm != FGE_NORM_NONE && pl.tiles_n > 1;
+    // cooperative form: the column tiles of a row block must all be in flight at once, so the
+    // grid is a whole number of row blocks that fits the chip
+    const int capacity = NUM_CU * ti.coop_per_cu;
+    pl.coop = pl.split && !(p->flags & FGE_FLAG_TWO_PASS) && tile_has_coop(pl.tile, p->in_dtype) && capacity >= pl.tiles_n;
+    if (pl.coop) {
+        const int64_t total = (int64_t)pl.tiles_m * pl.tiles_n * pr.batch;
+        const int64_t g = (int64_t)(capacity / pl.tiles_n) * pl.tiles_n;
+        pl.coop_grid = (int)(total < g ? total : g);
+    }
+    pl.needs_finish = pl.split && !pl.coop;
+    // pairs per row: one per wave strip for the second pass, one per tile in the cooperative form
+    pl.strips = pl.coop ? pl.tiles_n : pl.tiles_n * ti.waves_n;
+    pl.ws_stats = pl.split ? round256((size_t)pr.M * pr.batch * pl.strips * sizeof(float2)) : 0;
+    pl.ws_marks = pl.coop ? round256((size_t)pl.tiles_m * pr.batch * pl.tiles_n * sizeof(unsigned)) + 256 : 0;
     const size_t extent = (size_t)(pr.batch - 1) * pr.bso + (size_t)(pr.M - 1) * pr.ldo + pr.N;
     pl.ws_buf = round256(extent * esize(p->out_dtype));
     // K2 writes straight into `out` when the row op leaves the activated values in place
@@ -130,8 +155,16 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
     a.ldx = pl.pr.ldx; a.ldw = pl.pr.ldw; a.ldo = pl.pr.ldo; a.bsx = pl.pr.bsx; a.bso = pl.pr.bso;
     a.alpha = p->alpha; a.post = p->post_scale; a.lo = p->clamp_lo; a.hi = p->clamp_hi; a.eps = p->eps;
     a.act = act; a.norm = norm;
-    a.tiles_m = pl.tiles_m; a.tiles_n = pl.tiles_n;
+    a.tiles_m = pl.tiles_m; a.tiles_n = pl.tiles_n; a.batch = pl.pr.batch;
     a.group_m = pl.tiles_m < 8 ? pl.tiles_m : 8;
+    a.coop = 0;
+    if (pl.coop && norm != FGE_NORM_NONE) {
+        char *base = static_cast<char *>(p->workspace) + pl.ws_stats;
+        a.coop = 1;
+        a.gen = g_generation.fetch_add(1) + 1;
+        a.arrive = reinterpret_cast<unsigned *>(base);
+        a.fault = reinterpret_cast<int *>(base + pl.ws_marks - 256);
+    }
     return a;
 }
 
@@ -140,7 +173,8 @@ int launch_tiles(const TileArgs &a, const fge_params *p, const Plan &pl, hipStre
         const dim3 pgrid((unsigned)(pl.tiles_m < NUM_CU ? pl.tiles_m : NUM_CU));
         return hip_status(launch_panel_f32(p->out_dtype, pgrid, s, a));
     }
-    const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n), 1, (unsigned)pl.pr.batch);
+    const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
+                    a.coop ? 1u : (unsigned)pl.pr.batch);
     const hipError_t e = p->in_dtype == FGE_BF16 ? launch_tile_bf16(pl.tile, p->out_dtype, grid, s, a)
                                                  : launch_tile_f32(pl.tile, p->out_dtype, grid, s, a);
     return hip_status(e);
@@ -179,9 +213,9 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
     if (!aligned16(X) || !aligned16(W) || !aligned16(out) || !aligned16(b)) return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
     const Plan pl = make_plan(p, norm);
-    if (pl.needs_finish) {
+    if (pl.split) {
         if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
-        if (!p->workspace || p->workspace_bytes < pl.ws_stats) return FGE_ERR_WORKSPACE;
+        if (!p->workspace || p->workspace_bytes < pl.ws_stats + pl.ws_marks) return FGE_ERR_WORKSPACE;
     }
     if (plan_out) *plan_out = pl;
     return launch_tiles(tile_args(X, W, b, act, norm, p, pl, out), p, pl, s);
@@ -305,14 +339,14 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return (size_t)-1;
     const Plan pl = make_plan(p, norm);
-    return fused ? pl.ws_stats : pl.ws_buf * pl.n_bufs;
+    return fused ? pl.ws_stats + pl.ws_marks : pl.ws_buf * pl.n_bufs;
 }
 
 const char *fge_status_string(int status) {
     switch (status) {
     case FGE_OK:              return "ok";
     case FGE_ERR_NULL:        return "a required pointer is NULL";
-    case FGE_ERR_BAD_ENUM:    return "activation, row-op or dtype code out of range";
+    case FGE_ERR_BAD_ENUM:    return "activation, row-op, dtype or flag code out of range";
     case FGE_ERR_BAD_SHAPE:   return "non-positive extent or stride smaller than the extent";
     case FGE_ERR_UNSUPPORTED: return "valid request outside the supported set";
     case FGE_ERR_ALIGN:       return "pointer or stride not 16-byte aligned";

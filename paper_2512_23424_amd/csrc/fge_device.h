@@ -41,6 +41,13 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
     return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));
 }
+// two at once (one conversion instruction): lo in bits 0-15, hi in bits 16-31
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
 template <typename T> struct Store;
 template <> struct Store<float> {
@@ -73,7 +80,7 @@ template <> struct Store<bf16_t> {
         uint32_t w[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+            w[i] = f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
         return make_uint4(w[0], w[1], w[2], w[3]);
     }
 };

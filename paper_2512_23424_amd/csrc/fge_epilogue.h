@@ -32,7 +32,13 @@ struct TileArgs {
     int64_t ldx, ldw, ldo, bsx, bso;
     float alpha, post, lo, hi, eps;
     int act, norm;
-    int tiles_m, tiles_n, group_m;
+    int tiles_m, tiles_n, group_m, batch;
+    // cooperative completion of split rows (coop != 0): persistent grid, the column tiles of a
+    // row block run in the same round and finish their rows themselves
+    int coop;
+    unsigned gen;               // value that marks "arrived" in this launch
+    unsigned *arrive;           // [batch * tiles_m][tiles_n] arrival marks
+    int *fault;                 // set to 1 if a wait ran out (result then invalid)
 };
 
 // OutT: storage type of out.  MB x NB: 32x32 accumulator blocks per wave.  WAVES_N: waves
@@ -41,8 +47,9 @@ struct TileArgs {
 // tiles that span N) instead of one per block (less register pressure; split rows never
 // exchange anyway).  WAIT_VM: drain the wave's vector-memory counter before the first global
 // store of a group (for callers with asynchronous global->LDS loads in flight that want them
-// accounted for before stores are queued behind them).
-template <typename OutT, int MB, int NB, int WAVES_N, int PATCH_ROWS, bool JOINT, bool WAIT_VM>
+// accounted for before stores are queued behind them).  COOP: the cooperative form only - rows
+// are split over column tiles that are all in flight and finish their rows themselves.
+template <typename OutT, int MB, int NB, int WAVES_N, int PATCH_ROWS, bool JOINT, bool WAIT_VM, bool COOP = false>
 struct TileEpilogue {
     static constexpr int WTN = NB * 32;               // columns of a wave strip
     static constexpr int SSTR = WTN + 8;              // floats per patch row: +8 puts lanes 0-31
@@ -113,11 +120,28 @@ struct TileEpilogue {
             for (int r = 0; r < 16; ++r) blk[j][r] = activate<ACT>(scale * blk[j][r] + bias[j], a.lo, a.hi);
     }
 
-    // Publish the strip pair of pass q for the second pass.
+    // Publish the strip pair of pass q: to the workspace for the second pass, or (cooperative
+    // form) to LDS, where the tile's strips are merged before anything leaves the workgroup.
     __device__ __forceinline__ void put_stats(int grow0, int q, float s0, float s1) {
-        const int grow = m0 + qrow(grow0, q);
-        if (sub == 0 && grow < a.M)
-            a.ws[(row_base + grow) * (a.tiles_n * WAVES_N) + tn * WAVES_N + wave_n] = make_float2(s0, s1);
+        if constexpr (COOP) {
+            if (sub == 0) xch[qrow(grow0, q) * WAVES_N + wave_n] = make_float2(s0, s1);
+        } else {
+            const int grow = m0 + qrow(grow0, q);
+            if (sub == 0 && grow < a.M)
+                a.ws[(row_base + grow) * (a.tiles_n * WAVES_N) + tn * WAVES_N + wave_n] = make_float2(s0, s1);
+        }
+    }
+    // Cooperative form: the pairs travel between workgroups of one launch, possibly on different
+    // XCDs with separate L2s.  Both sides use device-scope atomic accesses (which go to the
+    // device-coherent level), so no cache-wide write-back or invalidate is needed.
+    static __device__ __forceinline__ void put_pair(float2 *slot, float s0, float s1) {
+        const uint64_t bits = (uint64_t)as_u32(s0) | ((uint64_t)as_u32(s1) << 32);
+        __hip_atomic_store(reinterpret_cast<uint64_t *>(slot), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    static __device__ __forceinline__ float2 get_pair(const float2 *slot) {
+        const uint64_t bits = __hip_atomic_load(reinterpret_cast<const uint64_t *>(slot), __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+        return make_float2(as_f32((uint32_t)bits), as_f32((uint32_t)(bits >> 32)));
     }
     // Whole rows: every strip's pair of every row of the group meets in LDS; afterwards lane
     // `sub` of a row segment holds the pair of strip `sub` (identity beyond WAVES_N).  The two
@@ -262,9 +286,8 @@ struct TileEpilogue {
         }
     }
 
-    // activation (accumulator layout) -> LDS patch -> row-wise layout, for block B of a group
-    template <int B> __device__ __forceinline__ void to_rows(floatx16 (&blk)[NB], float (&v)[NPG][VEC]) {
-        dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) { act_block<ACT>(blk); });
+    // accumulator layout -> LDS patch -> row-wise layout, for block B of a group
+    template <int B> __device__ __forceinline__ void transpose_block(floatx16 (&blk)[NB], float (&v)[NPG][VEC]) {
 #pragma unroll
         for (int half = 0; half < 32 / PATCH_ROWS; ++half) {
 #pragma unroll
@@ -286,35 +309,243 @@ struct TileEpilogue {
                 }
         }
     }
+    // activation in place (accumulator layout), then the transpose
+    template <int B> __device__ __forceinline__ void to_rows(floatx16 (&blk)[NB], float (&v)[NPG][VEC]) {
+        dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) { act_block<ACT>(blk); });
+        transpose_block<B>(blk, v);
+    }
 
-    // the whole epilogue of a wave's MB blocks; trow0 = tile row of the wave's first row
-    __device__ __forceinline__ void tile(floatx16 (&acc)[MB][NB], int trow0) {
-        static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
-            float v[NPG][VEC];
-            static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
-            const int grow0 = trow0 + g * G * 32;
-            switch (a.norm) {
-            case FGE_NORM_NONE:      break;
-            case FGE_NORM_SOFTMAX:   norm_group<FGE_NORM_SOFTMAX>(v, grow0); break;
-            case FGE_NORM_LOGSUMEXP: norm_group<FGE_NORM_LOGSUMEXP>(v, grow0); break;
-            case FGE_NORM_LAYERNORM: norm_group<FGE_NORM_LAYERNORM>(v, grow0); break;
-            default:                 norm_group<FGE_NORM_RMSNORM>(v, grow0); break;
-            }
-            if constexpr (WAIT_VM) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __device__ __forceinline__ void store_group(float (&v)[NPG][VEC], int grow0) {
 #pragma unroll
-            for (int q = 0; q < NPG; ++q) {
-                const int grow = m0 + qrow(grow0, q);
-                if (grow < a.M) {
-                    OutT *o = out + (int64_t)grow * a.ldo + gcol;
-                    if constexpr (sizeof(OutT) == 2) {     // N is a multiple of 8: all or nothing
-                        if (ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
-                    } else {
-                        if (ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
-                        if (ok4[1]) *reinterpret_cast<uint4 *>(o + G4STEP) = Store<OutT>::pack(v[q] + 4);
-                    }
+        for (int q = 0; q < NPG; ++q) {
+            const int grow = m0 + qrow(grow0, q);
+            if (grow < a.M) {
+                OutT *o = out + (int64_t)grow * a.ldo + gcol;
+                if constexpr (sizeof(OutT) == 2) {     // N is a multiple of 8: all or nothing
+                    if (ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
+                } else {
+                    if (ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
+                    if (ok4[1]) *reinterpret_cast<uint4 *>(o + G4STEP) = Store<OutT>::pack(v[q] + 4);
                 }
             }
-        });
+        }
+    }
+
+    // ---------------------------------------------------------------- cooperative completion
+    // Rows split over column tiles whose workgroups are all in flight.  Per tile:
+    //   1. every wave activates its blocks in place and leaves its strip pairs in LDS;
+    //   2. one thread per row merges the tile's strips and publishes one pair per (row, tile);
+    //   3. the workgroup marks its tile as arrived and waits for the other tiles of the row block;
+    //   4. NT / tile_rows threads per row merge the pairs of all tiles into the final row
+    //      statistics, which go to LDS;
+    //   5. every wave normalises its blocks - still in the accumulators - and stores them.
+    // Merging pairs: (m, s): m = max, s = sum s_i exp(m_i - m);  (mean, M2) with counts n_i:
+    // mean = sum n_i mean_i / n, M2 = sum M2_i + n_i (mean_i - mean)^2;  (sum of squares, -): sum.
+
+    // step 2: tile row `row` (one thread each)
+    __device__ __forceinline__ void merge_strips(int row) {
+        float2 e[WAVES_N];
+#pragma unroll
+        for (int w = 0; w < WAVES_N; ++w) e[w] = xch[row * WAVES_N + w];
+        float o0, o1 = 0.0f;
+        if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
+            o0 = e[0].x;
+#pragma unroll
+            for (int w = 1; w < WAVES_N; ++w) o0 = fmaxf(o0, e[w].x);
+#pragma unroll
+            for (int w = 0; w < WAVES_N; ++w) o1 += e[w].y * fast_exp(e[w].x - o0);   // empty strips: 0 * exp(-inf)
+        } else if (a.norm == FGE_NORM_LAYERNORM) {
+            const int nt = max(1, min(WAVES_N * WTN, a.N - n0));
+            float sm = 0.0f;
+#pragma unroll
+            for (int w = 0; w < WAVES_N; ++w) sm += (float)strip_cols(w) * e[w].x;
+            o0 = sm / (float)nt;
+#pragma unroll
+            for (int w = 0; w < WAVES_N; ++w) {
+                const float d = e[w].x - o0;
+                o1 += e[w].y + (float)strip_cols(w) * d * d;
+            }
+        } else {
+            o0 = 0.0f;
+#pragma unroll
+            for (int w = 0; w < WAVES_N; ++w) o0 += e[w].x;
+        }
+        if (m0 + row < a.M) put_pair(a.ws + (row_base + m0 + row) * a.tiles_n + tn, o0, o1);
+    }
+
+    // step 3.  Only correct when all tiles of the row block are in flight at once (the caller's
+    // persistent grid guarantees it); the wait is bounded all the same, and a wait that runs
+    // out raises the fault flag instead of hanging.
+    __device__ __forceinline__ void arrive_and_wait(int rowblock, int tid) {
+        // the pair stores are device-scope atomics: once the store counter has drained they are
+        // visible to the whole device, and the barrier orders every wave's drain before the mark
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        unsigned *marks = a.arrive + (int64_t)rowblock * a.tiles_n;
+        if (tid == 0) __hip_atomic_store(marks + tn, a.gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid < 64) {
+            bool ok = true;
+            for (int t = tid; t < a.tiles_n; t += 64) {
+                int spins = 0;
+                while (__hip_atomic_load(marks + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.gen) {
+                    __builtin_amdgcn_s_sleep(8);
+                    if (++spins > (1 << 20)) { ok = false; break; }
+                }
+            }
+            if (!ok) *a.fault = 1;
+        }
+        __syncthreads();                                        // pairs are read with device-scope loads
+    }
+
+    // step 4: TPR neighbouring threads per tile row; the result lands in fin[row]:
+    // (m, 1/s) softmax, (mean, rstd) LayerNorm, (rstd, -) RMSNorm; logsumexp writes aux.
+    template <int TPR> __device__ __forceinline__ void merge_tiles(int tid, float2 *fin) {
+        const int row = tid / TPR, part = tid % TPR;
+        const int grow = m0 + row;
+        const float2 *pr = a.ws + (row_base + min(grow, a.M - 1)) * a.tiles_n;
+        const int BN_ = WAVES_N * WTN;
+        constexpr int CH = 8;                 // pairs fetched together (independent loads in flight)
+        float o0, o1 = 0.0f;
+        if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
+            float m = OpMax::ident(), sum = 0.0f;
+            for (int t0 = part; t0 < a.tiles_n; t0 += CH * TPR) {
+                float2 e[CH];
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    e[i] = t0 + i * TPR < a.tiles_n ? get_pair(pr + t0 + i * TPR) : make_float2(OpMax::ident(), 0.0f);
+                float mc = e[0].x;
+#pragma unroll
+                for (int i = 1; i < CH; ++i) mc = fmaxf(mc, e[i].x);
+                const float mn = fmaxf(m, mc);            // finite: slot t0 exists and every tile has columns
+                sum *= fast_exp(m - mn);
+#pragma unroll
+                for (int i = 0; i < CH; ++i) sum += e[i].y * fast_exp(e[i].x - mn);
+                m = mn;
+            }
+            o0 = allreduce_lanes<OpMax, TPR>(m);
+            const float sden = allreduce_lanes<OpSum, TPR>(m == OpMax::ident() ? 0.0f : sum * fast_exp(m - o0));
+            if (a.norm == FGE_NORM_SOFTMAX) o1 = fast_rcp(sden);
+            else if (part == 0 && tn == 0 && grow < a.M) a.aux[row_base + grow] = o0 + __logf(sden);
+        } else if (a.norm == FGE_NORM_LAYERNORM) {
+            // two sweeps over the pairs: the mean first, then M2 about it
+            const float inv_n = 1.0f / (float)a.N;
+            float sm = 0.0f;
+            for (int t0 = part; t0 < a.tiles_n; t0 += CH * TPR) {
+                float2 e[CH];
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    e[i] = t0 + i * TPR < a.tiles_n ? get_pair(pr + t0 + i * TPR) : make_float2(0.0f, 0.0f);
+#pragma unroll
+                for (int i = 0; i < CH; ++i) sm += (float)max(0, min(BN_, a.N - (t0 + i * TPR) * BN_)) * e[i].x;
+            }
+            o0 = allreduce_lanes<OpSum, TPR>(sm) * inv_n;
+            float m2 = 0.0f;
+            for (int t0 = part; t0 < a.tiles_n; t0 += CH * TPR) {
+                float2 e[CH];
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    e[i] = t0 + i * TPR < a.tiles_n ? get_pair(pr + t0 + i * TPR) : make_float2(o0, 0.0f);
+#pragma unroll
+                for (int i = 0; i < CH; ++i) {
+                    const float d = e[i].x - o0;
+                    m2 += e[i].y + (float)max(0, min(BN_, a.N - (t0 + i * TPR) * BN_)) * d * d;
+                }
+            }
+            o1 = rsqrtf(allreduce_lanes<OpSum, TPR>(m2) * inv_n + a.eps);
+        } else {
+            float ss = 0.0f;
+            for (int t0 = part; t0 < a.tiles_n; t0 += CH * TPR) {
+                float2 e[CH];
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    e[i] = t0 + i * TPR < a.tiles_n ? get_pair(pr + t0 + i * TPR) : make_float2(0.0f, 0.0f);
+#pragma unroll
+                for (int i = 0; i < CH; ++i) ss += e[i].x;
+            }
+            o0 = rsqrtf(allreduce_lanes<OpSum, TPR>(ss) / (float)a.N + a.eps);
+        }
+        if (part == 0) fin[row] = make_float2(o0, o1);
+    }
+
+    // step 5 for one group
+    template <int NORM> __device__ __forceinline__ void finish_group(float (&v)[NPG][VEC], int grow0, const float2 *fin) {
+        float gam[VEC], bet[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; e += 4) {
+            floatx4 g = {1.0f, 1.0f, 1.0f, 1.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
+            const int c = gcol + (e >> 2) * G4STEP;
+            if (NORM != FGE_NORM_SOFTMAX && ok4[e >> 2] && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + c);
+            if (NORM == FGE_NORM_LAYERNORM && ok4[e >> 2] && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + c);
+            gam[e] = g[0]; gam[e + 1] = g[1]; gam[e + 2] = g[2]; gam[e + 3] = g[3];
+            bet[e] = b[0]; bet[e + 1] = b[1]; bet[e + 2] = b[2]; bet[e + 3] = b[3];
+        }
+#pragma unroll
+        for (int q = 0; q < NPG; ++q) {
+            const float2 r = fin[qrow(grow0, q)];
+            if constexpr (NORM == FGE_NORM_SOFTMAX) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[q][e] = fast_exp(v[q][e] - r.x) * r.y;
+            } else if constexpr (NORM == FGE_NORM_LAYERNORM) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[q][e] = (v[q][e] - r.x) * r.y * gam[e] + bet[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[q][e] *= r.x * gam[e];
+            }
+        }
+    }
+
+    // the whole epilogue of a wave's MB blocks; trow0 = tile row of the wave's first row;
+    // rowblock / tid / NT (threads of the workgroup) are used by the cooperative form only
+    template <int NT>
+    __device__ __forceinline__ void tile(floatx16 (&acc)[MB][NB], int trow0, int rowblock, int tid) {
+        if constexpr (COOP) {
+            // step 1 (logsumexp leaves the activated values as they are: stored right away)
+            static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+                float v[NPG][VEC];
+                static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
+                const int grow0 = trow0 + g * G * 32;
+                switch (a.norm) {
+                case FGE_NORM_SOFTMAX:   norm_group<FGE_NORM_SOFTMAX>(v, grow0); break;
+                case FGE_NORM_LOGSUMEXP: norm_group<FGE_NORM_LOGSUMEXP>(v, grow0); store_group(v, grow0); break;
+                case FGE_NORM_LAYERNORM: norm_group<FGE_NORM_LAYERNORM>(v, grow0); break;
+                default:                 norm_group<FGE_NORM_RMSNORM>(v, grow0); break;
+                }
+            });
+            __syncthreads();
+            if (tid < tile_rows) merge_strips(tid);
+            arrive_and_wait(rowblock, tid);
+            float2 *fin = xch + tile_rows * WAVES_N;
+            merge_tiles<NT / (MB * 32 * (NT / 64 / WAVES_N))>(tid, fin);
+            if (a.norm == FGE_NORM_LOGSUMEXP) return;
+            __syncthreads();
+            static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+                float v[NPG][VEC];
+                static_for<0, G>([&]<int b>() __attribute__((always_inline)) { transpose_block<b>(acc[g * G + b], v); });
+                const int grow0 = trow0 + g * G * 32;
+                switch (a.norm) {
+                case FGE_NORM_SOFTMAX:   finish_group<FGE_NORM_SOFTMAX>(v, grow0, fin); break;
+                case FGE_NORM_LAYERNORM: finish_group<FGE_NORM_LAYERNORM>(v, grow0, fin); break;
+                default:                 finish_group<FGE_NORM_RMSNORM>(v, grow0, fin); break;
+                }
+                store_group(v, grow0);
+            });
+        } else {
+            static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+                float v[NPG][VEC];
+                static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
+                const int grow0 = trow0 + g * G * 32;
+                switch (a.norm) {
+                case FGE_NORM_NONE:      break;
+                case FGE_NORM_SOFTMAX:   norm_group<FGE_NORM_SOFTMAX>(v, grow0); break;
+                case FGE_NORM_LOGSUMEXP: norm_group<FGE_NORM_LOGSUMEXP>(v, grow0); break;
+                case FGE_NORM_LAYERNORM: norm_group<FGE_NORM_LAYERNORM>(v, grow0); break;
+                default:                 norm_group<FGE_NORM_RMSNORM>(v, grow0); break;
+                }
+                if constexpr (WAIT_VM) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                store_group(v, grow0);
+            });
+        }
     }
 };
 

@@ -6,16 +6,19 @@ namespace fge {
 
 enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_64x128 = 5, TILE_COUNT = 6 };
 
-struct TileInfo { int bm, bn, threads, waves_n; const char *name; };
+// coop_per_cu: workgroups of this tile's cooperative kernel that are resident on one CU at the
+// same time (from the compiler's register / LDS report; a lower bound is safe), 0 if the tile
+// has no cooperative kernel.
+struct TileInfo { int bm, bn, threads, waves_n, coop_per_cu; const char *name; };
 
 inline const TileInfo &tile_info(int id) {
     static const TileInfo t[TILE_COUNT] = {
-        {64, 64, 256, 2, "64x64_w2x2"},
-        {64, 512, 256, 4, "64x512_w1x4"},
-        {128, 128, 256, 2, "128x128_w2x2"},
-        {256, 256, 512, 4, "256x256_w2x4"},
-        {64, 512, 512, 8, "panel64x512_w1x8_splitbf16"},   // persistent narrow-K kernel, fp32 operands
-        {64, 128, 256, 2, "64x128_w2x2"},
+        {64, 64, 256, 2, 0, "64x64_w2x2"},
+        {64, 512, 256, 4, 0, "64x512_w1x4"},
+        {128, 128, 256, 2, 1, "128x128_w2x2"},
+        {256, 256, 512, 4, 1, "256x256_w2x4"},
+        {64, 512, 512, 8, 0, "panel64x512_w1x8_splitbf16"},   // persistent narrow-K kernel, fp32 operands
+        {64, 128, 256, 2, 2, "64x128_w2x2"},
     };
     return t[id];
 }
@@ -28,25 +31,39 @@ hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileA
 
 template <typename InT>
 inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
-#define FGE_LAUNCH(BM, BN, WM, WN)                                                              \
+#define FGE_LAUNCH(BM, BN, WM, WN, COOP)                                                        \
     do {                                                                                        \
         if (out_dtype == FGE_BF16)                                                              \
-            hipLaunchKernelGGL((tile_kernel<InT, bf16_t, BM, BN, WM, WN>), grid,                \
+            hipLaunchKernelGGL((tile_kernel<InT, bf16_t, BM, BN, WM, WN, COOP>), grid,          \
                                dim3(64 * WM * WN), 0, s, a);                                    \
         else                                                                                    \
-            hipLaunchKernelGGL((tile_kernel<InT, float, BM, BN, WM, WN>), grid,                 \
+            hipLaunchKernelGGL((tile_kernel<InT, float, BM, BN, WM, WN, COOP>), grid,           \
                                dim3(64 * WM * WN), 0, s, a);                                    \
     } while (0)
+    // the cooperative form exists for the tiles large problems use: bf16 256x256 and 128x128,
+    // fp32 64x128 (tile_has_coop below must agree)
+    constexpr bool BF = sizeof(InT) == 2;
     switch (tile) {
-    case TILE_64x64:   FGE_LAUNCH(64, 64, 2, 2); break;
-    case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4); break;
-    case TILE_128x128: FGE_LAUNCH(128, 128, 2, 2); break;
-    case TILE_256x256: FGE_LAUNCH(256, 256, 2, 4); break;
-    case TILE_64x128:  FGE_LAUNCH(64, 128, 2, 2); break;
+    case TILE_64x64:   FGE_LAUNCH(64, 64, 2, 2, false); break;
+    case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4, false); break;
+    case TILE_128x128:
+        if constexpr (BF) { if (a.coop) { FGE_LAUNCH(128, 128, 2, 2, true); break; } }
+        FGE_LAUNCH(128, 128, 2, 2, false); break;
+    case TILE_256x256:
+        if constexpr (BF) { if (a.coop) { FGE_LAUNCH(256, 256, 2, 4, true); break; } }
+        FGE_LAUNCH(256, 256, 2, 4, false); break;
+    case TILE_64x128:
+        if constexpr (!BF) { if (a.coop) { FGE_LAUNCH(64, 128, 2, 2, true); break; } }
+        FGE_LAUNCH(64, 128, 2, 2, false); break;
     default: return hipErrorInvalidValue;
     }
 #undef FGE_LAUNCH
     return hipGetLastError();
+}
+
+// Whether launch_tile_any has a cooperative kernel for this tile and operand type.
+inline bool tile_has_coop(int tile, int in_dtype) {
+    return in_dtype == FGE_BF16 ? (tile == TILE_128x128 || tile == TILE_256x256) : tile == TILE_64x128;
 }
 
 }  // namespace fge

@@ -25,10 +25,10 @@ namespace fge {
 __device__ __forceinline__ void split_bf16x8(const float (&f)[8], u32x4 &hi, u32x4 &lo) {
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const uint32_t h0 = f32_to_bf16(f[2 * p]), h1 = f32_to_bf16(f[2 * p + 1]);
-        const float r0 = f[2 * p] - as_f32(h0 << 16), r1 = f[2 * p + 1] - as_f32(h1 << 16);
-        hi[p] = h0 | (h1 << 16);
-        lo[p] = (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16);
+        const uint32_t hh = f32x2_to_bf16x2(f[2 * p], f[2 * p + 1]);
+        const float r0 = f[2 * p] - as_f32(hh << 16), r1 = f[2 * p + 1] - as_f32(hh & 0xFFFF0000u);
+        hi[p] = hh;
+        lo[p] = f32x2_to_bf16x2(r0, r1);
     }
 }
 
@@ -170,7 +170,7 @@ void panel_kernel(const TileArgs a) {
         }
         // the epilogue waits for the copy of the next tile before it queues its stores
         epi.m0 = tile * BM;
-        epi.tile(acc, 0);
+        epi.template tile<NT>(acc, 0, 0, tid);
     }
 }
 

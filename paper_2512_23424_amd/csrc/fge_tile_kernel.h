@@ -64,7 +64,7 @@ template <> struct Mma<float> {
     }
 };
 
-template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N>
+template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N, bool COOP = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N)
 void tile_kernel(const TileArgs a) {
     constexpr int NT = 64 * WAVES_M * WAVES_N;
@@ -86,9 +86,42 @@ void tile_kernel(const TileArgs a) {
     const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
     const int h = lane >> 5, l32 = lane & 31;
 
-    int tm, tn;
-    tile_coords(blockIdx.x, a.tiles_m, a.tiles_n, a.group_m, tm, tn);
-    const int z = blockIdx.z;
+    // One pass for an ordinary launch.  A cooperative launch is persistent: every round the
+    // grid takes the next gridDim.x / tiles_n row blocks (gridDim.x is a multiple of tiles_n), so
+    // the column tiles of a row block are always in flight together.  Inside a round, position s
+    // (contiguous per XCD) walks the round's tiles in panels of PW column tiles, row block by row
+    // block, so that the tiles of an XCD form a patch about as tall as wide: what its L2 has to
+    // fetch per k-step is then close to the minimum for that many tiles.
+    for (int round = 0;; ++round) {
+    int tm, tn, z, rowblock;
+    if constexpr (COOP) {
+        constexpr int PW = 4;
+        const int G = gridDim.x, q = G >> 3, rem = G & 7;
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int s = xcd * q + (xcd < rem ? xcd : rem) + slot;
+        const int rpr = G / a.tiles_n;                                   // row blocks per round
+        const int R = min(rpr, a.tiles_m * a.batch - round * rpr);       // ... in this round
+        if (R <= 0 || s >= R * a.tiles_n) break;
+        const int full = a.tiles_n / PW, panel = s / (R * PW);
+        int rb;
+        if (panel < full) {
+            const int w = s - panel * R * PW;
+            rb = w / PW;
+            tn = panel * PW + w % PW;
+        } else {                                                         // the narrower last panel
+            const int wd = a.tiles_n - full * PW, w = s - full * R * PW;
+            rb = w / wd;
+            tn = full * PW + w % wd;
+        }
+        rowblock = round * rpr + rb;
+        z = rowblock / a.tiles_m;
+        tm = rowblock - z * a.tiles_m;
+    } else {
+        if (round > 0) break;
+        tile_coords(blockIdx.x, a.tiles_m, a.tiles_n, a.group_m, tm, tn);
+        z = blockIdx.z;
+        rowblock = z * a.tiles_m + tm;
+    }
     const int m0 = tm * BM, n0 = tn * BN;
 
     const InT *X = reinterpret_cast<const InT *>(a.X) + (int64_t)z * a.bsx;
@@ -249,11 +282,13 @@ void tile_kernel(const TileArgs a) {
     // mainloop's last fragment reads are behind the barrier above.  The 64-row tiles are the
     // ones chosen to span N; they take the joint form (one exchange per tile).
     constexpr bool JOINT = BM == 64;
-    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 32, JOINT, false>;
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 32, JOINT, false, COOP>;
     static_assert(WAVES_M * WAVES_N * Epi::PATCH_FLOATS * 4 <= 2 * STAGE, "store patches fit the panels");
     Epi epi(a, out, xch, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, BM, z, m0, n0, tn,
             wave_n, lane);
-    epi.tile(acc, wave_m * WTM);
+    epi.template tile<NT>(acc, wave_m * WTM, rowblock, tid);
+    if constexpr (COOP) __syncthreads();             // patches are panel memory of the next tile
+    }
 }
 
 }  // namespace fge

@@ -38,8 +38,8 @@ def oracle_chain(w: I.Workload, t: Dict[str, Optional[np.ndarray]]):
 
 
 def run_gpu(w: I.Workload, t: Dict[str, Optional[np.ndarray]], path: str = "fused",
-            dev: Optional[Dict[str, torch.Tensor]] = None, batched_call: bool = True
-            ) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+            dev: Optional[Dict[str, torch.Tensor]] = None, batched_call: bool = True,
+            flags: int = 0) -> Tuple[np.ndarray, Optional[np.ndarray]]:
     """One call of the fused or unfused path on freshly NaN-poisoned outputs."""
     d = dev if dev is not None else {k: to_device(v) for k, v in t.items()}
     X = d["X"]
@@ -52,7 +52,7 @@ def run_gpu(w: I.Workload, t: Dict[str, Optional[np.ndarray]], path: str = "fuse
     aux = (torch.full((rows,), float("nan"), dtype=torch.float32, device="cuda")
            if w.norm == I.NORM_LOGSUMEXP else None)
     p = B.make_params(X, d["W"], out, alpha=w.alpha, post_scale=w.post_scale, clamp_lo=w.clamp_lo,
-                      clamp_hi=w.clamp_hi, eps=w.eps, gamma=d["gamma"], beta=d["beta"], aux_out=aux)
+                      clamp_hi=w.clamp_hi, eps=w.eps, gamma=d["gamma"], beta=d["beta"], aux_out=aux, flags=flags)
     nbytes = B.fge_workspace_bytes(path == "fused", w.act, w.norm, p)
     ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * 4

@@ -71,7 +71,14 @@ def test_argument_errors_are_reported_before_any_launch():
     # split rows need a workspace
     p = _params(M=4096, N=1024, K=1024, ldx=1024, ldw=1024, ldo=1024)
     need = B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p))
-    assert need == 4096 * (8 * 2) * 8          # 8 column tiles x 2 waves across = 16 strips per row
+    # one-kernel form: a pair per (row, column tile), an arrival mark per tile, a flag line
+    assert need == 4096 * 8 * 8 + 64 * 8 * 4 + 256
+    p.flags = B.FLAG_TWO_PASS
+    # two-pass form: 8 column tiles x 2 waves across = 16 strips per row
+    assert B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p)) == 4096 * (8 * 2) * 8
+    p.flags = 2
+    assert _call(p, act=2, norm=2) == 2        # unknown flag bit
+    p.flags = 0
     assert _call(p, act=2, norm=2) == 6
     p.workspace, p.workspace_bytes = FAKE, need - 1
     assert _call(p, act=2, norm=2) == 6
@@ -92,7 +99,11 @@ def test_status_strings_and_tile_names():
     assert B.fge_tile_name(True, 5, 4, _params(M=1000, N=512, ldo=512)) == "64x512_w1x4"
     big = _params(M=8192, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, in_dtype=1, out_dtype=1)
     assert B.fge_tile_name(True, 4, 3, big) == "256x256_w2x4"
+    assert B.fge_fused_needs_finish(4, 3, big) is False      # the tiles finish their rows themselves
+    big.flags = B.FLAG_TWO_PASS
     assert B.fge_fused_needs_finish(4, 3, big) is True
+    small = _params(M=300, N=1024, K=256, ldx=256, ldw=256, ldo=1024)
+    assert B.fge_fused_needs_finish(2, 2, small) is True     # small problems keep the second pass
     assert B.fge_fused_needs_finish(1, 1, _params(N=64, ldo=64)) is False
     with pytest.raises(B.FgeError):
         B.fge_fused_needs_finish(1, 1, _params(M=0))

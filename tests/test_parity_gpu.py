@@ -104,6 +104,46 @@ def test_narrow_k_persistent_kernel(norm, shape):
                 H.check(w, got, gaux, ref, raux, f"narrow-k {path} act{act}")
 
 
+@pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
+@pytest.mark.parametrize("case", [(I.BF16, 4100, 136, 4000, "256x256_w2x4"), (I.BF16, 2050, 200, 2040, "128x128_w2x2"),
+                                  (I.F32, 1030, 100, 2040, "64x128_w2x2")])
+def test_split_rows_one_kernel_and_two_pass(norm, case):
+    """Rows split over column tiles, large enough for the one-kernel form (the tiles of a row
+    block exchange statistics and finish their rows themselves): ragged M / N / K, a partial
+    last round of the persistent grid, checked against the oracle; the two-pass form of the same
+    call must agree with the oracle as well."""
+    dt, M, K, N, tile = case
+    w = I.Workload(name=f"split{norm}", M=M, K=K, N=N, in_dtype=dt, out_dtype=dt, act=I.ACT_SILU,
+                   norm=norm, alpha=0.5, post_scale=1.5, eps=1e-5,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1),
+                         "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1),
+                         "beta": ("normal", 0.0, 0.1)})
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(dt), device="cuda"))
+    assert B.fge_tile_name(True, w.act, norm, p) == tile
+    assert not B.fge_fused_needs_finish(w.act, norm, p)
+    p.flags = B.FLAG_TWO_PASS
+    assert B.fge_fused_needs_finish(w.act, norm, p)
+    ref, raux = H.oracle_chain(w, t)
+    for flags in (0, B.FLAG_TWO_PASS):
+        got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
+        H.check(w, got, gaux, ref, raux, f"split flags={flags}")
+    # three launches in a row on one workspace: the marks an earlier launch left behind must
+    # not satisfy a later one (results stay identical)
+    aux = torch.zeros(M, device="cuda")
+    outs = [torch.full((M, N), float("nan"), dtype=H.tdtype(dt), device="cuda") for _ in range(3)]
+    p = B.make_params(d["X"], d["W"], outs[0], alpha=w.alpha, post_scale=w.post_scale, eps=w.eps,
+                      gamma=d["gamma"], beta=d["beta"], aux_out=aux)
+    ws = torch.empty(B.fge_workspace_bytes(True, w.act, norm, p), dtype=torch.uint8, device="cuda")
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+    for o in outs:
+        B.fused_gemm_epilogue(d["X"], d["W"], d["b"], w.act, norm, p, o)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert np.array_equal(H.to_host_f64(outs[0]), H.run_gpu(w, t, "fused", dev=d)[0])
+
+
 def test_narrow_k_exact_integers():
     """Small integers survive the bf16 split exactly: the result must match bit for bit."""
     w = I.Workload(name="nkint", M=4500, K=64, N=512, in_dtype=I.F32, out_dtype=I.F32,
@@ -191,7 +231,8 @@ def test_stage_entry_points_compose_to_the_paths():
     d = {k: H.to_device(v) for k, v in t.items()}
     full, _ = H.run_gpu(w, t, "fused", dev=d)
     out = torch.full((w.M, w.N), float("nan"), device="cuda")
-    p = B.make_params(d["X"], d["W"], out, eps=w.eps, gamma=d["gamma"], beta=d["beta"])
+    p = B.make_params(d["X"], d["W"], out, eps=w.eps, gamma=d["gamma"], beta=d["beta"],
+                      flags=B.FLAG_TWO_PASS)
     ws = torch.empty(B.fge_workspace_bytes(True, w.act, w.norm, p), dtype=torch.uint8, device="cuda")
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
     assert B.fge_fused_needs_finish(w.act, w.norm, p)
