@@ -140,6 +140,10 @@ Plan make_plan(const fge_params *p, int norm) {
     return pl;
 }
 
+// min(max(y, lo), hi) with lo > hi is hi for every y: the same as clamping to [hi, hi], which
+// lets the kernels use a median-of-three for the clamp.
+inline float clamp_low(const fge_params *p) { return p->clamp_lo < p->clamp_hi ? p->clamp_lo : p->clamp_hi; }
+
 int hip_status(hipError_t e) {
     if (e == hipSuccess) return FGE_OK;
     g_last_hip = (int)e;
@@ -153,7 +157,7 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
     a.out = out; a.aux = p->aux_out; a.ws = reinterpret_cast<float2 *>(p->workspace);
     a.M = pl.pr.M; a.N = pl.pr.N; a.K = pl.pr.K;
     a.ldx = pl.pr.ldx; a.ldw = pl.pr.ldw; a.ldo = pl.pr.ldo; a.bsx = pl.pr.bsx; a.bso = pl.pr.bso;
-    a.alpha = p->alpha; a.post = p->post_scale; a.lo = p->clamp_lo; a.hi = p->clamp_hi; a.eps = p->eps;
+    a.alpha = p->alpha; a.post = p->post_scale; a.lo = clamp_low(p); a.hi = p->clamp_hi; a.eps = p->eps;
     a.act = act; a.norm = norm;
     a.tiles_m = pl.tiles_m; a.tiles_n = pl.tiles_n; a.batch = pl.pr.batch;
     a.group_m = pl.tiles_m < 8 ? pl.tiles_m : 8;
@@ -185,7 +189,7 @@ RowArgs row_args(const void *in, void *out, int act, int norm, const fge_params 
     r.in = in; r.out = out; r.gamma = p->gamma; r.beta = p->beta; r.aux = p->aux_out;
     r.ws = reinterpret_cast<const float2 *>(p->workspace);
     r.M = pl.pr.M; r.N = pl.pr.N; r.batch = pl.pr.batch; r.ldo = pl.pr.ldo; r.bso = pl.pr.bso;
-    r.lo = p->clamp_lo; r.hi = p->clamp_hi; r.eps = p->eps; r.act = act; r.norm = norm;
+    r.lo = clamp_low(p); r.hi = p->clamp_hi; r.eps = p->eps; r.act = act; r.norm = norm;
     r.tiles_n = pl.strips; r.bn = tile_info(pl.tile).bn / tile_info(pl.tile).waves_n;
     return r;
 }

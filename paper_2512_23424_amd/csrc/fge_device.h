@@ -90,14 +90,23 @@ template <> struct Store<bf16_t> {
 // below avoid cancellation so the relative error stays near 1e-6 for every input.
 __device__ __forceinline__ float fast_exp(float x) { return __expf(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+constexpr float LOG2E = 1.4426950408889634f;
+// exp(x - m) as one multiply-add and one exponential: c = -m * LOG2E is formed once per row
+__device__ __forceinline__ float exp_rel(float x, float c) { return __builtin_amdgcn_exp2f(fmaf(x, LOG2E, c)); }
+// max / clamp as single median-of-three instructions (the compiler wraps fmaxf / fminf of
+// values it cannot prove canonical - anything that came through LDS or a select - in an extra
+// canonicalising instruction each)
+__device__ __forceinline__ float max_nc(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_inff()); }
+__device__ __forceinline__ float clamp_nc(float y, float lo, float hi) { return __builtin_amdgcn_fmed3f(y, lo, hi); }
 
 template <int ACT> __device__ __forceinline__ float activate(float y, float lo, float hi) {
     if constexpr (ACT == FGE_ACT_RELU) {
         return fmaxf(y, 0.0f);
     } else if constexpr (ACT == FGE_ACT_GELU_TANH) {
         // 0.5 y (1 + tanh u) == y * sigmoid(2u),  u = sqrt(2/pi) (y + 0.044715 y^3)
-        const float u2 = 1.5957691216057308f * (y + 0.044715f * y * y * y);
-        return y * fast_rcp(1.0f + fast_exp(-u2));
+        // (exp(-2u) as one exp2: the factor below is -2 sqrt(2/pi) log2(e))
+        const float w = -2.302208198144325f * (y + 0.044715f * y * y * y);
+        return y * fast_rcp(1.0f + __builtin_amdgcn_exp2f(w));
     } else if constexpr (ACT == FGE_ACT_GELU_ERF) {
         // 0.5 y (1 + erf(y/sqrt2)) = y * Phi(y).  erfc(|x|) by the rational approximation 7.1.26
         // of Abramowitz & Stegun (|error| <= 1.5e-7 on erf):  erfc(|x|) = poly(t) exp(-x^2),
@@ -115,7 +124,7 @@ template <int ACT> __device__ __forceinline__ float activate(float y, float lo, 
     } else if constexpr (ACT == FGE_ACT_SILU) {
         return y * fast_rcp(1.0f + fast_exp(-y));
     } else if constexpr (ACT == FGE_ACT_CLAMP) {
-        return fminf(fmaxf(y, lo), hi);
+        return clamp_nc(y, lo, hi);                // the host passes lo <= hi
     } else {
         return y;
     }
@@ -146,7 +155,7 @@ template <int I0, int N, typename F> __device__ __forceinline__ void static_for(
 // ---------------------------------------------------------------- wavefront reductions
 struct OpSum { __device__ static __forceinline__ float f(float a, float b) { return a + b; }
                static constexpr float ident() { return 0.0f; } };
-struct OpMax { __device__ static __forceinline__ float f(float a, float b) { return fmaxf(a, b); }
+struct OpMax { __device__ static __forceinline__ float f(float a, float b) { return max_nc(a, b); }
                static constexpr float ident() { return -__builtin_inff(); } };
 
 template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {

@@ -49,7 +49,10 @@ struct TileArgs {
 // store of a group (for callers with asynchronous global->LDS loads in flight that want them
 // accounted for before stores are queued behind them).  COOP: the cooperative form only - rows
 // are split over column tiles that are all in flight and finish their rows themselves.
-template <typename OutT, int MB, int NB, int WAVES_N, int PATCH_ROWS, bool JOINT, bool WAIT_VM, bool COOP = false>
+// FULL_TILE: the caller guarantees that every tile lies inside the matrix (M and N are multiples
+// of the tile shape), so no row or column needs a guard.
+template <typename OutT, int MB, int NB, int WAVES_N, int PATCH_ROWS, bool JOINT, bool WAIT_VM, bool COOP = false,
+          bool FULL_TILE = false>
 struct TileEpilogue {
     static constexpr int WTN = NB * 32;               // columns of a wave strip
     static constexpr int SSTR = WTN + 8;              // floats per patch row: +8 puts lanes 0-31
@@ -85,6 +88,7 @@ struct TileEpilogue {
     int xch_par;                // which exchange buffer the next exchange uses
     float scale, bias[NB];      // y = scale * acc + bias  (scale = post*alpha, bias = post*b)
     bool whole_row;
+    bool bounded;               // clamp activation with a narrow range feeds softmax / logsumexp
 
     __device__ __forceinline__ TileEpilogue(const TileArgs &a_, OutT *out_, float2 *xch_, float *patch_,
                                             int tile_rows_, int z, int m0_, int n0_, int tn_,
@@ -104,6 +108,8 @@ struct TileEpilogue {
         ok4[1] = gcol + G4STEP < a.N;
         xch_par = 0;
         whole_row = a.tiles_n == 1;
+        // (not in the cooperative form, whose registers are too scarce for two more variants)
+        bounded = !COOP && a.act == FGE_ACT_CLAMP && a.hi - a.lo <= 64.0f;
     }
 
     // valid columns of strip w of this tile
@@ -122,12 +128,13 @@ struct TileEpilogue {
 
     // Publish the strip pair of pass q: to the workspace for the second pass, or (cooperative
     // form) to LDS, where the tile's strips are merged before anything leaves the workgroup.
-    __device__ __forceinline__ void put_stats(int grow0, int q, float s0, float s1) {
+    // FULL (here and below): the tile lies inside the matrix, no row or column needs a guard.
+    template <bool FULL> __device__ __forceinline__ void put_stats(int grow0, int q, float s0, float s1) {
         if constexpr (COOP) {
             if (sub == 0) xch[qrow(grow0, q) * WAVES_N + wave_n] = make_float2(s0, s1);
         } else {
             const int grow = m0 + qrow(grow0, q);
-            if (sub == 0 && grow < a.M)
+            if (sub == 0 && (FULL || grow < a.M))
                 a.ws[(row_base + grow) * (a.tiles_n * WAVES_N) + tn * WAVES_N + wave_n] = make_float2(s0, s1);
         }
     }
@@ -172,25 +179,33 @@ struct TileEpilogue {
 
     // Row operation on one group in the row-wise layout: v[q][e] is column gcol + (e/4)*G4STEP + e%4 of tile row
     // qrow(grow0, q).  Whole rows are normalised in place; split rows keep the parked value.
-    template <int NORM> __device__ __forceinline__ void norm_group(float (&v)[NPG][VEC], int grow0) {
+    // BOUNDED (softmax / logsumexp after a clamp): every value lies in [lo, hi] with hi - lo
+    // small, so hi serves as the reference of the exponentials and no maximum is searched.
+    template <int NORM, bool FULL, bool BOUNDED> __device__ __forceinline__ void norm_group(float (&v)[NPG][VEC], int grow0) {
+        auto okc = [&](int e) __attribute__((always_inline)) { return FULL || ok4[e >> 2]; };
         float s0[NPG], s1[NPG];
         if constexpr (NORM == FGE_NORM_SOFTMAX || NORM == FGE_NORM_LOGSUMEXP) {
-            float ml[NPG];                            // strip maxima
+            float ml[NPG];                            // strip maxima (or the common bound)
 #pragma unroll
             for (int q = 0; q < NPG; ++q) {
-                float m = OpMax::ident();
+                if constexpr (BOUNDED) {
+                    ml[q] = a.hi;
+                } else {
+                    float m = OpMax::ident();
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) m = fmaxf(m, ok4[e >> 2] ? v[q][e] : OpMax::ident());
-                ml[q] = allreduce_lanes<OpMax, LPR>(m);
+                    for (int e = 0; e < VEC; ++e) m = max_nc(m, okc(e) ? v[q][e] : OpMax::ident());
+                    ml[q] = allreduce_lanes<OpMax, LPR>(m);
+                }
             }
 #pragma unroll
             for (int q = 0; q < NPG; ++q) {
+                const float c = -ml[q] * LOG2E;
                 float s = 0.0f;
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    const float x = fast_exp(v[q][e] - ml[q]);
+                    const float x = exp_rel(v[q][e], c);
                     if constexpr (NORM == FGE_NORM_SOFTMAX) v[q][e] = x;
-                    s += ok4[e >> 2] ? x : 0.0f;
+                    s += okc(e) ? x : 0.0f;
                 }
                 s0[q] = ml[q];
                 s1[q] = allreduce_lanes<OpSum, LPR>(s);
@@ -198,21 +213,27 @@ struct TileEpilogue {
             if (!whole_row) {
                 // softmax parks exp(a - m_strip); the second pass rescales by exp(m_strip - m)/s
 #pragma unroll
-                for (int q = 0; q < NPG; ++q) put_stats(grow0, q, s0[q], s1[q]);
+                for (int q = 0; q < NPG; ++q) put_stats<FULL>(grow0, q, s0[q], s1[q]);
                 return;
             }
             exchange(grow0, s0, s1, OpMax::ident());
 #pragma unroll
             for (int q = 0; q < NPG; ++q) {
-                const float m = allreduce_lanes<OpMax, LPR>(s0[q]);
-                const float s = allreduce_lanes<OpSum, LPR>(s1[q] * fast_exp(s0[q] - m));
+                float m, s;
+                if constexpr (BOUNDED) {                  // all references are equal
+                    m = a.hi;
+                    s = allreduce_lanes<OpSum, LPR>(s1[q]);
+                } else {
+                    m = allreduce_lanes<OpMax, LPR>(s0[q]);
+                    s = allreduce_lanes<OpSum, LPR>(s1[q] * fast_exp(s0[q] - m));
+                }
                 if constexpr (NORM == FGE_NORM_SOFTMAX) {
-                    const float f = fast_exp(ml[q] - m) * fast_rcp(s);
+                    const float f = (BOUNDED ? 1.0f : fast_exp(ml[q] - m)) * fast_rcp(s);
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) v[q][e] *= f;
                 } else {
                     const int grow = m0 + qrow(grow0, q);
-                    if (sub == 0 && wave_n == 0 && grow < a.M) a.aux[row_base + grow] = m + __logf(s);
+                    if (sub == 0 && wave_n == 0 && (FULL || grow < a.M)) a.aux[row_base + grow] = m + __logf(s);
                 }
             }
             return;
@@ -223,31 +244,31 @@ struct TileEpilogue {
         for (int e = 0; e < VEC; e += 4) {
             floatx4 g = {1.0f, 1.0f, 1.0f, 1.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
             const int c = gcol + (e >> 2) * G4STEP;
-            if (whole_row && ok4[e >> 2] && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + c);
-            if (whole_row && ok4[e >> 2] && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + c);
+            if (whole_row && okc(e) && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + c);
+            if (whole_row && okc(e) && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + c);
             gam[e] = g[0]; gam[e + 1] = g[1]; gam[e + 2] = g[2]; gam[e + 3] = g[3];
             bet[e] = b[0]; bet[e + 1] = b[1]; bet[e + 2] = b[2]; bet[e + 3] = b[3];
         }
         if constexpr (NORM == FGE_NORM_LAYERNORM) {
-            const int nl = strip_cols(wave_n);
+            const int nl = FULL ? WTN : strip_cols(wave_n);
             const float inv_nl = nl > 0 ? 1.0f / (float)nl : 0.0f;
 #pragma unroll
             for (int q = 0; q < NPG; ++q) {
                 float s = 0.0f;
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) s += ok4[e >> 2] ? v[q][e] : 0.0f;
+                for (int e = 0; e < VEC; ++e) s += okc(e) ? v[q][e] : 0.0f;
                 s0[q] = allreduce_lanes<OpSum, LPR>(s) * inv_nl;                  // strip mean
                 float d2 = 0.0f;
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
                     const float d = v[q][e] - s0[q];
-                    d2 += ok4[e >> 2] ? d * d : 0.0f;
+                    d2 += okc(e) ? d * d : 0.0f;
                 }
                 s1[q] = allreduce_lanes<OpSum, LPR>(d2);                          // strip M2
             }
             if (!whole_row) {
 #pragma unroll
-                for (int q = 0; q < NPG; ++q) put_stats(grow0, q, s0[q], s1[q]);
+                for (int q = 0; q < NPG; ++q) put_stats<FULL>(grow0, q, s0[q], s1[q]);
                 return;
             }
             exchange(grow0, s0, s1, 0.0f);
@@ -267,13 +288,13 @@ struct TileEpilogue {
             for (int q = 0; q < NPG; ++q) {
                 float s = 0.0f;
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) s += ok4[e >> 2] ? v[q][e] * v[q][e] : 0.0f;
+                for (int e = 0; e < VEC; ++e) s += okc(e) ? v[q][e] * v[q][e] : 0.0f;
                 s0[q] = allreduce_lanes<OpSum, LPR>(s);
                 s1[q] = 0.0f;
             }
             if (!whole_row) {
 #pragma unroll
-                for (int q = 0; q < NPG; ++q) put_stats(grow0, q, s0[q], 0.0f);
+                for (int q = 0; q < NPG; ++q) put_stats<FULL>(grow0, q, s0[q], 0.0f);
                 return;
             }
             exchange(grow0, s0, s1, 0.0f);
@@ -283,6 +304,18 @@ struct TileEpilogue {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) v[q][e] *= rr * gam[e];
             }
+        }
+    }
+    // norm_group with the runtime row-op code (and the clamp bound) turned into constants
+    template <bool FULL> __device__ __forceinline__ void norm_dispatch(float (&v)[NPG][VEC], int grow0) {
+        switch (a.norm + (bounded ? 8 : 0)) {
+        case FGE_NORM_NONE: case FGE_NORM_NONE + 8: break;
+        case FGE_NORM_SOFTMAX:       norm_group<FGE_NORM_SOFTMAX, FULL, false>(v, grow0); break;
+        case FGE_NORM_SOFTMAX + 8:   norm_group<FGE_NORM_SOFTMAX, FULL, true>(v, grow0); break;
+        case FGE_NORM_LOGSUMEXP:     norm_group<FGE_NORM_LOGSUMEXP, FULL, false>(v, grow0); break;
+        case FGE_NORM_LOGSUMEXP + 8: norm_group<FGE_NORM_LOGSUMEXP, FULL, true>(v, grow0); break;
+        case FGE_NORM_LAYERNORM: case FGE_NORM_LAYERNORM + 8: norm_group<FGE_NORM_LAYERNORM, FULL, false>(v, grow0); break;
+        default:                 norm_group<FGE_NORM_RMSNORM, FULL, false>(v, grow0); break;
         }
     }
 
@@ -315,17 +348,17 @@ struct TileEpilogue {
         transpose_block<B>(blk, v);
     }
 
-    __device__ __forceinline__ void store_group(float (&v)[NPG][VEC], int grow0) {
+    template <bool FULL> __device__ __forceinline__ void store_group(float (&v)[NPG][VEC], int grow0) {
 #pragma unroll
         for (int q = 0; q < NPG; ++q) {
             const int grow = m0 + qrow(grow0, q);
-            if (grow < a.M) {
+            if (FULL || grow < a.M) {
                 OutT *o = out + (int64_t)grow * a.ldo + gcol;
                 if constexpr (sizeof(OutT) == 2) {     // N is a multiple of 8: all or nothing
-                    if (ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
+                    if (FULL || ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
                 } else {
-                    if (ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
-                    if (ok4[1]) *reinterpret_cast<uint4 *>(o + G4STEP) = Store<OutT>::pack(v[q] + 4);
+                    if (FULL || ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
+                    if (FULL || ok4[1]) *reinterpret_cast<uint4 *>(o + G4STEP) = Store<OutT>::pack(v[q] + 4);
                 }
             }
         }
@@ -351,7 +384,7 @@ struct TileEpilogue {
         if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
             o0 = e[0].x;
 #pragma unroll
-            for (int w = 1; w < WAVES_N; ++w) o0 = fmaxf(o0, e[w].x);
+            for (int w = 1; w < WAVES_N; ++w) o0 = max_nc(o0, e[w].x);
 #pragma unroll
             for (int w = 0; w < WAVES_N; ++w) o1 += e[w].y * fast_exp(e[w].x - o0);   // empty strips: 0 * exp(-inf)
         } else if (a.norm == FGE_NORM_LAYERNORM) {
@@ -415,8 +448,8 @@ struct TileEpilogue {
                     e[i] = t0 + i * TPR < a.tiles_n ? get_pair(pr + t0 + i * TPR) : make_float2(OpMax::ident(), 0.0f);
                 float mc = e[0].x;
 #pragma unroll
-                for (int i = 1; i < CH; ++i) mc = fmaxf(mc, e[i].x);
-                const float mn = fmaxf(m, mc);            // finite: slot t0 exists and every tile has columns
+                for (int i = 1; i < CH; ++i) mc = max_nc(mc, e[i].x);
+                const float mn = max_nc(m, mc);            // finite: slot t0 exists and every tile has columns
                 sum *= fast_exp(m - mn);
 #pragma unroll
                 for (int i = 0; i < CH; ++i) sum += e[i].y * fast_exp(e[i].x - mn);
@@ -468,14 +501,14 @@ struct TileEpilogue {
     }
 
     // step 5 for one group
-    template <int NORM> __device__ __forceinline__ void finish_group(float (&v)[NPG][VEC], int grow0, const float2 *fin) {
+    template <int NORM, bool FULL> __device__ __forceinline__ void finish_group(float (&v)[NPG][VEC], int grow0, const float2 *fin) {
         float gam[VEC], bet[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; e += 4) {
             floatx4 g = {1.0f, 1.0f, 1.0f, 1.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
             const int c = gcol + (e >> 2) * G4STEP;
-            if (NORM != FGE_NORM_SOFTMAX && ok4[e >> 2] && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + c);
-            if (NORM == FGE_NORM_LAYERNORM && ok4[e >> 2] && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + c);
+            if (NORM != FGE_NORM_SOFTMAX && (FULL || ok4[e >> 2]) && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + c);
+            if (NORM == FGE_NORM_LAYERNORM && (FULL || ok4[e >> 2]) && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + c);
             gam[e] = g[0]; gam[e + 1] = g[1]; gam[e + 2] = g[2]; gam[e + 3] = g[3];
             bet[e] = b[0]; bet[e + 1] = b[1]; bet[e + 2] = b[2]; bet[e + 3] = b[3];
         }
@@ -483,8 +516,9 @@ struct TileEpilogue {
         for (int q = 0; q < NPG; ++q) {
             const float2 r = fin[qrow(grow0, q)];
             if constexpr (NORM == FGE_NORM_SOFTMAX) {
+                const float c = -r.x * LOG2E;
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) v[q][e] = fast_exp(v[q][e] - r.x) * r.y;
+                for (int e = 0; e < VEC; ++e) v[q][e] = exp_rel(v[q][e], c) * r.y;
             } else if constexpr (NORM == FGE_NORM_LAYERNORM) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) v[q][e] = (v[q][e] - r.x) * r.y * gam[e] + bet[e];
@@ -501,17 +535,16 @@ struct TileEpilogue {
     __device__ __forceinline__ void tile(floatx16 (&acc)[MB][NB], int trow0, int rowblock, int tid) {
         if constexpr (COOP) {
             // step 1 (logsumexp leaves the activated values as they are: stored right away)
-            static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
-                float v[NPG][VEC];
-                static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
-                const int grow0 = trow0 + g * G * 32;
-                switch (a.norm) {
-                case FGE_NORM_SOFTMAX:   norm_group<FGE_NORM_SOFTMAX>(v, grow0); break;
-                case FGE_NORM_LOGSUMEXP: norm_group<FGE_NORM_LOGSUMEXP>(v, grow0); store_group(v, grow0); break;
-                case FGE_NORM_LAYERNORM: norm_group<FGE_NORM_LAYERNORM>(v, grow0); break;
-                default:                 norm_group<FGE_NORM_RMSNORM>(v, grow0); break;
-                }
-            });
+            auto step1 = [&]<bool FULL>() __attribute__((always_inline)) {
+                static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+                    float v[NPG][VEC];
+                    static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
+                    const int grow0 = trow0 + g * G * 32;
+                    norm_dispatch<FULL>(v, grow0);
+                    if (a.norm == FGE_NORM_LOGSUMEXP) store_group<FULL>(v, grow0);
+                });
+            };
+            step1.template operator()<FULL_TILE>();
             __syncthreads();
             if (tid < tile_rows) merge_strips(tid);
             arrive_and_wait(rowblock, tid);
@@ -519,32 +552,32 @@ struct TileEpilogue {
             merge_tiles<NT / (MB * 32 * (NT / 64 / WAVES_N))>(tid, fin);
             if (a.norm == FGE_NORM_LOGSUMEXP) return;
             __syncthreads();
-            static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
-                float v[NPG][VEC];
-                static_for<0, G>([&]<int b>() __attribute__((always_inline)) { transpose_block<b>(acc[g * G + b], v); });
-                const int grow0 = trow0 + g * G * 32;
-                switch (a.norm) {
-                case FGE_NORM_SOFTMAX:   finish_group<FGE_NORM_SOFTMAX>(v, grow0, fin); break;
-                case FGE_NORM_LAYERNORM: finish_group<FGE_NORM_LAYERNORM>(v, grow0, fin); break;
-                default:                 finish_group<FGE_NORM_RMSNORM>(v, grow0, fin); break;
-                }
-                store_group(v, grow0);
-            });
+            auto step5 = [&]<bool FULL>() __attribute__((always_inline)) {
+                static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+                    float v[NPG][VEC];
+                    static_for<0, G>([&]<int b>() __attribute__((always_inline)) { transpose_block<b>(acc[g * G + b], v); });
+                    const int grow0 = trow0 + g * G * 32;
+                    switch (a.norm) {
+                    case FGE_NORM_SOFTMAX:   finish_group<FGE_NORM_SOFTMAX, FULL>(v, grow0, fin); break;
+                    case FGE_NORM_LAYERNORM: finish_group<FGE_NORM_LAYERNORM, FULL>(v, grow0, fin); break;
+                    default:                 finish_group<FGE_NORM_RMSNORM, FULL>(v, grow0, fin); break;
+                    }
+                    store_group<FULL>(v, grow0);
+                });
+            };
+            step5.template operator()<FULL_TILE>();
         } else {
-            static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
-                float v[NPG][VEC];
-                static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
-                const int grow0 = trow0 + g * G * 32;
-                switch (a.norm) {
-                case FGE_NORM_NONE:      break;
-                case FGE_NORM_SOFTMAX:   norm_group<FGE_NORM_SOFTMAX>(v, grow0); break;
-                case FGE_NORM_LOGSUMEXP: norm_group<FGE_NORM_LOGSUMEXP>(v, grow0); break;
-                case FGE_NORM_LAYERNORM: norm_group<FGE_NORM_LAYERNORM>(v, grow0); break;
-                default:                 norm_group<FGE_NORM_RMSNORM>(v, grow0); break;
-                }
-                if constexpr (WAIT_VM) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                store_group(v, grow0);
-            });
+            auto body = [&]<bool FULL>() __attribute__((always_inline)) {
+                static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+                    float v[NPG][VEC];
+                    static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
+                    const int grow0 = trow0 + g * G * 32;
+                    norm_dispatch<FULL>(v, grow0);
+                    if constexpr (WAIT_VM) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    store_group<FULL>(v, grow0);
+                });
+            };
+            body.template operator()<FULL_TILE>();
         }
     }
 };

@@ -29,34 +29,59 @@ hipError_t launch_tile_bf16(int tile, int out_dtype, dim3 grid, hipStream_t s, c
 // Defined in fge_panel_f32.hip: the persistent narrow-K kernel (grid = number of workgroups).
 hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 
+// Workgroups of `kernel` the current device holds at the same time (0 if the query fails).
+inline int resident_workgroups(const void *kernel, int threads) {
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) return 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return per_cu * cus;
+}
+
 template <typename InT>
 inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
-#define FGE_LAUNCH(BM, BN, WM, WN, COOP)                                                        \
+#define FGE_LAUNCH(BM, BN, WM, WN, COOP, FULL)                                                  \
     do {                                                                                        \
         if (out_dtype == FGE_BF16)                                                              \
-            hipLaunchKernelGGL((tile_kernel<InT, bf16_t, BM, BN, WM, WN, COOP>), grid,          \
+            hipLaunchKernelGGL((tile_kernel<InT, bf16_t, BM, BN, WM, WN, COOP, FULL>), grid,    \
                                dim3(64 * WM * WN), 0, s, a);                                    \
         else                                                                                    \
-            hipLaunchKernelGGL((tile_kernel<InT, float, BM, BN, WM, WN, COOP>), grid,           \
+            hipLaunchKernelGGL((tile_kernel<InT, float, BM, BN, WM, WN, COOP, FULL>), grid,     \
                                dim3(64 * WM * WN), 0, s, a);                                    \
+    } while (0)
+    // cooperative kernel of a tile.  All workgroups of the grid must be resident at once; a launch that the device cannot hold
+    // that way is refused instead of being left to run into its wait limit.
+#define FGE_LAUNCH_COOP1(BM, BN, WM, WN, OT, FULL)                                              \
+    do {                                                                                        \
+        auto kern = tile_kernel<InT, OT, BM, BN, WM, WN, true, FULL>;                           \
+        static const int resident = resident_workgroups(reinterpret_cast<const void *>(kern), 64 * WM * WN); \
+        if ((int)grid.x > resident) return hipErrorCooperativeLaunchTooLarge;                   \
+        hipLaunchKernelGGL(kern, grid, dim3(64 * WM * WN), 0, s, a);                            \
+    } while (0)
+#define FGE_LAUNCH_COOP(BM, BN, WM, WN)                                                         \
+    do {                                                                                        \
+        if (out_dtype == FGE_BF16) FGE_LAUNCH_COOP1(BM, BN, WM, WN, bf16_t, false);             \
+        else                       FGE_LAUNCH_COOP1(BM, BN, WM, WN, float, false);              \
     } while (0)
     // the cooperative form exists for the tiles large problems use: bf16 256x256 and 128x128,
     // fp32 64x128 (tile_has_coop below must agree)
     constexpr bool BF = sizeof(InT) == 2;
     switch (tile) {
-    case TILE_64x64:   FGE_LAUNCH(64, 64, 2, 2, false); break;
-    case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4, false); break;
+    case TILE_64x64:   FGE_LAUNCH(64, 64, 2, 2, false, false); break;
+    case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4, false, false); break;
     case TILE_128x128:
-        if constexpr (BF) { if (a.coop) { FGE_LAUNCH(128, 128, 2, 2, true); break; } }
-        FGE_LAUNCH(128, 128, 2, 2, false); break;
+        if constexpr (BF) { if (a.coop) { FGE_LAUNCH_COOP(128, 128, 2, 2); break; } }
+        FGE_LAUNCH(128, 128, 2, 2, false, false); break;
     case TILE_256x256:
-        if constexpr (BF) { if (a.coop) { FGE_LAUNCH(256, 256, 2, 4, true); break; } }
-        FGE_LAUNCH(256, 256, 2, 4, false); break;
+        if constexpr (BF) { if (a.coop) { FGE_LAUNCH_COOP(256, 256, 2, 4); break; } }
+        FGE_LAUNCH(256, 256, 2, 4, false, false); break;
     case TILE_64x128:
-        if constexpr (!BF) { if (a.coop) { FGE_LAUNCH(64, 128, 2, 2, true); break; } }
-        FGE_LAUNCH(64, 128, 2, 2, false); break;
+        if constexpr (!BF) { if (a.coop) { FGE_LAUNCH_COOP(64, 128, 2, 2); break; } }
+        FGE_LAUNCH(64, 128, 2, 2, false, false); break;
     default: return hipErrorInvalidValue;
     }
+#undef FGE_LAUNCH_COOP
+#undef FGE_LAUNCH_COOP1
 #undef FGE_LAUNCH
     return hipGetLastError();
 }

@@ -45,7 +45,8 @@ struct PanelShape {
     static constexpr int THREADS = 64 * WAVES_N;
 };
 
-template <typename OutT>
+// FULL: M is a multiple of 64 and N == 512, so the epilogue needs no row or column guards.
+template <typename OutT, bool FULL>
 __global__ __launch_bounds__(PanelShape::THREADS)
 void panel_kernel(const TileArgs a) {
     constexpr int BM = PanelShape::BM, BN = PanelShape::BN, WAVES_N = PanelShape::WAVES_N;
@@ -54,7 +55,7 @@ void panel_kernel(const TileArgs a) {
     constexpr int XROWB = 256;                        // LDS bytes per X row: 64 fp32
     constexpr int XTILE = BM * XROWB;                 // 16 KB
     constexpr int X_LD = BM * 16 / NT;                // 16-byte chunks per thread per tile (2)
-    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, PANEL_JOINT, true>;
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, PANEL_JOINT, true, false, FULL>;
 
     __shared__ __attribute__((aligned(16))) unsigned char xs[2 * XTILE];
     __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];

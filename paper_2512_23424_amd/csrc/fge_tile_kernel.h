@@ -64,8 +64,11 @@ template <> struct Mma<float> {
     }
 };
 
-template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N, bool COOP = false>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N)
+// FULL: M and N are multiples of BM and BN - the epilogue then runs without row or column guards.
+// Tiles of up to 64x128 are meant to run two workgroups per CU (second launch bound: waves per
+// SIMD), which caps their registers at 256.
+template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N, bool COOP = false, bool FULL = false>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN <= 64 * 128 ? 2 : 1))
 void tile_kernel(const TileArgs a) {
     constexpr int NT = 64 * WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -82,10 +85,6 @@ void tile_kernel(const TileArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
     __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
-    const int h = lane >> 5, l32 = lane & 31;
-
     // One pass for an ordinary launch.  A cooperative launch is persistent: every round the
     // grid takes the next gridDim.x / tiles_n row blocks (gridDim.x is a multiple of tiles_n), so
     // the column tiles of a row block are always in flight together.  Inside a round, position s
@@ -93,6 +92,14 @@ void tile_kernel(const TileArgs a) {
     // block, so that the tiles of an XCD form a patch about as tall as wide: what its L2 has to
     // fetch per k-step is then close to the minimum for that many tiles.
     for (int round = 0;; ++round) {
+    // In the persistent form the thread index is made opaque once per round: everything derived
+    // from it (staging plan, fragment offsets, epilogue coordinates) is then recomputed per tile
+    // instead of being kept in registers across the epilogue, where registers are scarce.
+    int tid = threadIdx.x;
+    if constexpr (COOP) asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+    const int h = lane >> 5, l32 = lane & 31;
     int tm, tn, z, rowblock;
     if constexpr (COOP) {
         constexpr int PW = 4;
@@ -282,7 +289,7 @@ void tile_kernel(const TileArgs a) {
     // mainloop's last fragment reads are behind the barrier above.  The 64-row tiles are the
     // ones chosen to span N; they take the joint form (one exchange per tile).
     constexpr bool JOINT = BM == 64;
-    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 32, JOINT, false, COOP>;
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 32, JOINT, false, COOP, FULL>;
     static_assert(WAVES_M * WAVES_N * Epi::PATCH_FLOATS * 4 <= 2 * STAGE, "store patches fit the panels");
     Epi epi(a, out, xch, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, BM, z, m0, n0, tn,
             wave_n, lane);
