@@ -50,9 +50,11 @@ struct TileArgs {
 // accounted for before stores are queued behind them).  COOP: the cooperative form only - rows
 // are split over column tiles that are all in flight and finish their rows themselves.
 // FULL_TILE: the caller guarantees that every tile lies inside the matrix (M and N are multiples
-// of the tile shape), so no row or column needs a guard.
+// of the tile shape), so no row or column needs a guard.  STREAM_OUT: the output is too large
+// for the last-level cache; it is stored with the streaming hint, which keeps it from displacing
+// the operands on its way out (nothing of it would still be cached for a consumer anyway).
 template <typename OutT, int MB, int NB, int WAVES_N, int PATCH_ROWS, bool JOINT, bool WAIT_VM, bool COOP = false,
-          bool FULL_TILE = false>
+          bool FULL_TILE = false, bool STREAM_OUT = false>
 struct TileEpilogue {
     static constexpr int WTN = NB * 32;               // columns of a wave strip
     static constexpr int SSTR = WTN + 8;              // floats per patch row: +8 puts lanes 0-31
@@ -89,6 +91,8 @@ struct TileEpilogue {
     float scale, bias[NB];      // y = scale * acc + bias  (scale = post*alpha, bias = post*b)
     bool whole_row;
     bool bounded;               // clamp activation with a narrow range feeds softmax / logsumexp
+    bool defer_lse = false;     // whole-row logsumexp: park the strip pairs, the caller merges them later
+    int lse_par = 0;            // exchange buffer the parked pairs of this tile go to
 
     __device__ __forceinline__ TileEpilogue(const TileArgs &a_, OutT *out_, float2 *xch_, float *patch_,
                                             int tile_rows_, int z, int m0_, int n0_, int tn_,
@@ -216,6 +220,16 @@ struct TileEpilogue {
                 for (int q = 0; q < NPG; ++q) put_stats<FULL>(grow0, q, s0[q], s1[q]);
                 return;
             }
+            if constexpr (NORM == FGE_NORM_LOGSUMEXP) {
+                if (defer_lse) {          // out is already final; only aux needs the other strips
+                    if (sub == 0) {
+#pragma unroll
+                        for (int q = 0; q < NPG; ++q)
+                            xch[(lse_par * tile_rows + qrow(grow0, q)) * WAVES_N + wave_n] = make_float2(s0[q], s1[q]);
+                    }
+                    return;
+                }
+            }
             exchange(grow0, s0, s1, OpMax::ident());
 #pragma unroll
             for (int q = 0; q < NPG; ++q) {
@@ -306,6 +320,22 @@ struct TileEpilogue {
             }
         }
     }
+    // Deferred whole-row logsumexp: merges the strip pairs that a tile (first row m0_prev) parked
+    // in exchange buffer `par`.  To be called by all threads after a workgroup barrier that
+    // follows that tile's epilogue; the buffer may be parked into again after the next barrier.
+    __device__ __forceinline__ void flush_lse(int tid, int par, int m0_prev) {
+        if (tid < tile_rows) {
+            const float2 *e = xch + (par * tile_rows + tid) * WAVES_N;
+            float m = e[0].x;
+#pragma unroll
+            for (int w = 1; w < WAVES_N; ++w) m = max_nc(m, e[w].x);
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < WAVES_N; ++w) sum += e[w].y * fast_exp(e[w].x - m);
+            if (m0_prev + tid < a.M) a.aux[row_base + m0_prev + tid] = m + __logf(sum);
+        }
+    }
+
     // norm_group with the runtime row-op code (and the clamp bound) turned into constants
     template <bool FULL> __device__ __forceinline__ void norm_dispatch(float (&v)[NPG][VEC], int grow0) {
         switch (a.norm + (bounded ? 8 : 0)) {
@@ -348,6 +378,15 @@ struct TileEpilogue {
         transpose_block<B>(blk, v);
     }
 
+    // 16-byte store of output; STREAM_OUT stores carry the streaming (non-temporal) hint.
+    static __device__ __forceinline__ void put16(OutT *o, const uint4 &u) {
+        if constexpr (STREAM_OUT) {
+            const u32x4 w = {u.x, u.y, u.z, u.w};
+            __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(o));
+        } else {
+            *reinterpret_cast<uint4 *>(o) = u;
+        }
+    }
     template <bool FULL> __device__ __forceinline__ void store_group(float (&v)[NPG][VEC], int grow0) {
 #pragma unroll
         for (int q = 0; q < NPG; ++q) {
@@ -355,10 +394,10 @@ struct TileEpilogue {
             if (FULL || grow < a.M) {
                 OutT *o = out + (int64_t)grow * a.ldo + gcol;
                 if constexpr (sizeof(OutT) == 2) {     // N is a multiple of 8: all or nothing
-                    if (FULL || ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
+                    if (FULL || ok4[0]) put16(o, Store<OutT>::pack(v[q]));
                 } else {
-                    if (FULL || ok4[0]) *reinterpret_cast<uint4 *>(o) = Store<OutT>::pack(v[q]);
-                    if (FULL || ok4[1]) *reinterpret_cast<uint4 *>(o + G4STEP) = Store<OutT>::pack(v[q] + 4);
+                    if (FULL || ok4[0]) put16(o, Store<OutT>::pack(v[q]));
+                    if (FULL || ok4[1]) put16(o + G4STEP, Store<OutT>::pack(v[q] + 4));
                 }
             }
         }
@@ -573,7 +612,8 @@ struct TileEpilogue {
                     static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
                     const int grow0 = trow0 + g * G * 32;
                     norm_dispatch<FULL>(v, grow0);
-                    if constexpr (WAIT_VM) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    // (once per tile: a second wait would sit behind the first group's own stores)
+                    if constexpr (WAIT_VM && g == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     store_group<FULL>(v, grow0);
                 });
             };

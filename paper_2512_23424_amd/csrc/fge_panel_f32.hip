@@ -2,16 +2,27 @@
 #include "fge_launch.h"
 #include "fge_panel_kernel.h"
 namespace fge {
-hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
+namespace {
+constexpr size_t LLC_BYTES = (size_t)256 << 20;     // memory-side cache in front of HBM
+
+template <typename OutT>
+void launch(dim3 grid, hipStream_t s, const TileArgs &a) {
     const bool full = a.M % PanelShape::BM == 0 && a.N == PanelShape::BN;
+    const bool stream = (size_t)a.M * a.N * sizeof(OutT) >= LLC_BYTES;
     const dim3 block(PanelShape::THREADS);
-    if (out_dtype == FGE_BF16) {
-        if (full) hipLaunchKernelGGL((panel_kernel<bf16_t, true>), grid, block, 0, s, a);
-        else      hipLaunchKernelGGL((panel_kernel<bf16_t, false>), grid, block, 0, s, a);
+    if (full) {
+        if (stream) hipLaunchKernelGGL((panel_kernel<OutT, true, true>), grid, block, 0, s, a);
+        else        hipLaunchKernelGGL((panel_kernel<OutT, true, false>), grid, block, 0, s, a);
     } else {
-        if (full) hipLaunchKernelGGL((panel_kernel<float, true>), grid, block, 0, s, a);
-        else      hipLaunchKernelGGL((panel_kernel<float, false>), grid, block, 0, s, a);
+        if (stream) hipLaunchKernelGGL((panel_kernel<OutT, false, true>), grid, block, 0, s, a);
+        else        hipLaunchKernelGGL((panel_kernel<OutT, false, false>), grid, block, 0, s, a);
     }
+}
+}  // namespace
+
+hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
+    if (out_dtype == FGE_BF16) launch<bf16_t>(grid, s, a);
+    else                       launch<float>(grid, s, a);
     return hipGetLastError();
 }
 }  // namespace fge

@@ -46,7 +46,8 @@ struct PanelShape {
 };
 
 // FULL: M is a multiple of 64 and N == 512, so the epilogue needs no row or column guards.
-template <typename OutT, bool FULL>
+// STREAM: the output is larger than the last-level cache and is stored with the streaming hint.
+template <typename OutT, bool FULL, bool STREAM>
 __global__ __launch_bounds__(PanelShape::THREADS)
 void panel_kernel(const TileArgs a) {
     constexpr int BM = PanelShape::BM, BN = PanelShape::BN, WAVES_N = PanelShape::WAVES_N;
@@ -55,7 +56,7 @@ void panel_kernel(const TileArgs a) {
     constexpr int XROWB = 256;                        // LDS bytes per X row: 64 fp32
     constexpr int XTILE = BM * XROWB;                 // 16 KB
     constexpr int X_LD = BM * 16 / NT;                // 16-byte chunks per thread per tile (2)
-    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, PANEL_JOINT, true, false, FULL>;
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, PANEL_JOINT, true, false, FULL, STREAM>;
 
     __shared__ __attribute__((aligned(16))) unsigned char xs[2 * XTILE];
     __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];
@@ -132,9 +133,15 @@ void panel_kernel(const TileArgs a) {
     __syncthreads();                                  // zero fill is complete
     if (tile < ntiles) dma_x(0, tile * BM);
     lds_dma_wait();
-    for (int it = 0; tile < ntiles; tile += gridDim.x, ++it) {
+    // Whole-row logsumexp leaves `out` final without any exchange between the waves; only aux
+    // needs all strips of a row.  The strips' pairs are parked in LDS and merged one iteration
+    // later, behind the barrier the loop has anyway.
+    epi.defer_lse = a.norm == FGE_NORM_LOGSUMEXP;
+    int it = 0;
+    for (; tile < ntiles; tile += gridDim.x, ++it) {
         const int buf = it & 1;
         __syncthreads();    // tile `it` has landed for every wave; reads of the other buffer are over
+        if (epi.defer_lse && it > 0) epi.flush_lse(tid, (it - 1) & 1, (tile - (int)gridDim.x) * BM);
         const int next = tile + gridDim.x;
         if (next < ntiles) dma_x(buf ^ 1, next * BM);
 
@@ -171,7 +178,12 @@ void panel_kernel(const TileArgs a) {
         }
         // the epilogue waits for the copy of the next tile before it queues its stores
         epi.m0 = tile * BM;
+        epi.lse_par = buf;
         epi.template tile<NT>(acc, 0, 0, tid);
+    }
+    if (epi.defer_lse && it > 0) {
+        __syncthreads();
+        epi.flush_lse(tid, (it - 1) & 1, (tile - (int)gridDim.x) * BM);
     }
 }
 
