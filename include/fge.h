@@ -83,8 +83,14 @@ typedef enum {
  *   kernel of a large problem finishes its rows itself: the column tiles of a row block run at
  *   the same time, exchange their row statistics through the workspace and wait for each other
  *   (a bounded wait).  That form assumes the launch has the device to itself; set this flag when
- *   several launches may overlap on the device (other streams, other processes). */
-enum { FGE_FLAG_TWO_PASS = 1 };
+ *   several launches may overlap on the device (other streams, other processes).
+ *   FGE_FLAG_IEEE_FP32 : multiply fp32 operands with the fp32 matrix instruction.  Without it
+ *   fp32 operands are multiplied on the bf16 matrix instruction after a split of each operand
+ *   into two bf16 terms, x = xh + xl:  x*w ~= xl*wh + xh*wl + xh*wh with fp32 accumulation.
+ *   Relative error per product <= about 2^-16.5 (a few 1e-5 on the final result, inside the
+ *   1e-4 the fp32 path is held to, and exact for operands that bf16 holds exactly) at less than a
+ *   fifth of the matrix-pipe time.  bf16 operands are not affected. */
+enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2 };
 
 typedef struct fge_params {
     int32_t M, N, K, batch;        /* rows per problem, columns, contraction length, problems  */

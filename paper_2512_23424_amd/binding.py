@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfge.so")
 ACT = {"none": 0, "relu": 1, "gelu_tanh": 2, "gelu_erf": 3, "silu": 4, "clamp": 5}
 NORM = {"none": 0, "softmax": 1, "layernorm": 2, "rmsnorm": 3, "logsumexp": 4}
 FLAG_TWO_PASS = 1
+FLAG_IEEE_FP32 = 2
 STATUS_OK = 0
 
 

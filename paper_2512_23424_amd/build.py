@@ -2,7 +2,7 @@
 
     python -m paper_2512_23424_amd.build [--force]
 
-The three translation units compile in parallel; the library is written next to this file so
+The translation units compile in parallel; the library is written next to this file so
 it travels with the source tree.  Packed-fp32 instruction selection is switched off for the
 device pass (the host pass prints a harmless "not a recognized feature" note)."""
 import os
@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfge.so")
 OBJDIR = os.path.join(HERE, "_build")
-UNITS = ["fge_api.hip", "fge_tiles_f32.hip", "fge_tiles_bf16.hip", "fge_panel_f32.hip"]
+UNITS = ["fge_api.hip", "fge_tiles_f32.hip", "fge_tiles_f32s.hip", "fge_tiles_bf16.hip", "fge_panel_f32.hip"]
 HEADERS = ["fge_device.h", "fge_epilogue.h", "fge_tile_kernel.h", "fge_panel_kernel.h", "fge_rowops.h", "fge_launch.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

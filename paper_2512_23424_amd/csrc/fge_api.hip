@@ -53,7 +53,7 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
     if (p == nullptr) return FGE_ERR_NULL;
     if (act < FGE_ACT_NONE || act > FGE_ACT_CLAMP) return FGE_ERR_BAD_ENUM;
     if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
-    if (p->flags & ~FGE_FLAG_TWO_PASS) return FGE_ERR_BAD_ENUM;
+    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32)) return FGE_ERR_BAD_ENUM;
     if ((p->in_dtype != FGE_F32 && p->in_dtype != FGE_BF16) ||
         (p->out_dtype != FGE_F32 && p->out_dtype != FGE_BF16))
         return FGE_ERR_BAD_ENUM;
@@ -80,9 +80,10 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
 
 constexpr int PANEL_MIN_ROWS = 4096;   // below this the persistent kernel cannot fill the chip
 
-int pick_tile(const Problem &pr, int in_dtype, int norm) {
-    // fp32, narrow K, row fits one tile, many rows: bound by the output stream
-    if (in_dtype == FGE_F32 && pr.K <= 64 && pr.N <= 512 && pr.batch == 1 && pr.M >= PANEL_MIN_ROWS)
+int pick_tile(const Problem &pr, int in_dtype, int norm, bool ieee_fp32) {
+    // fp32, narrow K, row fits one tile, many rows: bound by the output stream (the kernel for it
+    // exists with the split product only)
+    if (in_dtype == FGE_F32 && !ieee_fp32 && pr.K <= 64 && pr.N <= 512 && pr.batch == 1 && pr.M >= PANEL_MIN_ROWS)
         return TILE_PANEL;
     // A tile spanning the whole row finishes the row operation without a second pass.
     if (norm != FGE_NORM_NONE) {
@@ -114,7 +115,7 @@ Plan make_plan(const fge_params *p, int norm) {
         pr.batch = 1;
         pr.bsx = pr.bso = 0;
     }
-    pl.tile = pick_tile(pr, p->in_dtype, norm);
+    pl.tile = pick_tile(pr, p->in_dtype, norm, (p->flags & FGE_FLAG_IEEE_FP32) != 0);
     const TileInfo &ti = tile_info(pl.tile);
     pl.tiles_m = (pr.M + ti.bm - 1) / ti.bm;
     pl.tiles_n = (pr.N + ti.bn - 1) / ti.bn;
@@ -179,8 +180,9 @@ int launch_tiles(const TileArgs &a, const fge_params *p, const Plan &pl, hipStre
     }
     const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
                     a.coop ? 1u : (unsigned)pl.pr.batch);
-    const hipError_t e = p->in_dtype == FGE_BF16 ? launch_tile_bf16(pl.tile, p->out_dtype, grid, s, a)
-                                                 : launch_tile_f32(pl.tile, p->out_dtype, grid, s, a);
+    const hipError_t e = p->in_dtype == FGE_BF16       ? launch_tile_bf16(pl.tile, p->out_dtype, grid, s, a)
+                         : (p->flags & FGE_FLAG_IEEE_FP32) ? launch_tile_f32(pl.tile, p->out_dtype, grid, s, a)
+                                                           : launch_tile_f32s(pl.tile, p->out_dtype, grid, s, a);
     return hip_status(e);
 }
 
@@ -364,7 +366,8 @@ int fge_last_hip_error(void) { return g_last_hip; }
 
 const char *fge_tile_name(int fused, int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return nullptr;
-    return tile_info(make_plan(p, fused ? norm : FGE_NORM_NONE).tile).name;
+    const TileInfo &ti = tile_info(make_plan(p, fused ? norm : FGE_NORM_NONE).tile);
+    return p->in_dtype == FGE_F32 && !(p->flags & FGE_FLAG_IEEE_FP32) ? ti.name_split : ti.name;
 }
 
 }  // extern "C"

@@ -44,6 +44,20 @@ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, i
 // XOR pattern of the panel swizzle for a panel row.
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
+// 8 fp32 values (two 16-byte chunks) -> their bf16 high parts and the bf16 roundings of the
+// remainders, packed two per word in the order the bf16 matrix instruction takes them.
+__device__ __forceinline__ void split_bf16x8(const u32x4 &c0, const u32x4 &c1, u32x4 &hi, u32x4 &lo) {
+    const float f[8] = {as_f32(c0.x), as_f32(c0.y), as_f32(c0.z), as_f32(c0.w),
+                        as_f32(c1.x), as_f32(c1.y), as_f32(c1.z), as_f32(c1.w)};
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t hh = f32x2_to_bf16x2(f[2 * p], f[2 * p + 1]);
+        const float r0 = f[2 * p] - as_f32(hh << 16), r1 = f[2 * p + 1] - as_f32(hh & 0xFFFF0000u);
+        hi[p] = hh;
+        lo[p] = f32x2_to_bf16x2(r0, r1);
+    }
+}
+
 template <typename InT> struct Mma;
 template <> struct Mma<bf16_t> {
     __device__ static __forceinline__ void run(const u32x4 &a, const u32x4 &b, floatx16 &c) {
@@ -67,9 +81,16 @@ template <> struct Mma<float> {
 // FULL: M and N are multiples of BM and BN - the epilogue then runs without row or column guards.
 // Tiles of up to 64x128 are meant to run two workgroups per CU (second launch bound: waves per
 // SIMD), which caps their registers at 256.
-template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N, bool COOP = false, bool FULL = false>
+// SPLIT (fp32 operands only): the product runs on the bf16 matrix instruction with every fp32
+// operand split in two bf16 terms, x = xh + xl (bf16 rounding of the value and of the rest):
+//     x*w ~= xl*wh + xh*wl + xh*wh        (fp32 accumulate, the xl*wl term is dropped)
+// Relative error per product <= about 2^-16.5, against 2^-24 of the fp32 instruction, at less
+// than a fifth of its matrix-pipe time (3 x 8 passes per 16 k instead of 8 x 16 passes).
+template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N, bool COOP = false, bool FULL = false,
+          bool SPLIT = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN <= 64 * 128 ? 2 : 1))
 void tile_kernel(const TileArgs a) {
+    static_assert(!SPLIT || sizeof(InT) == 4, "only fp32 operands are split");
     constexpr int NT = 64 * WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int MB = WTM / 32, NB = WTN / 32;
@@ -78,6 +99,8 @@ void tile_kernel(const TileArgs a) {
     constexpr int CW = 16 / (int)sizeof(InT);        // elements per 16-byte chunk
     constexpr int A_LD = BM * 8 / NT, B_LD = BN * 8 / NT;
     constexpr int RSTEP = NT / 8;                    // rows between a thread's successive chunks
+    constexpr int FR = SPLIT ? 2 : 1;                // 16-byte chunks per fragment per k-step
+    constexpr int KS = 4 / FR;                       // k-steps per staged tile
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 16 == 0, "load plan");
     constexpr int STAGE = (BM + BN) * ROWB;
@@ -188,9 +211,12 @@ void tile_kernel(const TileArgs a) {
 
     // ---------------- fragment read plan
     const int fa_row = wave_m * WTM + l32, fb_row = wave_n * WTN + l32;
+    // chunk pair u (0..3) of a panel row: lanes 0-31 take chunk 2u, lanes 32-63 chunk 2u+1.
+    // A k-step consumes FR pairs.  Which k land in which lane and slot does not matter as long
+    // as both operands use the same assignment - the sum over k is complete either way.
     int fsw[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) fsw[t] = ((2 * t + h) ^ swz(l32)) << 4;
+    for (int u = 0; u < 4; ++u) fsw[u] = ((2 * u + h) ^ swz(l32)) << 4;
 
     floatx16 acc[MB][NB];
 #pragma unroll
@@ -201,19 +227,22 @@ void tile_kernel(const TileArgs a) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     // ---------------- mainloop
-    // Per staged tile: 4 k-steps of NM MFMAs.  Fragments of the next k-step are read from LDS
+    // Per staged tile: KS k-steps of NM MFMAs (3 NM with split operands).  Fragments of the next k-step are read from LDS
     // behind the first MFMAs of the current one (two register sets).  The single barrier of an
-    // iteration sits between k-steps 2 and 3, and k-step 3 already prefetches the next tile's
+    // iteration sits before the last k-step, and that k-step already prefetches the next tile's
     // first fragments, so no LDS or barrier latency is exposed.  sched_barrier pins this order:
     // left alone, the compiler sinks every fragment read next to its first use.
     constexpr int NM = MB * NB, NR = MB + NB;
-    u32x4 fr[2][NR];                                  // [0,MB): A fragments, [MB,NR): B fragments
+    u32x4 fr[2][NR][FR];                              // [0,MB): A fragments, [MB,NR): B fragments
     auto read_frag = [&](int buf, int t, int q) __attribute__((always_inline)) {
         const unsigned char *sA = smem + buf * STAGE + fa_row * ROWB;
         const unsigned char *sB = smem + buf * STAGE + BM * ROWB + fb_row * ROWB;
-        fr[t & 1][q] = q < MB
-            ? *reinterpret_cast<const u32x4 *>(sA + q * 32 * ROWB + fsw[t & 3])
-            : *reinterpret_cast<const u32x4 *>(sB + (q - MB) * 32 * ROWB + fsw[t & 3]);
+#pragma unroll
+        for (int c = 0; c < FR; ++c) {
+            const int off = fsw[(t & (KS - 1)) * FR + c];
+            fr[t & 1][q][c] = q < MB ? *reinterpret_cast<const u32x4 *>(sA + q * 32 * ROWB + off)
+                                     : *reinterpret_cast<const u32x4 *>(sB + (q - MB) * 32 * ROWB + off);
+        }
     };
     // prefetch order = order of first use: A0, B0..B(NB-1), A1..A(MB-1)
     auto slot = [&](int s) __attribute__((always_inline)) { return s == 0 ? 0 : (s <= NB ? MB + s - 1 : s - NB); };
@@ -224,9 +253,21 @@ void tile_kernel(const TileArgs a) {
     // wave's in-order issue, and with it its MFMAs, on the address unit
     auto kstep = [&]<int DMA_PART>(int t, bool do_read, int rbuf, bool do_dma, int dbuf, int dk0) __attribute__((always_inline)) {
         constexpr int HALF = NS / 2;
+        u32x4 hi[SPLIT ? NR : 1], lo[SPLIT ? NR : 1];
+        if constexpr (SPLIT) {
+#pragma unroll
+            for (int q = 0; q < NR; ++q) split_bf16x8(fr[t & 1][q][0], fr[t & 1][q][1], hi[q], lo[q]);
+        }
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
-            Mma<InT>::run(fr[t & 1][m / NB], fr[t & 1][MB + m % NB], acc[m / NB][m % NB]);
+            if constexpr (SPLIT) {                    // small terms first
+                floatx16 &c = acc[m / NB][m % NB];
+                Mma<bf16_t>::run(lo[m / NB], hi[MB + m % NB], c);
+                Mma<bf16_t>::run(hi[m / NB], lo[MB + m % NB], c);
+                Mma<bf16_t>::run(hi[m / NB], hi[MB + m % NB], c);
+            } else {
+                Mma<InT>::run(fr[t & 1][m / NB][0], fr[t & 1][MB + m % NB][0], acc[m / NB][m % NB]);
+            }
             if (do_read) {
 #pragma unroll
                 for (int s = (m * NR) / RSPAN; s < ((m + 1) * NR) / RSPAN && s < NR; ++s) read_frag(rbuf, t + 1, slot(s));
@@ -245,16 +286,15 @@ void tile_kernel(const TileArgs a) {
         __builtin_amdgcn_sched_barrier(0);
     };
     auto compute_last = [&](int buf) __attribute__((always_inline)) {   // fr[0] holds k-step 0
-        kstep.template operator()<0>(0, true, buf, false, 0, 0);
-        kstep.template operator()<0>(1, true, buf, false, 0, 0);
-        kstep.template operator()<0>(2, true, buf, false, 0, 0);
-        kstep.template operator()<0>(3, false, 0, false, 0, 0);
+        static_for<0, KS>([&]<int t>() __attribute__((always_inline)) {
+            kstep.template operator()<0>(t, t + 1 < KS, buf, false, 0, 0);
+        });
     };
     const int KF = a.K / BK;                          // full K tiles
     const bool ragged_k = (a.K % BK) != 0;            // plus one partial tile
     // Tile kt lives in buffer kt & 1.  Its copy is issued in two halves - behind the MFMAs of
-    // k-step 3 of tile kt-2 (right after the barrier that ends the reads of that buffer) and of
-    // k-step 0 of tile kt-1 - and is awaited just before the barrier in the middle of tile kt-1.
+    // the last k-step of tile kt-2 (right after the barrier that ends the reads of that buffer)
+    // and of k-step 0 of tile kt-1 - and is awaited just before the barrier of tile kt-1.
     if (KF > 0) { dma_tile(0, 0); lds_dma_wait(); }
     else        stage_tail(0, 0);
     __syncthreads();
@@ -268,12 +308,13 @@ void tile_kernel(const TileArgs a) {
     for (; kt + 1 < KF; ++kt) {                       // tile kt+1 is a full one
         const int buf = kt & 1;
         kstep.template operator()<2>(0, true, buf, true, buf ^ 1, (kt + 1) * BK);
-        kstep.template operator()<0>(1, true, buf, false, 0, 0);
-        kstep.template operator()<0>(2, true, buf, false, 0, 0);
+        static_for<1, KS - 1>([&]<int t>() __attribute__((always_inline)) {
+            kstep.template operator()<0>(t, true, buf, false, 0, 0);
+        });
         lds_dma_wait();                                   // tile kt+1 has landed in buf^1
         __syncthreads();                              // ... for every wave; reads of buf are over
         __builtin_amdgcn_sched_barrier(0);
-        kstep.template operator()<1>(3, true, buf ^ 1, kt + 2 < KF, buf, (kt + 2) * BK);   // t+1 == 4 -> k-step 0
+        kstep.template operator()<1>(KS - 1, true, buf ^ 1, kt + 2 < KF, buf, (kt + 2) * BK);   // then k-step 0
     }
     if (KF > 0 && ragged_k) {                         // last full tile, then the partial tile
         compute_last(kt & 1);

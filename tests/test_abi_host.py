@@ -76,7 +76,7 @@ def test_argument_errors_are_reported_before_any_launch():
     p.flags = B.FLAG_TWO_PASS
     # two-pass form: 8 column tiles x 2 waves across = 16 strips per row
     assert B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p)) == 4096 * (8 * 2) * 8
-    p.flags = 2
+    p.flags = 4
     assert _call(p, act=2, norm=2) == 2        # unknown flag bit
     p.flags = 0
     assert _call(p, act=2, norm=2) == 6
@@ -94,9 +94,12 @@ def test_status_strings_and_tile_names():
     assert len(seen) == 8 and all(seen)
     assert L.fge_status_string(99) == b"unknown status"
     assert L.fge_last_hip_error() == 0
-    assert B.fge_tile_name(True, 1, 1, _params(N=64, ldo=64)) == "64x64_w2x2"
+    # fp32 operands run the split-bf16 product unless the caller asks for the fp32 instruction
+    assert B.fge_tile_name(True, 1, 1, _params(N=64, ldo=64)) == "64x64_w2x2_splitbf16"
+    assert B.fge_tile_name(True, 1, 1, _params(N=64, ldo=64, flags=B.FLAG_IEEE_FP32)) == "64x64_w2x2"
+    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512, flags=B.FLAG_IEEE_FP32)) == "64x512_w1x4"
     assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512)) == "panel64x512_w1x8_splitbf16"
-    assert B.fge_tile_name(True, 5, 4, _params(M=1000, N=512, ldo=512)) == "64x512_w1x4"
+    assert B.fge_tile_name(True, 5, 4, _params(M=1000, N=512, ldo=512)) == "64x512_w1x4_splitbf16"
     big = _params(M=8192, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, in_dtype=1, out_dtype=1)
     assert B.fge_tile_name(True, 4, 3, big) == "256x256_w2x4"
     assert B.fge_fused_needs_finish(4, 3, big) is False      # the tiles finish their rows themselves

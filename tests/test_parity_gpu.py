@@ -106,7 +106,7 @@ def test_narrow_k_persistent_kernel(norm, shape):
 
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
 @pytest.mark.parametrize("case", [(I.BF16, 4100, 136, 4000, "256x256_w2x4"), (I.BF16, 2050, 200, 2040, "128x128_w2x2"),
-                                  (I.F32, 1030, 100, 2040, "64x128_w2x2")])
+                                  (I.F32, 1030, 100, 2040, "64x128_w2x2_splitbf16")])
 def test_split_rows_one_kernel_and_two_pass(norm, case):
     """Rows split over column tiles, large enough for the one-kernel form (the tiles of a row
     block exchange statistics and finish their rows themselves): ragged M / N / K, a partial
@@ -142,6 +142,27 @@ def test_split_rows_one_kernel_and_two_pass(norm, case):
     torch.cuda.synchronize()
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     assert np.array_equal(H.to_host_f64(outs[0]), H.run_gpu(w, t, "fused", dev=d)[0])
+
+
+@pytest.mark.parametrize("shape", [(300, 1024, 1024), (1030, 520, 2040), (77, 136, 328), (5000, 40, 328)])
+def test_fp32_matrix_instruction_on_request(shape):
+    """FGE_FLAG_IEEE_FP32 multiplies fp32 operands with the fp32 matrix instruction (products exact
+    in fp32): held to a gate five times tighter than the default split-bf16 product, which is
+    checked on the same inputs against the ordinary fp32 gate."""
+    M, K, N = shape
+    w = I.scaled(WL["cfg2"], M=M, K=K, N=N)
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    ref, _ = H.oracle_chain(w, t)
+    p = B.make_params(d["X"], d["W"], torch.empty(M, N, device="cuda"), flags=B.FLAG_IEEE_FP32)
+    assert "splitbf16" not in B.fge_tile_name(True, w.act, w.norm, p)
+    for path in ("fused", "unfused"):
+        got, _ = H.run_gpu(w, t, path, dev=d, flags=B.FLAG_IEEE_FP32)
+        err = H.C.max_rel_err(got, ref)
+        print(f"ieee {path} {shape}: {err:.3e}", flush=True)
+        assert np.isfinite(got).all() and err <= 2e-5
+        got, _ = H.run_gpu(w, t, path, dev=d)
+        H.check(w, got, None, ref, None, f"split {path}")
 
 
 def test_narrow_k_exact_integers():
@@ -207,7 +228,8 @@ def test_bf16_store_is_round_to_nearest_even():
     W = np.zeros((8, 8), np.float32); W[:, :] = np.diag(vals)
     Xd, Wd = torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda()
     out = torch.zeros(8, 8, dtype=torch.bfloat16, device="cuda")
-    p = B.make_params(Xd, Wd, out)
+    # (the fp32 matrix instruction: the split product keeps 16 bits of an operand, not all 24)
+    p = B.make_params(Xd, Wd, out, flags=B.FLAG_IEEE_FP32)
     B.fused_gemm_epilogue(Xd, Wd, None, "none", "none", p, out)
     torch.cuda.synchronize()
     got = out.view(torch.int16).cpu().numpy().view(np.uint16)
