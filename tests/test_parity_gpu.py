@@ -196,6 +196,22 @@ def test_edge_shapes():
         _parity(w, "unfused", label=f"edge-unfused {M}x{K}x{N}")
 
 
+@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+@pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
+def test_widest_row_and_smallest_problem(dt, norm):
+    """The widest row a row op accepts (N = 8192) and the smallest problem of each storage type
+    (one row, one 16-byte chunk of K, one 16-byte chunk of N)."""
+    kmin = 4 if dt == I.F32 else 8
+    for (M, K, N) in [(70, 72, 8192), (1, kmin, kmin)]:
+        w = I.Workload(name=f"wide{norm}", M=M, K=K, N=N, in_dtype=dt, out_dtype=dt, act=I.ACT_GELU_TANH,
+                       norm=norm, eps=1e-5,
+                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.05),
+                             "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1),
+                             "beta": ("normal", 0.0, 0.1)})
+        for path in ("fused", "unfused"):
+            _parity(w, path, label=f"{path} {M}x{K}x{N}")
+
+
 def test_strided_batch_not_flattened():
     """Batch with padding between problems and padded row strides goes through grid.z."""
     w = I.scaled(WL["cfg4"], M=70, K=64, N=264, batch=3)
