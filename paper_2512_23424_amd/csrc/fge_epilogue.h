@@ -185,7 +185,8 @@ struct TileEpilogue {
     // qrow(grow0, q).  Whole rows are normalised in place; split rows keep the parked value.
     // BOUNDED (softmax / logsumexp after a clamp): every value lies in [lo, hi] with hi - lo
     // small, so hi serves as the reference of the exponentials and no maximum is searched.
-    template <int NORM, bool FULL, bool BOUNDED> __device__ __forceinline__ void norm_group(float (&v)[NPG][VEC], int grow0) {
+    template <int NORM, bool FULL, bool BOUNDED>
+    __device__ __forceinline__ void norm_group(float (&v)[NPG][VEC], int grow0, float (&mkeep)[NPG]) {
         auto okc = [&](int e) __attribute__((always_inline)) { return FULL || ok4[e >> 2]; };
         float s0[NPG], s1[NPG];
         if constexpr (NORM == FGE_NORM_SOFTMAX || NORM == FGE_NORM_LOGSUMEXP) {
@@ -213,6 +214,7 @@ struct TileEpilogue {
                 }
                 s0[q] = ml[q];
                 s1[q] = allreduce_lanes<OpSum, LPR>(s);
+                mkeep[q] = ml[q];
             }
             if (!whole_row) {
                 // softmax parks exp(a - m_strip); the second pass rescales by exp(m_strip - m)/s
@@ -337,15 +339,16 @@ struct TileEpilogue {
     }
 
     // norm_group with the runtime row-op code (and the clamp bound) turned into constants
-    template <bool FULL> __device__ __forceinline__ void norm_dispatch(float (&v)[NPG][VEC], int grow0) {
+    // (mkeep: the references the exponentials of a softmax / logsumexp group were taken against)
+    template <bool FULL> __device__ __forceinline__ void norm_dispatch(float (&v)[NPG][VEC], int grow0, float (&mkeep)[NPG]) {
         switch (a.norm + (bounded ? 8 : 0)) {
         case FGE_NORM_NONE: case FGE_NORM_NONE + 8: break;
-        case FGE_NORM_SOFTMAX:       norm_group<FGE_NORM_SOFTMAX, FULL, false>(v, grow0); break;
-        case FGE_NORM_SOFTMAX + 8:   norm_group<FGE_NORM_SOFTMAX, FULL, true>(v, grow0); break;
-        case FGE_NORM_LOGSUMEXP:     norm_group<FGE_NORM_LOGSUMEXP, FULL, false>(v, grow0); break;
-        case FGE_NORM_LOGSUMEXP + 8: norm_group<FGE_NORM_LOGSUMEXP, FULL, true>(v, grow0); break;
-        case FGE_NORM_LAYERNORM: case FGE_NORM_LAYERNORM + 8: norm_group<FGE_NORM_LAYERNORM, FULL, false>(v, grow0); break;
-        default:                 norm_group<FGE_NORM_RMSNORM, FULL, false>(v, grow0); break;
+        case FGE_NORM_SOFTMAX:       norm_group<FGE_NORM_SOFTMAX, FULL, false>(v, grow0, mkeep); break;
+        case FGE_NORM_SOFTMAX + 8:   norm_group<FGE_NORM_SOFTMAX, FULL, true>(v, grow0, mkeep); break;
+        case FGE_NORM_LOGSUMEXP:     norm_group<FGE_NORM_LOGSUMEXP, FULL, false>(v, grow0, mkeep); break;
+        case FGE_NORM_LOGSUMEXP + 8: norm_group<FGE_NORM_LOGSUMEXP, FULL, true>(v, grow0, mkeep); break;
+        case FGE_NORM_LAYERNORM: case FGE_NORM_LAYERNORM + 8: norm_group<FGE_NORM_LAYERNORM, FULL, false>(v, grow0, mkeep); break;
+        default:                 norm_group<FGE_NORM_RMSNORM, FULL, false>(v, grow0, mkeep); break;
         }
     }
 
@@ -540,7 +543,8 @@ struct TileEpilogue {
     }
 
     // step 5 for one group
-    template <int NORM, bool FULL> __device__ __forceinline__ void finish_group(float (&v)[NPG][VEC], int grow0, const float2 *fin) {
+    template <int NORM, bool FULL>
+    __device__ __forceinline__ void finish_group(float (&v)[NPG][VEC], int grow0, const float2 *fin, const float (&mkeep)[NPG]) {
         float gam[VEC], bet[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; e += 4) {
@@ -554,10 +558,10 @@ struct TileEpilogue {
 #pragma unroll
         for (int q = 0; q < NPG; ++q) {
             const float2 r = fin[qrow(grow0, q)];
-            if constexpr (NORM == FGE_NORM_SOFTMAX) {
-                const float c = -r.x * LOG2E;
+            if constexpr (NORM == FGE_NORM_SOFTMAX) {      // v holds exp(a - mkeep)
+                const float f = exp_rel(mkeep[q], -r.x * LOG2E) * r.y;
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) v[q][e] = exp_rel(v[q][e], c) * r.y;
+                for (int e = 0; e < VEC; ++e) v[q][e] *= f;
             } else if constexpr (NORM == FGE_NORM_LAYERNORM) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) v[q][e] = (v[q][e] - r.x) * r.y * gam[e] + bet[e];
@@ -573,17 +577,17 @@ struct TileEpilogue {
     template <int NT>
     __device__ __forceinline__ void tile(floatx16 (&acc)[MB][NB], int trow0, int rowblock, int tid) {
         if constexpr (COOP) {
-            // step 1 (logsumexp leaves the activated values as they are: stored right away)
-            auto step1 = [&]<bool FULL>() __attribute__((always_inline)) {
-                static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
-                    float v[NPG][VEC];
-                    static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
-                    const int grow0 = trow0 + g * G * 32;
-                    norm_dispatch<FULL>(v, grow0);
-                    if (a.norm == FGE_NORM_LOGSUMEXP) store_group<FULL>(v, grow0);
-                });
-            };
-            step1.template operator()<FULL_TILE>();
+            // step 1.  The accumulators move to the row-wise layout for good: what step 5 needs -
+            // the activated values, for softmax already exp(a - strip maximum) - stays in these
+            // registers across the wait, so nothing is transposed or exponentiated twice.
+            // (logsumexp leaves the activated values as they are: stored right away)
+            float vall[MB / G][NPG][VEC], mkeep[MB / G][NPG];
+            static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+                static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], vall[g]); });
+                const int grow0 = trow0 + g * G * 32;
+                norm_dispatch<FULL_TILE>(vall[g], grow0, mkeep[g]);
+                if (a.norm == FGE_NORM_LOGSUMEXP) store_group<FULL_TILE>(vall[g], grow0);
+            });
             __syncthreads();
             if (tid < tile_rows) merge_strips(tid);
             arrive_and_wait(rowblock, tid);
@@ -591,27 +595,22 @@ struct TileEpilogue {
             merge_tiles<NT / (MB * 32 * (NT / 64 / WAVES_N))>(tid, fin);
             if (a.norm == FGE_NORM_LOGSUMEXP) return;
             __syncthreads();
-            auto step5 = [&]<bool FULL>() __attribute__((always_inline)) {
-                static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
-                    float v[NPG][VEC];
-                    static_for<0, G>([&]<int b>() __attribute__((always_inline)) { transpose_block<b>(acc[g * G + b], v); });
-                    const int grow0 = trow0 + g * G * 32;
-                    switch (a.norm) {
-                    case FGE_NORM_SOFTMAX:   finish_group<FGE_NORM_SOFTMAX, FULL>(v, grow0, fin); break;
-                    case FGE_NORM_LAYERNORM: finish_group<FGE_NORM_LAYERNORM, FULL>(v, grow0, fin); break;
-                    default:                 finish_group<FGE_NORM_RMSNORM, FULL>(v, grow0, fin); break;
-                    }
-                    store_group<FULL>(v, grow0);
-                });
-            };
-            step5.template operator()<FULL_TILE>();
+            static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
+                const int grow0 = trow0 + g * G * 32;
+                switch (a.norm) {
+                case FGE_NORM_SOFTMAX:   finish_group<FGE_NORM_SOFTMAX, FULL_TILE>(vall[g], grow0, fin, mkeep[g]); break;
+                case FGE_NORM_LAYERNORM: finish_group<FGE_NORM_LAYERNORM, FULL_TILE>(vall[g], grow0, fin, mkeep[g]); break;
+                default:                 finish_group<FGE_NORM_RMSNORM, FULL_TILE>(vall[g], grow0, fin, mkeep[g]); break;
+                }
+                store_group<FULL_TILE>(vall[g], grow0);
+            });
         } else {
             auto body = [&]<bool FULL>() __attribute__((always_inline)) {
                 static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
-                    float v[NPG][VEC];
+                    float v[NPG][VEC], mkeep[NPG];
                     static_for<0, G>([&]<int b>() __attribute__((always_inline)) { to_rows<b>(acc[g * G + b], v); });
                     const int grow0 = trow0 + g * G * 32;
-                    norm_dispatch<FULL>(v, grow0);
+                    norm_dispatch<FULL>(v, grow0, mkeep);
                     // (once per tile: a second wait would sit behind the first group's own stores)
                     if constexpr (WAIT_VM && g == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     store_group<FULL>(v, grow0);
