@@ -542,19 +542,24 @@ struct TileEpilogue {
         if (part == 0) fin[row] = make_float2(o0, o1);
     }
 
-    // step 5 for one group
-    template <int NORM, bool FULL>
-    __device__ __forceinline__ void finish_group(float (&v)[NPG][VEC], int grow0, const float2 *fin, const float (&mkeep)[NPG]) {
-        float gam[VEC], bet[VEC];
+    // gamma / beta of this lane's columns (ones / zeros where absent or not used by the row op)
+    template <bool FULL> __device__ __forceinline__ void load_affine(float (&gam)[VEC], float (&bet)[VEC]) {
 #pragma unroll
         for (int e = 0; e < VEC; e += 4) {
             floatx4 g = {1.0f, 1.0f, 1.0f, 1.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
             const int c = gcol + (e >> 2) * G4STEP;
-            if (NORM != FGE_NORM_SOFTMAX && (FULL || ok4[e >> 2]) && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + c);
-            if (NORM == FGE_NORM_LAYERNORM && (FULL || ok4[e >> 2]) && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + c);
+            const bool ok = FULL || ok4[e >> 2];
+            if (a.norm != FGE_NORM_SOFTMAX && ok && a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + c);
+            if (a.norm == FGE_NORM_LAYERNORM && ok && a.beta != nullptr) b = *reinterpret_cast<const floatx4 *>(a.beta + c);
             gam[e] = g[0]; gam[e + 1] = g[1]; gam[e + 2] = g[2]; gam[e + 3] = g[3];
             bet[e] = b[0]; bet[e + 1] = b[1]; bet[e + 2] = b[2]; bet[e + 3] = b[3];
         }
+    }
+
+    // step 5 for one group
+    template <int NORM>
+    __device__ __forceinline__ void finish_group(float (&v)[NPG][VEC], int grow0, const float2 *fin, const float (&mkeep)[NPG],
+                                                 const float (&gam)[VEC], const float (&bet)[VEC]) {
 #pragma unroll
         for (int q = 0; q < NPG; ++q) {
             const float2 r = fin[qrow(grow0, q)];
@@ -588,6 +593,9 @@ struct TileEpilogue {
                 norm_dispatch<FULL_TILE>(vall[g], grow0, mkeep[g]);
                 if (a.norm == FGE_NORM_LOGSUMEXP) store_group<FULL_TILE>(vall[g], grow0);
             });
+            // the affine vectors are the same for every group: fetched once, behind the wait
+            float gam[VEC], bet[VEC];
+            load_affine<FULL_TILE>(gam, bet);
             __syncthreads();
             if (tid < tile_rows) merge_strips(tid);
             arrive_and_wait(rowblock, tid);
@@ -598,9 +606,9 @@ struct TileEpilogue {
             static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {
                 const int grow0 = trow0 + g * G * 32;
                 switch (a.norm) {
-                case FGE_NORM_SOFTMAX:   finish_group<FGE_NORM_SOFTMAX, FULL_TILE>(vall[g], grow0, fin, mkeep[g]); break;
-                case FGE_NORM_LAYERNORM: finish_group<FGE_NORM_LAYERNORM, FULL_TILE>(vall[g], grow0, fin, mkeep[g]); break;
-                default:                 finish_group<FGE_NORM_RMSNORM, FULL_TILE>(vall[g], grow0, fin, mkeep[g]); break;
+                case FGE_NORM_SOFTMAX:   finish_group<FGE_NORM_SOFTMAX>(vall[g], grow0, fin, mkeep[g], gam, bet); break;
+                case FGE_NORM_LAYERNORM: finish_group<FGE_NORM_LAYERNORM>(vall[g], grow0, fin, mkeep[g], gam, bet); break;
+                default:                 finish_group<FGE_NORM_RMSNORM>(vall[g], grow0, fin, mkeep[g], gam, bet); break;
                 }
                 store_group<FULL_TILE>(vall[g], grow0);
             });

@@ -15,7 +15,7 @@ inline const TileInfo &tile_info(int id) {
     static const TileInfo t[TILE_COUNT] = {
         {64, 64, 256, 2, 0, "64x64_w2x2", "64x64_w2x2_splitbf16"},
         {64, 512, 256, 4, 0, "64x512_w1x4", "64x512_w1x4_splitbf16"},
-        {128, 128, 256, 2, 1, "128x128_w2x2", nullptr},
+        {128, 128, 256, 2, 2, "128x128_w2x2", nullptr},
         {256, 256, 512, 4, 1, "256x256_w2x4", nullptr},
         // persistent narrow-K kernel, fp32 operands, always the split product
         {64, 512, 512, 8, 0, "panel64x512_w1x8_splitbf16", "panel64x512_w1x8_splitbf16"},
