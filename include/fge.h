@@ -27,15 +27,19 @@
  *
  * Errors.  Every function returning int returns an fge_status.  All argument checks are done
  * on the host before anything is launched, so a non-zero status other than FGE_ERR_HIP means
- * that no work was enqueued.  A shape the kernels cannot handle yields FGE_ERR_UNSUPPORTED,
- * never a wrong result (the paper's benchmark section names silent divisibility assumptions
- * as the typical failure of generated kernels under dynamic shapes).
+ * that no work was enqueued.  FGE_ERR_UNSUPPORTED is left for requests beyond the index range
+ * (more than 2^30 rows in total).
  *
  * Supported set.  in_dtype, out_dtype in {FGE_F32, FGE_BF16} (accumulation and all epilogue
- * arithmetic in fp32; bf16 stores round to nearest even).  Any M >= 1, batch >= 1.  K, N
- * >= 1 with K*sizeof(in) and N*sizeof(out) multiples of 16 bytes; ldx, ldw, ldo and the batch
- * strides likewise multiples of 16 bytes; base pointers 16-byte aligned (else FGE_ERR_ALIGN).
- * Row operations need N <= 8192.  out must not alias X or W.
+ * arithmetic in fp32; bf16 stores round to nearest even).  Any M, N, K, batch >= 1 and any
+ * strides >= the extents.  Base pointers (X, W, b, out, gamma, beta, aux_out, workspace) must be
+ * 16-byte aligned (else FGE_ERR_ALIGN).  The fast kernels move data in 16-byte units: they run
+ * when K*sizeof(in), N*sizeof(out), ldx, ldw, ldo and the batch strides are multiples of 16 bytes
+ * and a row operation spans at most 8192 columns.  Every other shape is computed by
+ * element-granular kernels (plain fp32 FMA, not tuned; fge_tile_name reports
+ * "generic32x32_scalar"), never refused and never computed wrongly - the paper's benchmark
+ * section names silent divisibility assumptions as the typical failure of generated kernels
+ * under dynamic shapes.  out must not alias X or W.
  */
 #ifndef FGE_H
 #define FGE_H
@@ -53,7 +57,7 @@ typedef enum {
     FGE_ERR_BAD_ENUM = 2,     /* act / norm / dtype code or flag bit out of range            */
     FGE_ERR_BAD_SHAPE = 3,    /* M, N, K, batch <= 0, or a stride smaller than the extent    */
     FGE_ERR_UNSUPPORTED = 4,  /* valid request outside the supported set                     */
-    FGE_ERR_ALIGN = 5,        /* pointer or stride not 16-byte aligned                       */
+    FGE_ERR_ALIGN = 5,        /* a base pointer is not 16-byte aligned                       */
     FGE_ERR_WORKSPACE = 6,    /* workspace NULL or smaller than fge_workspace_bytes()        */
     FGE_ERR_HIP = 7           /* a launch failed; see fge_last_hip_error()                   */
 } fge_status;

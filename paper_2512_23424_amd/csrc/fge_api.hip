@@ -46,6 +46,8 @@ struct Plan {
     size_t ws_marks;             // bytes of arrival marks + fault word (cooperative form)
     size_t ws_buf;               // bytes of one out-shaped intermediate (unfused)
     int n_bufs;                  // intermediates the unfused path needs
+    bool generic;                // the element-granular kernels run this problem
+    size_t ws_generic;           // fused, generic: bytes of the fp32 rows x N intermediate
 };
 
 // Checks everything that does not depend on the path (fused / stage) being run.
@@ -64,18 +66,26 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
         if (p->batch_stride_o < (int64_t)(p->M - 1) * p->ldo + p->N) return FGE_ERR_BAD_SHAPE;
         if (need_in && p->batch_stride_x < (int64_t)(p->M - 1) * p->ldx + p->K) return FGE_ERR_BAD_SHAPE;
     }
-    const size_t is = esize(p->in_dtype), os = esize(p->out_dtype);
-    if ((p->N * os) % 16 || (p->ldo * os) % 16) return FGE_ERR_ALIGN;
-    if (p->batch > 1 && (p->batch_stride_o * os) % 16) return FGE_ERR_ALIGN;
-    if (need_in) {
-        if ((p->K * is) % 16 || (p->ldx * is) % 16 || (p->ldw * is) % 16) return FGE_ERR_ALIGN;
-        if (p->batch > 1 && (p->batch_stride_x * is) % 16) return FGE_ERR_ALIGN;
-    }
     if (!aligned16(p->gamma) || !aligned16(p->beta) || !aligned16(p->aux_out) || !aligned16(p->workspace))
         return FGE_ERR_ALIGN;
-    if (norm != FGE_NORM_NONE && p->N > MAX_ROWOP_N) return FGE_ERR_UNSUPPORTED;
     if ((int64_t)p->M * p->batch > (int64_t)INT32_MAX / 2) return FGE_ERR_UNSUPPORTED;
     return FGE_OK;
+}
+
+// Whether the vectorised kernels take this problem: every extent and stride they move in
+// 16-byte units must be a multiple of 16 bytes (base pointers are checked separately), and a
+// row operation needs the row to fit a wave's registers.  Everything else goes to the
+// element-granular kernels.
+bool vectorisable(const fge_params *p, int norm, bool need_in) {
+    const size_t is = esize(p->in_dtype), os = esize(p->out_dtype);
+    if ((p->N * os) % 16 || (p->ldo * os) % 16) return false;
+    if (p->batch > 1 && (p->batch_stride_o * os) % 16) return false;
+    if (need_in) {
+        if ((p->K * is) % 16 || (p->ldx * is) % 16 || (p->ldw * is) % 16) return false;
+        if (p->batch > 1 && (p->batch_stride_x * is) % 16) return false;
+    }
+    if (norm != FGE_NORM_NONE && p->N > MAX_ROWOP_N) return false;
+    return true;
 }
 
 constexpr int PANEL_MIN_ROWS = 4096;   // below this the persistent kernel cannot fill the chip
@@ -138,7 +148,24 @@ Plan make_plan(const fge_params *p, int norm) {
     pl.ws_buf = round256(extent * esize(p->out_dtype));
     // K2 writes straight into `out` when the row op leaves the activated values in place
     pl.n_bufs = (norm == FGE_NORM_NONE || norm == FGE_NORM_LOGSUMEXP) ? 1 : 2;
+    pl.generic = !vectorisable(p, norm, true);
+    if (pl.generic) {                // no tiles, no statistics: GEMM + activation to fp32, then the row op
+        pl.split = pl.coop = pl.needs_finish = false;
+        pl.ws_stats = pl.ws_marks = 0;
+        pl.ws_generic = norm == FGE_NORM_NONE ? 0 : round256((size_t)p->M * p->batch * p->N * sizeof(float));
+    }
     return pl;
+}
+
+GenArgs gen_args(const fge_params *p) {
+    GenArgs g{};
+    g.gamma = p->gamma; g.beta = p->beta; g.aux = p->aux_out;
+    g.M = p->M; g.N = p->N; g.K = p->K; g.batch = p->batch;
+    g.ldx = p->ldx; g.ldw = p->ldw; g.bsx = p->batch > 1 ? p->batch_stride_x : 0;
+    g.ldd = p->ldo; g.bsd = p->batch > 1 ? p->batch_stride_o : 0;
+    g.alpha = p->alpha; g.post = p->post_scale; g.lo = p->clamp_lo < p->clamp_hi ? p->clamp_lo : p->clamp_hi;
+    g.hi = p->clamp_hi; g.eps = p->eps;
+    return g;
 }
 
 // min(max(y, lo), hi) with lo > hi is hi for every y: the same as clamping to [hi, hi], which
@@ -219,11 +246,27 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
     if (!aligned16(X) || !aligned16(W) || !aligned16(out) || !aligned16(b)) return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
     const Plan pl = make_plan(p, norm);
+    if (plan_out) *plan_out = pl;
+    if (pl.generic) {
+        // GEMM + activation straight into out, or into an fp32 rows x N intermediate that the row
+        // kernel then reads (several passes) and turns into out
+        GenArgs g = gen_args(p);
+        g.X = X; g.W = W; g.b = b; g.act = act; g.norm = norm;
+        if (norm == FGE_NORM_NONE) {
+            g.dst = out;
+            return hip_status(launch_generic_gemm(p->in_dtype, p->out_dtype, s, g));
+        }
+        if (!p->workspace || p->workspace_bytes < pl.ws_generic) return FGE_ERR_WORKSPACE;
+        g.dst = p->workspace; g.ldd = p->N; g.bsd = (int64_t)p->M * p->N;
+        if ((rc = hip_status(launch_generic_gemm(p->in_dtype, FGE_F32, s, g)))) return rc;
+        GenArgs r = gen_args(p);
+        r.X = p->workspace; r.ldx = p->N; r.bsx = (int64_t)p->M * p->N; r.dst = out; r.norm = norm;
+        return hip_status(launch_generic_row(FGE_F32, p->out_dtype, s, r));
+    }
     if (pl.split) {
         if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
         if (!p->workspace || p->workspace_bytes < pl.ws_stats + pl.ws_marks) return FGE_ERR_WORKSPACE;
     }
-    if (plan_out) *plan_out = pl;
     return launch_tiles(tile_args(X, W, b, act, norm, p, pl, out), p, pl, s);
 }
 
@@ -251,6 +294,11 @@ int do_gemm_bias(const void *X, const void *W, const float *b, const fge_params 
     if (!X || !W || !Y) return FGE_ERR_NULL;
     if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(b)) return FGE_ERR_ALIGN;
     const Plan pl = make_plan(p, FGE_NORM_NONE);
+    if (pl.generic) {
+        GenArgs g = gen_args(p);
+        g.X = X; g.W = W; g.b = b; g.act = FGE_ACT_NONE; g.dst = Y;
+        return hip_status(launch_generic_gemm(p->in_dtype, p->out_dtype, s, g));
+    }
     return launch_tiles(tile_args(X, W, b, FGE_ACT_NONE, FGE_NORM_NONE, p, pl, Y), p, pl, s);
 }
 
@@ -259,6 +307,11 @@ int do_act(const void *Y, int act, const fge_params *p, void *A, hipStream_t s) 
     if (rc) return rc;
     if (!Y || !A) return FGE_ERR_NULL;
     if (!aligned16(Y) || !aligned16(A)) return FGE_ERR_ALIGN;
+    if (!vectorisable(p, FGE_NORM_NONE, false)) {
+        GenArgs g = gen_args(p);
+        g.X = Y; g.dst = A; g.act = act;
+        return hip_status(launch_generic_act(p->out_dtype, s, g));
+    }
     const Plan pl = make_plan(p, FGE_NORM_NONE);
     const RowArgs r = row_args(Y, A, act, FGE_NORM_NONE, p, pl);
     const int cw = p->out_dtype == FGE_BF16 ? 8 : 4;
@@ -277,6 +330,11 @@ int do_rownorm(const void *A, int norm, const fge_params *p, void *out, hipStrea
     if (!A || !out) return FGE_ERR_NULL;
     if (!aligned16(A) || !aligned16(out)) return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
+    if (!vectorisable(p, norm, false)) {
+        GenArgs g = gen_args(p);
+        g.X = A; g.ldx = p->ldo; g.bsx = g.bsd; g.dst = out; g.norm = norm;
+        return hip_status(launch_generic_row(p->out_dtype, p->out_dtype, s, g));
+    }
     const Plan pl = make_plan(p, norm);
     const RowArgs r = row_args(A, out, FGE_ACT_NONE, norm, p, pl);
     if (norm == FGE_NORM_NONE) {
@@ -345,7 +403,7 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return (size_t)-1;
     const Plan pl = make_plan(p, norm);
-    return fused ? pl.ws_stats + pl.ws_marks : pl.ws_buf * pl.n_bufs;
+    return fused ? (pl.generic ? pl.ws_generic : pl.ws_stats + pl.ws_marks) : pl.ws_buf * pl.n_bufs;
 }
 
 const char *fge_status_string(int status) {
@@ -355,7 +413,7 @@ const char *fge_status_string(int status) {
     case FGE_ERR_BAD_ENUM:    return "activation, row-op, dtype or flag code out of range";
     case FGE_ERR_BAD_SHAPE:   return "non-positive extent or stride smaller than the extent";
     case FGE_ERR_UNSUPPORTED: return "valid request outside the supported set";
-    case FGE_ERR_ALIGN:       return "pointer or stride not 16-byte aligned";
+    case FGE_ERR_ALIGN:       return "base pointer not 16-byte aligned";
     case FGE_ERR_WORKSPACE:   return "workspace missing or too small";
     case FGE_ERR_HIP:         return "HIP launch failed";
     default:                  return "unknown status";
@@ -366,7 +424,9 @@ int fge_last_hip_error(void) { return g_last_hip; }
 
 const char *fge_tile_name(int fused, int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return nullptr;
-    const TileInfo &ti = tile_info(make_plan(p, fused ? norm : FGE_NORM_NONE).tile);
+    const Plan pl = make_plan(p, fused ? norm : FGE_NORM_NONE);
+    if (pl.generic) return "generic32x32_scalar";
+    const TileInfo &ti = tile_info(pl.tile);
     return p->in_dtype == FGE_F32 && !(p->flags & FGE_FLAG_IEEE_FP32) ? ti.name_split : ti.name;
 }
 

@@ -1,22 +1,23 @@
 // Register epilogue shared by the GEMM kernels: scale + bias + activation on the accumulators,
-// in-tile row statistics, and either the final normalised store or the parked tile plus its
-// per-tile statistics for the second pass.
+// in-tile row statistics, and the store - final when the tile spans the row or when the tiles
+// of a row block finish their rows together (cooperative form), otherwise the parked tile plus
+// its per-strip statistics for the second pass.
 //
 // It works on one 32-row accumulator block of one wave at a time: `blk[j][r]` is the MFMA
 // 32x32 accumulator of column block j, whose element r lives at
 //     row = (r / 4) * 8 + (lane / 32) * 4 + r % 4,   column = j * 32 + lane % 32
 // of the block.  Scale, bias and activation are applied in that layout.  The block then goes
-// through a wave-private LDS patch into a row-wise layout - a lane holds 16 bytes' worth of
-// neighbouring columns of one row, LPR neighbouring lanes hold a row segment - in which the row
-// statistics need only log2(LPR) cross-lane steps per row and the global stores are 16 bytes
-// per lane over whole row segments.
+// through a wave-private LDS patch into a row-wise layout - a lane holds 8 columns of one row,
+// LPR neighbouring lanes hold a row segment - in which the row statistics need only log2(LPR)
+// cross-lane steps per row and the global stores are 16 bytes per lane over whole row segments.
 //
 // Every wave first reduces its own strip of WTN columns to a mergeable pair per row:
 //     softmax / logsumexp (m, s = sum exp(a - m)),  LayerNorm (mean, M2),  RMSNorm (sum a^2, -).
-// Rows split over several column tiles publish that pair per (row, strip) for the second
-// pass - no exchange between waves at all.  Rows that the tile spans are finished in place:
-// the WAVES_N pairs of a row meet in LDS (one barrier) and are merged by the same rules the
-// second pass uses (online-softmax merge, Chan's variance merge, plain sum).
+// Rows that the tile spans are finished in place: the WAVES_N pairs of a row meet in LDS (one
+// barrier) and are merged (online-softmax merge, Chan's variance merge, plain sum).  Rows split
+// over several column tiles either publish the pair per (row, strip) for the second pass - no
+// exchange between waves at all - or, in the cooperative form, merge per tile, exchange one pair
+// per (row, tile) through the workspace and finish from registers (see further down).
 #pragma once
 #include "fge_device.h"
 
@@ -27,7 +28,8 @@ struct TileArgs {
     const float *b, *gamma, *beta;
     void *out;
     float *aux;
-    float2 *ws;                 // [batch*M][tiles_n] per-tile row statistics (split rows only)
+    float2 *ws;                 // split rows: [batch*M][tiles_n * waves across] strip pairs for the
+                                // second pass, or [batch*M][tiles_n] tile pairs (cooperative form)
     int M, N, K;
     int64_t ldx, ldw, ldo, bsx, bso;
     float alpha, post, lo, hi, eps;

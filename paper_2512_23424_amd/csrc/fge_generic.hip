@@ -1,0 +1,167 @@
+// Element-granular kernels for shapes the vectorised kernels do not take: extents or strides
+// that are not multiples of 16 bytes, and row operations over rows wider than a wave's
+// registers hold.  They make every valid shape computable; they are not tuned (plain fp32 FMA
+// on the vector ALU, scalar loads and stores, rows re-read from memory per pass).
+//
+//   generic_gemm_kernel : dst = act(post*(alpha*X.W^T + b))   32x32 tile, LDS staged, fp32 FMA
+//   generic_act_kernel  : dst = act(src)                      elementwise
+//   generic_row_kernel  : out = rowop(src)                    one wave per row, passes over src
+#include "fge_launch.h"
+
+namespace fge {
+
+namespace {
+
+template <typename T> __device__ __forceinline__ const T *row_ptr(const void *base, int64_t rowg, int M,
+                                                                 int64_t ld, int64_t bs) {
+    return reinterpret_cast<const T *>(base) + (rowg / M) * bs + (rowg % M) * ld;
+}
+
+template <typename InT, typename DstT>
+__global__ __launch_bounds__(256) void generic_gemm_kernel(const GenArgs a) {
+    constexpr int T = 32;
+    __shared__ float xs[T][T + 1], ws[T][T + 1];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8 threads
+    const int n0 = blockIdx.x * T, m0 = blockIdx.y * T, z = blockIdx.z;
+    const InT *X = reinterpret_cast<const InT *>(a.X) + (int64_t)z * a.bsx;
+    const InT *W = reinterpret_cast<const InT *>(a.W);
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int k0 = 0; k0 < a.K; k0 += T) {
+        const int k = k0 + tx;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = ty + 8 * i;
+            xs[r][tx] = (m0 + r < a.M && k < a.K) ? Store<InT>::get(X + (int64_t)(m0 + r) * a.ldx + k) : 0.0f;
+            ws[r][tx] = (n0 + r < a.N && k < a.K) ? Store<InT>::get(W + (int64_t)(n0 + r) * a.ldw + k) : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int kk = 0; kk < T; ++kk) {
+            const float w = ws[tx][kk];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = fmaf(xs[ty + 8 * i][kk], w, acc[i]);
+        }
+        __syncthreads();
+    }
+    const int col = n0 + tx;
+    if (col >= a.N) return;
+    const float scale = a.post * a.alpha;
+    const float bias = a.b != nullptr ? a.post * a.b[col] : 0.0f;
+    DstT *dst = reinterpret_cast<DstT *>(a.dst) + (int64_t)z * a.bsd;
+    dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = m0 + ty + 8 * i;
+            if (row < a.M)
+                Store<DstT>::put(dst + (int64_t)row * a.ldd + col, activate<ACT>(scale * acc[i] + bias, a.lo, a.hi));
+        }
+    });
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void generic_act_kernel(const GenArgs a) {
+    const int64_t total = (int64_t)a.batch * a.M * a.N;
+    dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) {
+        for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+            const int64_t rowg = idx / a.N;
+            const int c = (int)(idx - rowg * a.N);
+            const int64_t off = (rowg / a.M) * a.bsd + (rowg % a.M) * a.ldd + c;
+            const float v = Store<T>::get(reinterpret_cast<const T *>(a.X) + off);
+            Store<T>::put(reinterpret_cast<T *>(a.dst) + off, activate<ACT>(v, a.lo, a.hi));
+        }
+    });
+}
+
+// src: rows x N of SrcT (row stride lds, batch stride bss); out: rows x N of OutT (ldd, bsd).
+template <typename SrcT, typename OutT>
+__global__ __launch_bounds__(256) void generic_row_kernel(const GenArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t rowg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (rowg >= (int64_t)a.batch * a.M) return;                       // wave-uniform
+    const SrcT *src = row_ptr<SrcT>(a.X, rowg, a.M, a.ldx, a.bsx);
+    OutT *out = const_cast<OutT *>(row_ptr<OutT>(a.dst, rowg, a.M, a.ldd, a.bsd));
+    const float inv_n = 1.0f / (float)a.N;
+    if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
+        float m = OpMax::ident();
+        for (int j = lane; j < a.N; j += 64) m = max_nc(m, Store<SrcT>::get(src + j));
+        m = allreduce64<OpMax>(m);
+        float s = 0.0f;
+        for (int j = lane; j < a.N; j += 64) s += fast_exp(Store<SrcT>::get(src + j) - m);
+        s = allreduce64<OpSum>(s);
+        if (a.norm == FGE_NORM_SOFTMAX) {
+            const float inv = 1.0f / s;
+            for (int j = lane; j < a.N; j += 64) Store<OutT>::put(out + j, fast_exp(Store<SrcT>::get(src + j) - m) * inv);
+        } else {
+            if (lane == 0) a.aux[rowg] = m + __logf(s);
+            if (reinterpret_cast<const void *>(src) != reinterpret_cast<const void *>(out))
+                for (int j = lane; j < a.N; j += 64) Store<OutT>::put(out + j, Store<SrcT>::get(src + j));
+        }
+    } else if (a.norm == FGE_NORM_LAYERNORM) {
+        float s = 0.0f;
+        for (int j = lane; j < a.N; j += 64) s += Store<SrcT>::get(src + j);
+        const float mean = allreduce64<OpSum>(s) * inv_n;
+        float d2 = 0.0f;
+        for (int j = lane; j < a.N; j += 64) {
+            const float d = Store<SrcT>::get(src + j) - mean;
+            d2 += d * d;
+        }
+        const float rstd = rsqrtf(allreduce64<OpSum>(d2) * inv_n + a.eps);
+        for (int j = lane; j < a.N; j += 64) {
+            const float g = a.gamma != nullptr ? a.gamma[j] : 1.0f, b = a.beta != nullptr ? a.beta[j] : 0.0f;
+            Store<OutT>::put(out + j, (Store<SrcT>::get(src + j) - mean) * rstd * g + b);
+        }
+    } else if (a.norm == FGE_NORM_RMSNORM) {
+        float s = 0.0f;
+        for (int j = lane; j < a.N; j += 64) {
+            const float v = Store<SrcT>::get(src + j);
+            s += v * v;
+        }
+        const float rr = rsqrtf(allreduce64<OpSum>(s) * inv_n + a.eps);
+        for (int j = lane; j < a.N; j += 64) {
+            const float g = a.gamma != nullptr ? a.gamma[j] : 1.0f;
+            Store<OutT>::put(out + j, Store<SrcT>::get(src + j) * rr * g);
+        }
+    } else {
+        if (reinterpret_cast<const void *>(src) != reinterpret_cast<const void *>(out))
+            for (int j = lane; j < a.N; j += 64) Store<OutT>::put(out + j, Store<SrcT>::get(src + j));
+    }
+}
+
+}  // namespace
+
+hipError_t launch_generic_gemm(int in_dtype, int dst_dtype, hipStream_t s, const GenArgs &a) {
+    const dim3 grid((unsigned)((a.N + 31) / 32), (unsigned)((a.M + 31) / 32), (unsigned)a.batch), block(256);
+    if (in_dtype == FGE_BF16) {
+        if (dst_dtype == FGE_BF16) hipLaunchKernelGGL((generic_gemm_kernel<bf16_t, bf16_t>), grid, block, 0, s, a);
+        else                       hipLaunchKernelGGL((generic_gemm_kernel<bf16_t, float>), grid, block, 0, s, a);
+    } else {
+        if (dst_dtype == FGE_BF16) hipLaunchKernelGGL((generic_gemm_kernel<float, bf16_t>), grid, block, 0, s, a);
+        else                       hipLaunchKernelGGL((generic_gemm_kernel<float, float>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_generic_act(int dtype, hipStream_t s, const GenArgs &a) {
+    const int64_t total = (int64_t)a.batch * a.M * a.N;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;                           // grid-stride beyond that
+    const dim3 grid((unsigned)blocks), block(256);
+    if (dtype == FGE_BF16) hipLaunchKernelGGL((generic_act_kernel<bf16_t>), grid, block, 0, s, a);
+    else                   hipLaunchKernelGGL((generic_act_kernel<float>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_generic_row(int src_dtype, int out_dtype, hipStream_t s, const GenArgs &a) {
+    const int64_t rows = (int64_t)a.batch * a.M;
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    if (src_dtype == FGE_BF16) {
+        if (out_dtype != FGE_BF16) return hipErrorInvalidValue;          // never asked for
+        hipLaunchKernelGGL((generic_row_kernel<bf16_t, bf16_t>), grid, block, 0, s, a);
+    } else {
+        if (out_dtype == FGE_BF16) hipLaunchKernelGGL((generic_row_kernel<float, bf16_t>), grid, block, 0, s, a);
+        else                       hipLaunchKernelGGL((generic_row_kernel<float, float>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace fge

@@ -32,6 +32,23 @@ hipError_t launch_tile_bf16(int tile, int out_dtype, dim3 grid, hipStream_t s, c
 // Defined in fge_panel_f32.hip: the persistent narrow-K kernel (grid = number of workgroups).
 hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 
+// Element-granular kernels (fge_generic.hip) for shapes the vectorised kernels do not take.
+// gemm: dst = act(post*(alpha*X.W^T + b)); act: dst = act(X) with X laid out like dst; row:
+// dst = rowop(X) with X rows x N at strides (ldx, bsx).  M rows per problem, `batch` problems.
+struct GenArgs {
+    const void *X, *W;
+    const float *b, *gamma, *beta;
+    void *dst;
+    float *aux;
+    int M, N, K, batch;
+    int64_t ldx, ldw, ldd, bsx, bsd;
+    float alpha, post, lo, hi, eps;
+    int act, norm;
+};
+hipError_t launch_generic_gemm(int in_dtype, int dst_dtype, hipStream_t s, const GenArgs &a);
+hipError_t launch_generic_act(int dtype, hipStream_t s, const GenArgs &a);
+hipError_t launch_generic_row(int src_dtype, int out_dtype, hipStream_t s, const GenArgs &a);
+
 // Workgroups of `kernel` the current device holds at the same time (0 if the query fails).
 inline int resident_workgroups(const void *kernel, int threads) {
     int per_cu = 0, dev = 0, cus = 0;

@@ -1,5 +1,5 @@
 // Row-wise and elementwise kernels: the unfused K2 (activation) and K3 (row operation), and
-// the light second pass of the fused path that merges per-tile row statistics.
+// the light second pass of the fused path that merges per-strip row statistics.
 // One 64-lane wavefront owns one row; data moves in 16-byte chunks per lane.
 #pragma once
 #include "fge_device.h"
@@ -11,7 +11,7 @@ struct RowArgs {
     void *out;
     const float *gamma, *beta;
     float *aux;
-    const float2 *ws;           // finish only: [batch*M][tiles_n]
+    const float2 *ws;           // finish only: [batch*M][tiles_n] strip pairs
     int M, N, batch;
     int64_t ldo, bso;
     float lo, hi, eps;

@@ -1,14 +1,14 @@
-// The tile kernel: MFMA mainloop with double-buffered LDS panels, accumulators kept in
-// registers through scale + bias + activation, in-tile row statistics, and either the final
-// normalised store (tile spans N) or a parked tile plus per-tile statistics for the light
-// second pass (row split over several column tiles).
+// The tile kernel: MFMA mainloop with double-buffered LDS panels filled by asynchronous
+// global -> LDS copies, accumulators kept in registers through scale + bias + activation and the
+// in-tile row statistics, then the store: final when the tile spans N or when the launch is the
+// cooperative one (the column tiles of a row block finish their rows together), otherwise a
+// parked tile plus per-strip statistics for the light second pass.
 //
 // One workgroup computes a BM x BN tile of  act(post_scale*(alpha*X.W^T + b)).
 // Waves are laid out WAVES_M x WAVES_N; each owns (BM/WAVES_M) x (BN/WAVES_N) outputs as
 // 32x32 MFMA blocks.  X rows feed the MFMA A operand and W rows the B operand, so in every
 // accumulator register the 32 lanes with equal lane/32 hold 32 neighbouring columns of one
-// output row: stores are 128-byte contiguous and a row reduction is lane-local over the
-// wave's column blocks, then 5 cross-lane steps, then one LDS exchange between waves.
+// output row.
 //
 // LDS panel layout (both operands): row-major, 128 bytes of K per row (64 bf16 / 32 fp32),
 // the eight 16-byte chunks of a row stored at chunk ^ ((row >> 1) & 7): the 16-byte fragment

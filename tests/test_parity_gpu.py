@@ -212,6 +212,53 @@ def test_widest_row_and_smallest_problem(dt, norm):
             _parity(w, path, label=f"{path} {M}x{K}x{N}")
 
 
+@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (33, 17, 65), (100, 101, 250), (70, 63, 1001),
+                                   (40, 72, 9000)])
+def test_any_shape_takes_the_element_granular_kernels(dt, shape):
+    """Extents that are not multiples of 16 bytes (and a row op over more than 8192 columns) are
+    computed by the element-granular kernels: every row op, both paths, against the oracle."""
+    M, K, N = shape
+    for norm in NORMS:
+        act = I.ACT_GELU_TANH if norm in (I.NORM_NONE, I.NORM_LAYERNORM) else I.ACT_CLAMP
+        w = I.Workload(name=f"any{norm}", M=M, K=K, N=N, in_dtype=dt, out_dtype=dt, act=act, norm=norm,
+                       alpha=0.5, post_scale=1.5, clamp_lo=-1.0, clamp_hi=2.0, eps=1e-5,
+                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1),
+                             "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1),
+                             "beta": ("normal", 0.0, 0.1)})
+        t = I.generate(w)
+        d = {k: H.to_device(v) for k, v in t.items()}
+        p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(dt), device="cuda"))
+        if norm != I.NORM_NONE or N != 9000:
+            assert B.fge_tile_name(True, act, norm, p) == "generic32x32_scalar"
+        ref, raux = H.oracle_chain(w, t)
+        for path in ("fused", "unfused"):
+            got, gaux = H.run_gpu(w, t, path, dev=d)
+            H.check(w, got, gaux, ref, raux, f"any-shape {path} {shape} norm{norm}")
+
+
+def test_unaligned_strides_and_odd_batches():
+    """Aligned extents but row and batch strides that are not multiples of 16 bytes: padding is
+    left untouched, results match the oracle."""
+    w = I.scaled(WL["cfg2"], M=50, K=64, N=128, batch=3)
+    t = I.generate(w)
+    ref, _ = H.oracle_chain(w, t)
+    Xd = torch.zeros(3, 53, 67, device="cuda"); Xd[:, :50, :64] = torch.from_numpy(t["X"]).cuda().view(3, 50, 64)
+    Wd = torch.zeros(128, 65, device="cuda"); Wd[:, :64] = torch.from_numpy(t["W"]).cuda()
+    bd, gd, be = (torch.from_numpy(t[k]).cuda() for k in ("b", "gamma", "beta"))
+    for path, fn in (("fused", B.fused_gemm_epilogue), ("unfused", B.unfused_gemm_epilogue)):
+        outd = torch.full((3, 51, 131), float("nan"), device="cuda")
+        X, W, out = Xd[:, :50, :64], Wd[:, :64], outd[:, :50, :128]
+        p = B.make_params(X, W, out, eps=w.eps, gamma=gd, beta=be)
+        assert B.fge_tile_name(path == "fused", w.act, w.norm, p) == "generic32x32_scalar"
+        ws = torch.empty(max(B.fge_workspace_bytes(path == "fused", w.act, w.norm, p), 16), dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+        fn(X, W, bd, w.act, w.norm, p, out)
+        torch.cuda.synchronize()
+        H.check(w, H.to_host_f64(out).reshape(-1, 128), None, ref, None, f"odd strides {path}")
+        assert torch.isnan(outd[:, 50:, :]).all() and torch.isnan(outd[:, :, 128:]).all()
+
+
 def test_strided_batch_not_flattened():
     """Batch with padding between problems and padded row strides goes through grid.z."""
     w = I.scaled(WL["cfg4"], M=70, K=64, N=264, batch=3)
