@@ -23,7 +23,9 @@
  * may overlap must not share one.
  *
  * Asynchrony.  Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
- * the default stream) and return; they never synchronise the device.
+ * the default stream) and return; they never synchronise the device.  Calls may be captured
+ * into a HIP graph (nothing is allocated, no memset node is recorded); on a capturing stream
+ * split rows always take the two-pass form, and fge_workspace_bytes covers both forms.
  *
  * Errors.  Every function returning int returns an fge_status.  All argument checks are done
  * on the host before anything is launched, so a non-zero status other than FGE_ERR_HIP means

@@ -115,7 +115,9 @@ int pick_tile(const Problem &pr, int in_dtype, int norm, bool ieee_fp32) {
     return TILE_64x64;
 }
 
-Plan make_plan(const fge_params *p, int norm) {
+// two_pass: finish split rows with the second kernel even where the cooperative form exists
+// (asked for by flag, or the stream is being captured into a graph).
+Plan make_plan(const fge_params *p, int norm, bool two_pass = false) {
     Plan pl{};
     Problem &pr = pl.pr;
     pr = Problem{p->M, p->N, p->K, p->batch, p->ldx, p->ldw, p->ldo,
@@ -133,7 +135,7 @@ Plan make_plan(const fge_params *p, int norm) {
     // cooperative form: the column tiles of a row block must all be in flight at once, so the
     // grid is a whole number of row blocks that fits the chip
     const int capacity = NUM_CU * ti.coop_per_cu;
-    pl.coop = pl.split && !(p->flags & FGE_FLAG_TWO_PASS) && tile_has_coop(pl.tile, p->in_dtype) && capacity >= pl.tiles_n;
+    pl.coop = pl.split && !two_pass && !(p->flags & FGE_FLAG_TWO_PASS) && tile_has_coop(pl.tile, p->in_dtype) && capacity >= pl.tiles_n;
     if (pl.coop) {
         const int64_t total = (int64_t)pl.tiles_m * pl.tiles_n * pr.batch;
         const int64_t g = (int64_t)(capacity / pl.tiles_n) * pl.tiles_n;
@@ -157,6 +159,15 @@ Plan make_plan(const fge_params *p, int norm) {
     return pl;
 }
 
+// Workspace of the fused path: enough for either form of split rows, since a launch on a
+// stream under graph capture takes the two-pass form whatever the flags say.
+size_t fused_workspace(const fge_params *p, int norm) {
+    const Plan p1 = make_plan(p, norm, false), p2 = make_plan(p, norm, true);
+    if (p1.generic) return p1.ws_generic;
+    const size_t a = p1.ws_stats + p1.ws_marks, b = p2.ws_stats + p2.ws_marks;
+    return a > b ? a : b;
+}
+
 GenArgs gen_args(const fge_params *p) {
     GenArgs g{};
     g.gamma = p->gamma; g.beta = p->beta; g.aux = p->aux_out;
@@ -171,6 +182,14 @@ GenArgs gen_args(const fge_params *p) {
 // min(max(y, lo), hi) with lo > hi is hi for every y: the same as clamping to [hi, hi], which
 // lets the kernels use a median-of-three for the clamp.
 inline float clamp_low(const fge_params *p) { return p->clamp_lo < p->clamp_hi ? p->clamp_lo : p->clamp_hi; }
+
+// A replayed graph launches with the arguments recorded at capture time, generation number
+// included, so the arrival marks of one replay would satisfy the next: the cooperative form is
+// not used on a stream that is being captured.
+bool capturing(hipStream_t s) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    return hipStreamIsCapturing(s, &st) == hipSuccess && st != hipStreamCaptureStatusNone;
+}
 
 int hip_status(hipError_t e) {
     if (e == hipSuccess) return FGE_OK;
@@ -245,7 +264,7 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
     if (!X || !W || !out) return FGE_ERR_NULL;
     if (!aligned16(X) || !aligned16(W) || !aligned16(out) || !aligned16(b)) return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
-    const Plan pl = make_plan(p, norm);
+    const Plan pl = make_plan(p, norm, capturing(s));
     if (plan_out) *plan_out = pl;
     if (pl.generic) {
         // GEMM + activation straight into out, or into an fp32 rows x N intermediate that the row
@@ -265,7 +284,7 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
     }
     if (pl.split) {
         if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
-        if (!p->workspace || p->workspace_bytes < pl.ws_stats + pl.ws_marks) return FGE_ERR_WORKSPACE;
+        if (!p->workspace || p->workspace_bytes < fused_workspace(p, norm)) return FGE_ERR_WORKSPACE;
     }
     return launch_tiles(tile_args(X, W, b, act, norm, p, pl, out), p, pl, s);
 }
@@ -276,10 +295,10 @@ int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream
     if (!out) return FGE_ERR_NULL;
     if (!aligned16(out)) return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
-    const Plan pl = make_plan(p, norm);
+    const Plan pl = make_plan(p, norm, capturing(s));
     if (!pl.needs_finish) return FGE_OK;
     if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
-    if (!p->workspace || p->workspace_bytes < pl.ws_stats) return FGE_ERR_WORKSPACE;
+    if (!p->workspace || p->workspace_bytes < fused_workspace(p, norm)) return FGE_ERR_WORKSPACE;
     const RowArgs r = row_args(out, out, act, norm, p, pl);
     const int64_t rows = (int64_t)r.batch * r.M;
     const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
@@ -403,7 +422,7 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return (size_t)-1;
     const Plan pl = make_plan(p, norm);
-    return fused ? (pl.generic ? pl.ws_generic : pl.ws_stats + pl.ws_marks) : pl.ws_buf * pl.n_bufs;
+    return fused ? fused_workspace(p, norm) : pl.ws_buf * pl.n_bufs;
 }
 
 const char *fge_status_string(int status) {

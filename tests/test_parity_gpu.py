@@ -299,6 +299,39 @@ def test_bf16_store_is_round_to_nearest_even():
     assert np.array_equal(np.diag(got), I.f32_to_bf16_bits(vals))
 
 
+def test_graph_capture_and_replay():
+    """The fused call can be captured into a graph: nothing is allocated or cleared with memset
+    nodes, and on a capturing stream split rows take the two-pass form (a replay repeats the
+    recorded arguments, so arrival marks could not tell one replay from the next).  Every
+    replay - with eager work and synchronisations between them - reproduces the eager result."""
+    for (dt, M, K, N) in [(I.BF16, 4100, 136, 4000), (I.F32, 1030, 100, 2040), (I.F32, 5000, 40, 328)]:
+        w = I.Workload(name="graph", M=M, K=K, N=N, in_dtype=dt, out_dtype=dt, act=I.ACT_SILU,
+                       norm=I.NORM_RMSNORM, eps=1e-5,
+                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1), "gamma": ("normal", 1.0, 0.1)})
+        t = I.generate(w)
+        d = {k: H.to_device(v) for k, v in t.items()}
+        eager = torch.empty(M, N, dtype=H.tdtype(dt), device="cuda")
+        out = torch.empty_like(eager)
+        p = B.make_params(d["X"], d["W"], out, eps=w.eps, gamma=d["gamma"])
+        ws = torch.empty(max(B.fge_workspace_bytes(True, w.act, w.norm, p), 16), dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+        B.fused_gemm_epilogue(d["X"], d["W"], None, w.act, w.norm, p, eager)
+        torch.cuda.synchronize()
+        ref, _ = H.oracle_chain(w, t)
+        H.check(w, H.to_host_f64(eager), None, ref, None, "eager")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            B.fused_gemm_epilogue(d["X"], d["W"], None, w.act, w.norm, p, out)
+        for rep in range(3):
+            out.fill_(float("nan"))
+            ws.random_(0, 255)                      # eager work on the same buffers in between
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            H.check(w, H.to_host_f64(out), None, ref, None, f"replay {rep}")
+        del g
+
+
 def test_run_to_run_bitwise_determinism():
     for name in ("cfg2", "cfg4"):
         w = I.scaled(WL[name], **SMALL[name])
