@@ -30,10 +30,12 @@
  * Errors.  Every function returning int returns an fge_status.  All argument checks are done
  * on the host before anything is launched, so a non-zero status other than FGE_ERR_HIP means
  * that no work was enqueued.  FGE_ERR_UNSUPPORTED is left for requests beyond the index range
- * (more than 2^30 rows in total).
+ * (more than 2^30 rows in total) and operand / output type pairs outside the set below.
  *
- * Supported set.  in_dtype, out_dtype in {FGE_F32, FGE_BF16} (accumulation and all epilogue
- * arithmetic in fp32; bf16 stores round to nearest even).  Any M, N, K, batch >= 1 and any
+ * Supported set.  in_dtype in {FGE_F32, FGE_BF16, FGE_F16}; out_dtype FGE_F32 or the 16-bit type
+ * that goes with the operands (FGE_BF16 with fp32 and bf16 operands, FGE_F16 with fp16 operands;
+ * other pairs yield FGE_ERR_UNSUPPORTED).  Accumulation and all epilogue arithmetic are fp32;
+ * 16-bit stores round to nearest even.  Any M, N, K, batch >= 1 and any
  * strides >= the extents.  Base pointers (X, W, b, out, gamma, beta, aux_out, workspace) must be
  * 16-byte aligned (else FGE_ERR_ALIGN).  The fast kernels move data in 16-byte units: they run
  * when K*sizeof(in), N*sizeof(out), ldx, ldw, ldo and the batch strides are multiples of 16 bytes
@@ -64,7 +66,7 @@ typedef enum {
     FGE_ERR_HIP = 7           /* a launch failed; see fge_last_hip_error()                   */
 } fge_status;
 
-typedef enum { FGE_F32 = 0, FGE_BF16 = 1 } fge_dtype;
+typedef enum { FGE_F32 = 0, FGE_BF16 = 1, FGE_F16 = 2 } fge_dtype;
 
 /* Activations (step A = act(Y)).  GELU_TANH: 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3)));
  * GELU_ERF: 0.5 y (1 + erf(y / sqrt 2)); SILU: y / (1 + exp(-y)); CLAMP: min(max(y, lo), hi). */

@@ -92,6 +92,8 @@ def _dt(t: torch.Tensor) -> int:
         return _codes.F32
     if t.dtype == torch.bfloat16:
         return _codes.BF16
+    if t.dtype == torch.float16:
+        return _codes.F16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 

@@ -23,7 +23,7 @@ constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 CUs
 constexpr int MAX_ROWOP_N = 8192;    // a row must fit the register-resident row kernels
 constexpr int MAX_SPLIT = 1024;      // column strips per row the second pass will merge
 
-inline size_t esize(int dt) { return dt == FGE_BF16 ? 2 : 4; }
+inline size_t esize(int dt) { return dt == FGE_F32 ? 4 : 2; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -56,9 +56,11 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
     if (act < FGE_ACT_NONE || act > FGE_ACT_CLAMP) return FGE_ERR_BAD_ENUM;
     if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
     if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32)) return FGE_ERR_BAD_ENUM;
-    if ((p->in_dtype != FGE_F32 && p->in_dtype != FGE_BF16) ||
-        (p->out_dtype != FGE_F32 && p->out_dtype != FGE_BF16))
+    if (p->in_dtype < FGE_F32 || p->in_dtype > FGE_F16 || p->out_dtype < FGE_F32 || p->out_dtype > FGE_F16)
         return FGE_ERR_BAD_ENUM;
+    // out is fp32 or the 16-bit type that goes with the operands (bf16 with fp32 / bf16, fp16 with fp16)
+    if (need_in && p->out_dtype != FGE_F32 && p->out_dtype != (p->in_dtype == FGE_F16 ? FGE_F16 : FGE_BF16))
+        return FGE_ERR_UNSUPPORTED;
     if (p->M <= 0 || p->N <= 0 || p->K <= 0 || p->batch <= 0) return FGE_ERR_BAD_SHAPE;
     if (p->ldo < p->N) return FGE_ERR_BAD_SHAPE;
     if (need_in && (p->ldx < p->K || p->ldw < p->K)) return FGE_ERR_BAD_SHAPE;
@@ -105,8 +107,8 @@ int pick_tile(const Problem &pr, int in_dtype, int norm, bool ieee_fp32) {
     // which share a CU so that one's epilogue hides behind another's MFMAs.
     const int bf16_order[3] = {TILE_256x256, TILE_128x128, TILE_64x64};
     const int f32_order[2] = {TILE_64x128, TILE_64x64};
-    const int *order = in_dtype == FGE_BF16 ? bf16_order : f32_order;
-    const int n_order = in_dtype == FGE_BF16 ? 3 : 2;
+    const int *order = in_dtype != FGE_F32 ? bf16_order : f32_order;     // 16-bit operands share the list
+    const int n_order = in_dtype != FGE_F32 ? 3 : 2;
     for (int t = 0; t < n_order; ++t) {
         const TileInfo &ti = tile_info(order[t]);
         const int64_t n = (int64_t)((pr.M + ti.bm - 1) / ti.bm) * ((pr.N + ti.bn - 1) / ti.bn) * pr.batch;
@@ -227,6 +229,7 @@ int launch_tiles(const TileArgs &a, const fge_params *p, const Plan &pl, hipStre
     const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
                     a.coop ? 1u : (unsigned)pl.pr.batch);
     const hipError_t e = p->in_dtype == FGE_BF16       ? launch_tile_bf16(pl.tile, p->out_dtype, grid, s, a)
+                         : p->in_dtype == FGE_F16      ? launch_tile_f16(pl.tile, p->out_dtype, grid, s, a)
                          : (p->flags & FGE_FLAG_IEEE_FP32) ? launch_tile_f32(pl.tile, p->out_dtype, grid, s, a)
                                                            : launch_tile_f32s(pl.tile, p->out_dtype, grid, s, a);
     return hip_status(e);
@@ -302,8 +305,9 @@ int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream
     const RowArgs r = row_args(out, out, act, norm, p, pl);
     const int64_t rows = (int64_t)r.batch * r.M;
     const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
-    if (p->out_dtype == FGE_BF16) hipLaunchKernelGGL((finish_kernel<bf16_t>), grid, block, 0, s, r);
-    else                          hipLaunchKernelGGL((finish_kernel<float>), grid, block, 0, s, r);
+    if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((finish_kernel<bf16_t>), grid, block, 0, s, r);
+    else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((finish_kernel<f16_t>), grid, block, 0, s, r);
+    else                              hipLaunchKernelGGL((finish_kernel<float>), grid, block, 0, s, r);
     return hip_status(hipGetLastError());
 }
 
@@ -333,13 +337,14 @@ int do_act(const void *Y, int act, const fge_params *p, void *A, hipStream_t s) 
     }
     const Plan pl = make_plan(p, FGE_NORM_NONE);
     const RowArgs r = row_args(Y, A, act, FGE_NORM_NONE, p, pl);
-    const int cw = p->out_dtype == FGE_BF16 ? 8 : 4;
+    const int cw = p->out_dtype == FGE_F32 ? 4 : 8;
     const int64_t chunks = (int64_t)r.batch * r.M * (r.N / cw);
     int64_t blocks = (chunks + 255) / 256;
     if (blocks > NUM_CU * 32) blocks = NUM_CU * 32;      // grid-stride beyond that
     const dim3 grid((unsigned)blocks), block(256);
-    if (p->out_dtype == FGE_BF16) hipLaunchKernelGGL((act_kernel<bf16_t>), grid, block, 0, s, r);
-    else                          hipLaunchKernelGGL((act_kernel<float>), grid, block, 0, s, r);
+    if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((act_kernel<bf16_t>), grid, block, 0, s, r);
+    else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((act_kernel<f16_t>), grid, block, 0, s, r);
+    else                              hipLaunchKernelGGL((act_kernel<float>), grid, block, 0, s, r);
     return hip_status(hipGetLastError());
 }
 
@@ -360,7 +365,9 @@ int do_rownorm(const void *A, int norm, const fge_params *p, void *out, hipStrea
         if (A == out) return FGE_OK;
         return do_act(A, FGE_ACT_NONE, p, out, s);       // plain copy
     }
-    return p->out_dtype == FGE_BF16 ? launch_rownorm<bf16_t>(r, s) : launch_rownorm<float>(r, s);
+    return p->out_dtype == FGE_BF16  ? launch_rownorm<bf16_t>(r, s)
+           : p->out_dtype == FGE_F16 ? launch_rownorm<f16_t>(r, s)
+                                     : launch_rownorm<float>(r, s);
 }
 
 }  // namespace

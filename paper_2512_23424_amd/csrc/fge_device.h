@@ -11,9 +11,11 @@ namespace fge {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct bf16_t { uint16_t bits; };   // storage only; arithmetic is always fp32
+struct f16_t { uint16_t bits; };    // IEEE half, storage only
 
 __device__ __forceinline__ float as_f32(uint32_t v) { return __builtin_bit_cast(float, v); }
 __device__ __forceinline__ uint32_t as_u32(float v) { return __builtin_bit_cast(uint32_t, v); }
@@ -81,6 +83,37 @@ template <> struct Store<bf16_t> {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             w[i] = f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+template <> struct Store<f16_t> {
+    static constexpr int CW = 8;
+    typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    // fp32 -> fp16 rounds to nearest even (the conversion instruction under the default mode)
+    __device__ static __forceinline__ void put(f16_t *p, float v) {
+        p->bits = __builtin_bit_cast(uint16_t, static_cast<_Float16>(v));
+    }
+    __device__ static __forceinline__ float get(const f16_t *p) {
+        return static_cast<float>(__builtin_bit_cast(_Float16, p->bits));
+    }
+    __device__ static __forceinline__ void unpack(const uint4 &u, float *v) {
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f32x2_t f = __builtin_convertvector(__builtin_bit_cast(f16x2_t, w[i]), f32x2_t);
+            v[2 * i] = f[0];
+            v[2 * i + 1] = f[1];
+        }
+    }
+    __device__ static __forceinline__ uint4 pack(const float *v) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f32x2_t f = {v[2 * i], v[2 * i + 1]};
+            w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2_t));
+        }
         return make_uint4(w[0], w[1], w[2], w[3]);
     }
 };

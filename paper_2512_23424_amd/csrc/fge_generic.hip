@@ -131,13 +131,15 @@ __global__ __launch_bounds__(256) void generic_row_kernel(const GenArgs a) {
 
 hipError_t launch_generic_gemm(int in_dtype, int dst_dtype, hipStream_t s, const GenArgs &a) {
     const dim3 grid((unsigned)((a.N + 31) / 32), (unsigned)((a.M + 31) / 32), (unsigned)a.batch), block(256);
-    if (in_dtype == FGE_BF16) {
-        if (dst_dtype == FGE_BF16) hipLaunchKernelGGL((generic_gemm_kernel<bf16_t, bf16_t>), grid, block, 0, s, a);
-        else                       hipLaunchKernelGGL((generic_gemm_kernel<bf16_t, float>), grid, block, 0, s, a);
-    } else {
-        if (dst_dtype == FGE_BF16) hipLaunchKernelGGL((generic_gemm_kernel<float, bf16_t>), grid, block, 0, s, a);
-        else                       hipLaunchKernelGGL((generic_gemm_kernel<float, float>), grid, block, 0, s, a);
-    }
+#define FGE_GG(InT, NarrowT)                                                                           \
+    do {                                                                                               \
+        if (dst_dtype != FGE_F32) hipLaunchKernelGGL((generic_gemm_kernel<InT, NarrowT>), grid, block, 0, s, a); \
+        else                      hipLaunchKernelGGL((generic_gemm_kernel<InT, float>), grid, block, 0, s, a);   \
+    } while (0)
+    if (in_dtype == FGE_BF16)     FGE_GG(bf16_t, bf16_t);
+    else if (in_dtype == FGE_F16) FGE_GG(f16_t, f16_t);
+    else                          FGE_GG(float, bf16_t);
+#undef FGE_GG
     return hipGetLastError();
 }
 
@@ -146,20 +148,25 @@ hipError_t launch_generic_act(int dtype, hipStream_t s, const GenArgs &a) {
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;                           // grid-stride beyond that
     const dim3 grid((unsigned)blocks), block(256);
-    if (dtype == FGE_BF16) hipLaunchKernelGGL((generic_act_kernel<bf16_t>), grid, block, 0, s, a);
-    else                   hipLaunchKernelGGL((generic_act_kernel<float>), grid, block, 0, s, a);
+    if (dtype == FGE_BF16)     hipLaunchKernelGGL((generic_act_kernel<bf16_t>), grid, block, 0, s, a);
+    else if (dtype == FGE_F16) hipLaunchKernelGGL((generic_act_kernel<f16_t>), grid, block, 0, s, a);
+    else                       hipLaunchKernelGGL((generic_act_kernel<float>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
+// src is fp32 (the fused intermediate) or of the output type (the unfused A)
 hipError_t launch_generic_row(int src_dtype, int out_dtype, hipStream_t s, const GenArgs &a) {
     const int64_t rows = (int64_t)a.batch * a.M;
     const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
-    if (src_dtype == FGE_BF16) {
-        if (out_dtype != FGE_BF16) return hipErrorInvalidValue;          // never asked for
-        hipLaunchKernelGGL((generic_row_kernel<bf16_t, bf16_t>), grid, block, 0, s, a);
+    if (src_dtype == FGE_F32) {
+        if (out_dtype == FGE_BF16)     hipLaunchKernelGGL((generic_row_kernel<float, bf16_t>), grid, block, 0, s, a);
+        else if (out_dtype == FGE_F16) hipLaunchKernelGGL((generic_row_kernel<float, f16_t>), grid, block, 0, s, a);
+        else                           hipLaunchKernelGGL((generic_row_kernel<float, float>), grid, block, 0, s, a);
+    } else if (src_dtype == out_dtype) {
+        if (out_dtype == FGE_BF16) hipLaunchKernelGGL((generic_row_kernel<bf16_t, bf16_t>), grid, block, 0, s, a);
+        else                       hipLaunchKernelGGL((generic_row_kernel<f16_t, f16_t>), grid, block, 0, s, a);
     } else {
-        if (out_dtype == FGE_BF16) hipLaunchKernelGGL((generic_row_kernel<float, bf16_t>), grid, block, 0, s, a);
-        else                       hipLaunchKernelGGL((generic_row_kernel<float, float>), grid, block, 0, s, a);
+        return hipErrorInvalidValue;                                     // never asked for
     }
     return hipGetLastError();
 }

@@ -29,6 +29,7 @@ inline const TileInfo &tile_info(int id) {
 hipError_t launch_tile_f32(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_tile_f32s(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_tile_bf16(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
+hipError_t launch_tile_f16(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 // Defined in fge_panel_f32.hip: the persistent narrow-K kernel (grid = number of workgroups).
 hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 
@@ -59,15 +60,20 @@ inline int resident_workgroups(const void *kernel, int threads) {
 }
 
 // Which tiles exist for which operand type (tile selection on the host must agree):
-//   bf16: 64x64, 64x512, 128x128 (+ cooperative), 256x256 (+ cooperative)
+//   bf16, fp16: 64x64, 64x512, 128x128 (+ cooperative), 256x256 (+ cooperative)
 //   fp32: 64x64, 64x512, 64x128 (+ cooperative) - once with the fp32 matrix instruction and once
 //         with the split-bf16 product (SPLIT)
+// The 16-bit output type that goes with an operand type (the other output type is fp32).
+template <typename InT> struct NarrowOut { typedef bf16_t type; };
+template <> struct NarrowOut<f16_t> { typedef f16_t type; };
+
 template <typename InT, bool SPLIT>
 inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
+    typedef typename NarrowOut<InT>::type NarrowT;
 #define FGE_LAUNCH(BM, BN, WM, WN)                                                              \
     do {                                                                                        \
-        if (out_dtype == FGE_BF16)                                                              \
-            hipLaunchKernelGGL((tile_kernel<InT, bf16_t, BM, BN, WM, WN, false, false, SPLIT>), grid, \
+        if (out_dtype != FGE_F32)                                                               \
+            hipLaunchKernelGGL((tile_kernel<InT, NarrowT, BM, BN, WM, WN, false, false, SPLIT>), grid, \
                                dim3(64 * WM * WN), 0, s, a);                                    \
         else                                                                                    \
             hipLaunchKernelGGL((tile_kernel<InT, float, BM, BN, WM, WN, false, false, SPLIT>), grid, \
@@ -85,7 +91,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     } while (0)
 #define FGE_LAUNCH_COOP(BM, BN, WM, WN)                                                         \
     do {                                                                                        \
-        if (out_dtype == FGE_BF16) FGE_LAUNCH_COOP1(BM, BN, WM, WN, bf16_t);                    \
+        if (out_dtype != FGE_F32)  FGE_LAUNCH_COOP1(BM, BN, WM, WN, NarrowT);                   \
         else                       FGE_LAUNCH_COOP1(BM, BN, WM, WN, float);                     \
     } while (0)
     constexpr bool BF = sizeof(InT) == 2;
@@ -123,7 +129,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
 
 // Whether launch_tile_any has a cooperative kernel for this tile and operand type.
 inline bool tile_has_coop(int tile, int in_dtype) {
-    return in_dtype == FGE_BF16 ? (tile == TILE_128x128 || tile == TILE_256x256) : tile == TILE_64x128;
+    return in_dtype != FGE_F32 ? (tile == TILE_128x128 || tile == TILE_256x256) : tile == TILE_64x128;
 }
 
 }  // namespace fge

@@ -65,6 +65,12 @@ template <> struct Mma<bf16_t> {
                                                     __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
 };
+template <> struct Mma<f16_t> {
+    __device__ static __forceinline__ void run(const u32x4 &a, const u32x4 &b, floatx16 &c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                   __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
 template <> struct Mma<float> {
     // A 16-byte fragment holds 4 consecutive k of one row; lanes 0-31 and 32-63 hold different
     // chunks.  The k pairing is the same for both operands, so the sum over k is complete.

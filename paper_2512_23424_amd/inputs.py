@@ -16,7 +16,8 @@ Generator (counter based, order independent, reproducible on any host):
     normal   : mean + std * sqrt(-2 ln(1 - u(2i))) * cos(2 pi u(2i + 1))   (Box-Muller, cos branch)
 
 Values are produced in float64 and rounded once (round-to-nearest-even) to the storage type
-(fp32 or bf16).  bf16 tensors are returned as uint16 bit patterns.
+(fp32, bf16 or fp16).  bf16 tensors are returned as uint16 bit patterns, fp16 tensors as
+numpy float16 arrays.
 """
 from __future__ import annotations
 
@@ -29,7 +30,7 @@ import numpy as np
 # activation / row-op / dtype codes: the same integers as the C header's enums.
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF, ACT_SILU, ACT_CLAMP = range(6)
 NORM_NONE, NORM_SOFTMAX, NORM_LAYERNORM, NORM_RMSNORM, NORM_LOGSUMEXP = range(5)
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 TENSOR_ID = {"X": 0, "W": 1, "b": 2, "gamma": 3, "beta": 4}
 
@@ -89,7 +90,11 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
 
 
 def _store(v64: np.ndarray, dtype: int) -> np.ndarray:
-    return f64_to_bf16_bits(v64) if dtype == BF16 else v64.astype(np.float32)
+    """One rounding (to nearest even) from float64 to the storage type; fp16 tensors are numpy
+    float16 arrays (numpy converts double to half directly, without an fp32 step)."""
+    if dtype == BF16:
+        return f64_to_bf16_bits(v64)
+    return v64.astype(np.float16 if dtype == F16 else np.float32)
 
 
 _CHUNK = 1 << 22
@@ -100,7 +105,7 @@ def draw(seed: int, tensor: str, shape: Tuple[int, ...], dist: Tuple, dtype: int
     ("int" draws integers lo..hi inclusive, exactly representable in bf16 and fp32)."""
     key = stream_key(seed, TENSOR_ID[tensor])
     n = int(np.prod(shape))
-    out = np.empty(n, dtype=np.uint16 if dtype == BF16 else np.float32)
+    out = np.empty(n, dtype={BF16: np.uint16, F16: np.float16}.get(dtype, np.float32))
     for s in range(0, n, _CHUNK):
         c = min(_CHUNK, n - s)
         if dist[0] == "normal":
@@ -149,8 +154,8 @@ class Workload:
     @property
     def algorithmic_bytes(self) -> int:
         """Every operand and result moved exactly once."""
-        isz = 2 if self.in_dtype == BF16 else 4
-        osz = 2 if self.out_dtype == BF16 else 4
+        isz = 4 if self.in_dtype == F32 else 2
+        osz = 4 if self.out_dtype == F32 else 2
         vecs = sum(1 for t in ("b", "gamma", "beta") if self.dist.get(t) is not None)
         aux = self.rows * 4 if self.norm == NORM_LOGSUMEXP else 0
         return (self.rows * self.K * isz + self.N * self.K * isz + vecs * self.N * 4

@@ -10,8 +10,11 @@ from oracle import oracle as O
 from paper_2512_23424_amd import binding as B
 from paper_2512_23424_amd import inputs as I
 
-TOL = {I.F32: 1e-4, I.BF16: 2e-2}        # max rel err: fp32 / bf16-in fp32-accumulate
-TAU = {I.F32: 1e-3, I.BF16: 2e-2}        # the paper's pass rule (fp32 value from its setup section)
+# max rel err: fp32 / bf16-in fp32-accumulate / fp16-in fp32-accumulate (one fp16 rounding of the
+# output is 2^-11 = 4.9e-4; the gate is the paper's float16 threshold)
+TOL = {I.F32: 1e-4, I.BF16: 2e-2, I.F16: 4e-3}
+# the paper's pass rule (fp32 and float16 values from its setup section, Section 5.1)
+TAU = {I.F32: 1e-3, I.BF16: 2e-2, I.F16: 4e-3}
 
 
 def to_device(a: Optional[np.ndarray]) -> Optional[torch.Tensor]:
@@ -27,7 +30,7 @@ def to_host_f64(t: torch.Tensor) -> np.ndarray:
 
 
 def tdtype(code: int):
-    return torch.bfloat16 if code == I.BF16 else torch.float32
+    return {I.BF16: torch.bfloat16, I.F16: torch.float16}.get(code, torch.float32)
 
 
 def oracle_chain(w: I.Workload, t: Dict[str, Optional[np.ndarray]]):

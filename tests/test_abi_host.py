@@ -58,7 +58,9 @@ def test_argument_errors_are_reported_before_any_launch():
     assert _call(_params(), out=None) == 1
     assert _call(_params(), act=6) == 2 and _call(_params(), act=-1) == 2
     assert _call(_params(), norm=5) == 2
-    assert _call(_params(in_dtype=2)) == 2
+    assert _call(_params(in_dtype=3)) == 2 and _call(_params(out_dtype=-1)) == 2
+    assert _call(_params(in_dtype=2, out_dtype=1)) == 4       # fp16 operands with a bf16 result
+    assert _call(_params(in_dtype=1, out_dtype=2)) == 4
     assert _call(_params(M=0)) == 3 and _call(_params(K=-8)) == 3 and _call(_params(batch=0)) == 3
     assert _call(_params(ldo=128)) == 3                       # stride smaller than the row
     assert _call(_params(ldx=32)) == 3

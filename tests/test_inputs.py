@@ -72,3 +72,19 @@ def test_workloads_match_their_description():
     assert g["X"].dtype == np.uint16 and g["gamma"].dtype == np.float32 and g["b"] is None
     g2 = I.generate(I.scaled(w["cfg3"], M=16, K=64, N=32), rows=np.array([3, 7]))
     assert np.array_equal(g2["X"], g["X"][[3, 7]])
+
+
+def test_fp16_storage_rounds_once_to_nearest_even():
+    """fp16 tensors: one rounding from float64, ties to even (hand-built cases), and the drawn
+    values are exactly what the float16 array holds."""
+    v = np.array([1.0 + 2.0 ** -11, 1.0 + 3.0 * 2.0 ** -11, 1.0 + 2.0 ** -11 + 2.0 ** -40, -(1.0 + 2.0 ** -11),
+                  65504.0, 2.0 ** -24, 2.0 ** -25], dtype=np.float64)
+    got = I._store(v, I.F16)
+    assert got.dtype == np.float16
+    want = np.array([1.0, 1.0 + 2.0 ** -9, 1.0 + 2.0 ** -10, -1.0, 65504.0, 2.0 ** -24, 0.0])
+    assert np.array_equal(got.astype(np.float64), want)
+    w = I.Workload(name="h", M=5, K=8, N=8, in_dtype=I.F16, out_dtype=I.F16,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("uniform", -1.0, 1.0)})
+    t = I.generate(w)
+    assert t["X"].dtype == np.float16 and t["W"].dtype == np.float16
+    assert np.array_equal(I.as_f64(t["X"]), t["X"].astype(np.float64))

@@ -27,7 +27,7 @@ def _parity(w, path, rows=None, label=""):
 
 
 # ---- layout / indexing: exact integers must match bit for bit whatever the summation order
-@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+@pytest.mark.parametrize("dt", [I.F32, I.BF16, I.F16])
 @pytest.mark.parametrize("shape", [(64, 64, 64), (96, 128, 160), (200, 72, 328), (300, 1024, 520)])
 def test_exact_integer_gemm(dt, shape):
     M, K, N = shape
@@ -62,7 +62,7 @@ ACTS = [I.ACT_NONE, I.ACT_RELU, I.ACT_GELU_TANH, I.ACT_GELU_ERF, I.ACT_SILU, I.A
 NORMS = [I.NORM_NONE, I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP]
 
 
-@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+@pytest.mark.parametrize("dt", [I.F32, I.BF16, I.F16])
 @pytest.mark.parametrize("norm", NORMS)
 @pytest.mark.parametrize("N", [40, 328, 1032])          # whole-row 64, whole-row 512, split
 def test_all_chains(dt, norm, N):
@@ -106,6 +106,7 @@ def test_narrow_k_persistent_kernel(norm, shape):
 
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
 @pytest.mark.parametrize("case", [(I.BF16, 4100, 136, 4000, "256x256_w2x4"), (I.BF16, 2050, 200, 2040, "128x128_w2x2"),
+                                  (I.F16, 4100, 136, 4000, "256x256_w2x4"), (I.F16, 2050, 200, 2040, "128x128_w2x2"),
                                   (I.F32, 1030, 100, 2040, "64x128_w2x2_splitbf16")])
 def test_split_rows_one_kernel_and_two_pass(norm, case):
     """Rows split over column tiles, large enough for the one-kernel form (the tiles of a row
@@ -196,7 +197,7 @@ def test_edge_shapes():
         _parity(w, "unfused", label=f"edge-unfused {M}x{K}x{N}")
 
 
-@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+@pytest.mark.parametrize("dt", [I.F32, I.BF16, I.F16])
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
 def test_widest_row_and_smallest_problem(dt, norm):
     """The widest row a row op accepts (N = 8192) and the smallest problem of each storage type
@@ -212,7 +213,7 @@ def test_widest_row_and_smallest_problem(dt, norm):
             _parity(w, path, label=f"{path} {M}x{K}x{N}")
 
 
-@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+@pytest.mark.parametrize("dt", [I.F32, I.BF16, I.F16])
 @pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (33, 17, 65), (100, 101, 250), (70, 63, 1001),
                                    (40, 72, 9000)])
 def test_any_shape_takes_the_element_granular_kernels(dt, shape):
