@@ -145,3 +145,35 @@ int fge_oracle_threads(void) { return omp_get_max_threads(); }
 #else
 int fge_oracle_threads(void) { return 1; }
 #endif
+
+/* Gated variant (the "SiLU-and-Mul" / "GELU-and-Mul" fused operators the paper's benchmark
+ * section lists among the fused operations, Section 4): two products sharing X,
+ *     G = post_scale * (alpha * X.W1^T + b1),   U = post_scale * (alpha * X.W2^T + b2),
+ *     A = act(G) * U   elementwise,             out = rowop_N(A).
+ * Gate step: A[t] = act(G[t]) * U[t], written into G. */
+void fge_oracle_gate(double *G, const double *U, long count, int act, double lo, double hi)
+{
+#pragma omp parallel for schedule(static)
+    for (long t = 0; t < count; ++t)
+        G[t] = fge_oracle_act1(G[t], act, lo, hi) * U[t];
+}
+
+/* The gated chain, step after step.  `work` is M x N scratch for U.  Returns 0, or -1 on an
+ * unknown enum. */
+int fge_oracle_gated_chain(const double *X, const double *W1, const double *W2,
+                           const double *b1, const double *b2,
+                           const double *gamma, const double *beta,
+                           long M, long N, long K, double alpha, double post_scale,
+                           int act, double clamp_lo, double clamp_hi, int norm, double eps,
+                           double *out, double *aux, double *work)
+{
+    if (act < ACT_NONE || act > ACT_CLAMP || norm < NORM_NONE || norm > NORM_LOGSUMEXP)
+        return -1;
+    fge_oracle_gemm(X, W1, M, N, K, out);
+    fge_oracle_scale_bias(out, b1, M, N, alpha, post_scale);
+    fge_oracle_gemm(X, W2, M, N, K, work);
+    fge_oracle_scale_bias(work, b2, M, N, alpha, post_scale);
+    fge_oracle_gate(out, work, M * N, act, clamp_lo, clamp_hi);
+    fge_oracle_rowop(out, M, N, norm, eps, gamma, beta, aux);
+    return 0;
+}

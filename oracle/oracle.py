@@ -27,6 +27,11 @@ def lib():
         L.fge_oracle_rowop.argtypes = [_D, ctypes.c_long, ctypes.c_long, ctypes.c_int,
                                        ctypes.c_double, _D, _D, _D]
         L.fge_oracle_rowop.restype = None
+        L.fge_oracle_gate.argtypes = [_D, _D, ctypes.c_long, ctypes.c_int, ctypes.c_double, ctypes.c_double]
+        L.fge_oracle_gate.restype = None
+        L.fge_oracle_gated_chain.argtypes = [_D] * 7 + [ctypes.c_long] * 3 + [ctypes.c_double] * 2 + [
+            ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_double, _D, _D, _D]
+        L.fge_oracle_gated_chain.restype = ctypes.c_int
         L.fge_oracle_chain.argtypes = [_D, _D, _D, _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_long,
                                        ctypes.c_double, ctypes.c_double, ctypes.c_int,
                                        ctypes.c_double, ctypes.c_double, ctypes.c_int,
@@ -94,6 +99,33 @@ def chain(X, W, b=None, gamma=None, beta=None, *, alpha=1.0, post_scale=1.0, act
     rc = lib().fge_oracle_chain(_p(X), _p(W), _p(b), _p(gamma), _p(beta), M, N, K,
                                 alpha, post_scale, act, clamp_lo, clamp_hi, norm, eps,
                                 _p(out), _p(aux))
+    if rc != 0:
+        raise ValueError("unknown activation or row-op code")
+    return out, aux
+
+
+def gate(G: np.ndarray, U: np.ndarray, kind: int, lo: float = 0.0, hi: float = 0.0) -> np.ndarray:
+    """act(G) * U elementwise."""
+    A = np.array(G, dtype=np.float64, order="C", copy=True)
+    U = _c(U)
+    assert A.shape == U.shape
+    lib().fge_oracle_gate(_p(A), _p(U), A.size, kind, lo, hi)
+    return A
+
+
+def gated_chain(X, W1, W2, b1=None, b2=None, gamma=None, beta=None, *, alpha=1.0, post_scale=1.0,
+                act=0, clamp_lo=0.0, clamp_hi=0.0, norm=0, eps=0.0) -> Tuple[np.ndarray, np.ndarray]:
+    """rowop(act(post*(alpha*X.W1^T + b1)) * (post*(alpha*X.W2^T + b2))): out and aux as in chain()."""
+    X, W1, W2, b1, b2, gamma, beta = (_c(v) for v in (X, W1, W2, b1, b2, gamma, beta))
+    M, K = X.shape
+    N = W1.shape[0]
+    assert W1.shape == (N, K) and W2.shape == (N, K)
+    out = np.empty((M, N), dtype=np.float64)
+    work = np.empty((M, N), dtype=np.float64)
+    aux = np.full(M, np.nan, dtype=np.float64)
+    rc = lib().fge_oracle_gated_chain(_p(X), _p(W1), _p(W2), _p(b1), _p(b2), _p(gamma), _p(beta),
+                                      M, N, K, alpha, post_scale, act, clamp_lo, clamp_hi, norm, eps,
+                                      _p(out), _p(aux), _p(work))
     if rc != 0:
         raise ValueError("unknown activation or row-op code")
     return out, aux

@@ -300,6 +300,49 @@ def test_chain_matches_library_composition(name):
         np.testing.assert_allclose(aux, ra, rtol=1e-13)
 
 
+def test_gated_chain_by_hand_and_special_cases():
+    """The gated variant (act(G) * U, the SiLU-and-Mul / GELU-and-Mul operators of the paper's
+    Section 4): a hand-computed case, reductions to the plain chain, and the scaling of each
+    product - a swapped operand, a gate applied to the wrong factor or a bias added to the wrong
+    product fails one of these."""
+    X = np.array([[1.0, 2.0], [0.0, -1.0]])
+    W1 = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]])          # G = [[1,2,3],[0,-1,-1]]
+    W2 = np.array([[2.0, 0.0], [0.0, 0.5], [1.0, -1.0]])         # U = [[2,1,-1],[0,-0.5,1]]
+    b1 = np.array([0.0, 1.0, -4.0]); b2 = np.array([1.0, 0.0, 0.0])
+    # G + b1 = [[1,3,-1],[0,0,-5]], U + b2 = [[3,1,-1],[1,-0.5,1]]; relu(G+b1) * (U+b2):
+    out, _ = O.gated_chain(X, W1, W2, b1, b2, act=I.ACT_RELU)
+    assert np.array_equal(out, np.array([[3.0, 3.0, 0.0], [0.0, -0.0, 0.0]]))
+    # alpha scales both products (not the biases), post_scale both biased sums
+    out, _ = O.gated_chain(X, W1, W2, b1, b2, alpha=2.0, post_scale=0.5, act=I.ACT_NONE)
+    G = 0.5 * (2.0 * X @ W1.T + b1); U = 0.5 * (2.0 * X @ W2.T + b2)
+    assert np.array_equal(out, G * U)
+    rng = np.random.default_rng(5)
+    X = rng.normal(size=(7, 11)); W1 = rng.normal(size=(13, 11)); W2 = rng.normal(size=(13, 11))
+    b1 = rng.normal(size=13); g = rng.normal(size=13) + 1.0; be = rng.normal(size=13)
+    # U == 1 (W2 = 0, b2 = 1): the gated chain is the plain chain, for every activation and row op
+    for act in range(6):
+        for norm in range(5):
+            a, ax = O.gated_chain(X, W1, np.zeros_like(W2), b1, np.ones(13), g, be, alpha=0.7, act=act,
+                                  clamp_lo=-1.0, clamp_hi=0.5, norm=norm, eps=1e-5)
+            r, rx = O.chain(X, W1, b1, g, be, alpha=0.7, act=act, clamp_lo=-1.0, clamp_hi=0.5, norm=norm, eps=1e-5)
+            assert np.array_equal(a, r) and np.array_equal(ax, rx, equal_nan=True)
+    # SiLU-and-Mul and GELU-and-Mul against scipy / numpy on the same products
+    G = X @ W1.T + b1; U = X @ W2.T
+    np.testing.assert_allclose(O.gated_chain(X, W1, W2, b1, None, act=I.ACT_SILU)[0], G * sp.expit(G) * U, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(O.gated_chain(X, W1, W2, b1, None, act=I.ACT_GELU_ERF)[0],
+                               G * sp.ndtr(G) * U, rtol=1e-12, atol=1e-15)
+    # the gate is not symmetric: swapping W1 and W2 changes the result (unless act is none)
+    assert not np.allclose(O.gated_chain(X, W1, W2, act=I.ACT_SILU)[0], O.gated_chain(X, W2, W1, act=I.ACT_SILU)[0])
+    assert np.array_equal(O.gated_chain(X, W1, W2, act=I.ACT_NONE)[0], O.gated_chain(X, W2, W1, act=I.ACT_NONE)[0])
+    # row op after the gate: torch float64 composition
+    out, _ = O.gated_chain(X, W1, W2, b1, None, g, None, act=I.ACT_SILU, norm=I.NORM_RMSNORM, eps=1e-6)
+    a = torch.from_numpy(G * sp.expit(G) * U)
+    np.testing.assert_allclose(out, torch.nn.functional.rms_norm(a, (13,), torch.from_numpy(g), 1e-6).numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(O.gate(G, U, I.ACT_RELU), np.maximum(G, 0.0) * U)
+    with pytest.raises(ValueError):
+        O.gated_chain(X, W1, W2, act=9)
+
+
 def test_chain_rejects_unknown_codes():
     X = np.ones((2, 2)); W = np.ones((2, 2))
     with pytest.raises(ValueError):
