@@ -69,6 +69,57 @@ def measured_traffic(workload: str):
         return None
 
 
+def gated_ffn(torch, B, I, timed, log):
+    """SiLU-and-Mul followed by RMSNorm at cfg3's shape (bf16, two 8192x4096x4096 products):
+    the gated tile kernel against the unfused sequence of the same library, with a parity check
+    of sampled rows against the oracle."""
+    from oracle import compare as C
+    from oracle import oracle as O
+    w = I.scaled(I.WORKLOADS["cfg3"], dist=dict(I.WORKLOADS["cfg3"].dist, W=("normal", 0.0, 1.0 / 64)))
+    log("[bench] generating the gated workload ...")
+    t = I.generate_gated(w)
+
+    def up(a):
+        return None if a is None else (torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+                                       if a.dtype == np.uint16 else torch.from_numpy(a).cuda())
+    d = {k: up(v) for k, v in t.items()}
+    sets = [(d["X"], torch.empty(w.M, w.N, dtype=torch.bfloat16, device="cuda")),
+            (d["X"].clone(), torch.empty(w.M, w.N, dtype=torch.bfloat16, device="cuda"))]
+    ps = []
+    for X, out in sets:
+        p = B.make_params(X, d["W"], out, eps=w.eps, gamma=d["gamma"])
+        n = max(B.fge_gated_workspace_bytes(True, w.act, w.norm, p), B.fge_gated_workspace_bytes(False, w.act, w.norm, p))
+        ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), n
+        ps.append((p, ws))
+
+    def fused(i):
+        B.fused_gated_gemm_epilogue(sets[i][0], d["W"], d["W2"], None, None, w.act, w.norm, ps[i][0], sets[i][1])
+
+    def unfused(i):
+        B.unfused_gated_gemm_epilogue(sets[i][0], d["W"], d["W2"], None, None, w.act, w.norm, ps[i][0], sets[i][1])
+    rows = np.unique(np.concatenate([[0, w.M - 1], np.random.default_rng(4).integers(0, w.M, 6)]))
+    sets[0][1].fill_(float("nan"))
+    fused(0)
+    torch.cuda.synchronize()
+    got = sets[0][1][torch.from_numpy(rows).cuda()].to(torch.float64).cpu().numpy()
+    f = {k: I.as_f64(v) for k, v in t.items()}
+    ref, _ = O.gated_chain(f["X"][rows], f["W"], f["W2"], None, None, f["gamma"], None, act=w.act, norm=w.norm, eps=w.eps)
+    err = C.max_rel_err(got, ref)
+    if not (err <= 2e-2):
+        raise SystemExit(f"bench.py: gated result off the oracle: {err:.3e}")
+    tf_ = timed(fused, 30, 10)
+    tu_ = timed(unfused, 15, 3)
+    flops = 4.0 * w.M * w.N * w.K
+    r = {"workload": "SiLU-and-Mul + RMSNorm, bf16, M=8192 K=4096 N=4096 (two products)",
+         "tile": B.fge_gated_tile_name(w.act, w.norm, ps[0][0]), "ms_fused": round(tf_, 5),
+         "ms_unfused": round(tu_, 5), "tflops": round(flops / (tf_ * 1e-3) / 1e12, 2),
+         "frac_mfma": round(flops / (tf_ * 1e-3) / 1e12 / PEAK_TFLOPS["bf16"], 4),
+         "speedup_vs_unfused": round(tu_ / tf_, 3), "parity_err": float(f"{err:.3e}")}
+    log(f"[bench] gated: {json.dumps(r)}")
+    return r
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -316,6 +367,10 @@ def main() -> int:
             del c
             torch.cuda.empty_cache()
     sp = [v["speedup_vs_unfused"] for v in per.values() if "speedup_vs_unfused" in v]
+    # ------------------------------------------------------------------ the gated form
+    gated = None
+    if not args.no_others:
+        gated = gated_ffn(torch, B, I, timed, log)
     geo = math.exp(sum(math.log(s) for s in sp) / len(sp)) if sp else None
 
     line = {
@@ -327,7 +382,7 @@ def main() -> int:
                                f"{'bf16 in/out' if dt == 'bf16' else 'fp32'}, fp32 accumulate, "
                                f"act={w.act} rowop={w.norm} (codes of include/fge.h)",
                    "tile": head["tile"], "speedup_vs_unfused": head.get("speedup_vs_unfused")},
-        "roofline": roof, "cpu_baseline": cpu, "per_config": per,
+        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated,
         "speedup_geomean": None if geo is None else round(geo, 3),
         "paper_context": "paper reports 1.46x geomean over PyTorch eager (Triton, Ascend 910B, "
                          "KernelBench L1); no number for this chain",

@@ -134,6 +134,27 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
  * arguments; 0 is a valid answer.  Returns (size_t)-1 when the arguments are invalid. */
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p);
 
+/* ---- the gated form (the "SiLU-and-Mul" / "GELU-and-Mul" fused operators of the paper's
+ * benchmark section, Section 4, followed by the optional row operation):
+ *
+ *     out = rowop_N( act(post_scale*(alpha*X.W1^T + b1)) * (post_scale*(alpha*X.W2^T + b2)) )
+ *
+ * W1 and W2 are both N x K with row stride ldw; b1, b2 fp32 of length N or NULL.  Everything
+ * else is as for fused_gemm_epilogue.  The fused call runs one tile kernel that forms both
+ * products from one staged X panel and applies the gate to the accumulators, for bf16 / fp16
+ * operands in shapes the fast kernels take; every other case (fp32 operands, odd extents) runs
+ * the unfused sequence: two GEMMs into the workspace, the gate as an elementwise kernel, the row
+ * operation.  fge_gated_workspace_bytes gives the workspace either call needs;
+ * fge_gated_tile_name names what the fused call runs ("unfused_sequence" for the fallback). */
+int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, const float *b1,
+                              const float *b2, int act, int norm, const fge_params *p, void *out,
+                              void *stream);
+int unfused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, const float *b1,
+                                const float *b2, int act, int norm, const fge_params *p, void *out,
+                                void *stream);
+size_t fge_gated_workspace_bytes(int fused, int act, int norm, const fge_params *p);
+const char *fge_gated_tile_name(int act, int norm, const fge_params *p);
+
 /* ---- the individual stages, callable on their own (the two paths above are built from them) */
 
 /* Fused stage 1: the tile kernel.  When the chosen tile spans N it produces the final out. */

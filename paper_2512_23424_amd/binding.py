@@ -79,6 +79,13 @@ def lib() -> ctypes.CDLL:
         L.fge_last_hip_error.restype = ci
         L.fge_tile_name.argtypes = [ci, ci, ci, pp]
         L.fge_tile_name.restype = ctypes.c_char_p
+        for name in ("fused_gated_gemm_epilogue", "unfused_gated_gemm_epilogue"):
+            getattr(L, name).argtypes = [vp, vp, vp, vp, vp, ci, ci, pp, vp, vp]
+            getattr(L, name).restype = ci
+        L.fge_gated_workspace_bytes.argtypes = [ci, ci, ci, pp]
+        L.fge_gated_workspace_bytes.restype = ctypes.c_size_t
+        L.fge_gated_tile_name.argtypes = [ci, ci, pp]
+        L.fge_gated_tile_name.restype = ctypes.c_char_p
         _lib = L
     return _lib
 
@@ -202,3 +209,27 @@ def fge_activation(Y, act, p: FgeParams, A, stream=None) -> None:
 def fge_row_op(A, norm, p: FgeParams, out, stream=None) -> None:
     _check(lib().fge_row_op(_ptr(A), _code(NORM, norm), ctypes.byref(p), _ptr(out), _stream(stream)),
            "fge_row_op")
+
+
+def fused_gated_gemm_epilogue(X, W1, W2, b1, b2, act, norm, p: FgeParams, out, stream=None) -> None:
+    _check(lib().fused_gated_gemm_epilogue(_ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2), _code(ACT, act),
+                                           _code(NORM, norm), ctypes.byref(p), _ptr(out), _stream(stream)),
+           "fused_gated_gemm_epilogue")
+
+
+def unfused_gated_gemm_epilogue(X, W1, W2, b1, b2, act, norm, p: FgeParams, out, stream=None) -> None:
+    _check(lib().unfused_gated_gemm_epilogue(_ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2), _code(ACT, act),
+                                             _code(NORM, norm), ctypes.byref(p), _ptr(out), _stream(stream)),
+           "unfused_gated_gemm_epilogue")
+
+
+def fge_gated_workspace_bytes(fused: bool, act, norm, p: FgeParams) -> int:
+    n = lib().fge_gated_workspace_bytes(int(bool(fused)), _code(ACT, act), _code(NORM, norm), ctypes.byref(p))
+    if n == ctypes.c_size_t(-1).value:
+        raise FgeError(3, "fge_gated_workspace_bytes (invalid arguments)")
+    return n
+
+
+def fge_gated_tile_name(act, norm, p: FgeParams) -> str:
+    s = lib().fge_gated_tile_name(_code(ACT, act), _code(NORM, norm), ctypes.byref(p))
+    return "" if s is None else s.decode()

@@ -119,7 +119,7 @@ int pick_tile(const Problem &pr, int in_dtype, int norm, bool ieee_fp32) {
 
 // two_pass: finish split rows with the second kernel even where the cooperative form exists
 // (asked for by flag, or the stream is being captured into a graph).
-Plan make_plan(const fge_params *p, int norm, bool two_pass = false) {
+Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_tile = -1) {
     Plan pl{};
     Problem &pr = pl.pr;
     pr = Problem{p->M, p->N, p->K, p->batch, p->ldx, p->ldw, p->ldo,
@@ -129,7 +129,7 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false) {
         pr.batch = 1;
         pr.bsx = pr.bso = 0;
     }
-    pl.tile = pick_tile(pr, p->in_dtype, norm, (p->flags & FGE_FLAG_IEEE_FP32) != 0);
+    pl.tile = force_tile >= 0 ? force_tile : pick_tile(pr, p->in_dtype, norm, (p->flags & FGE_FLAG_IEEE_FP32) != 0);
     const TileInfo &ti = tile_info(pl.tile);
     pl.tiles_m = (pr.M + ti.bm - 1) / ti.bm;
     pl.tiles_n = (pr.N + ti.bn - 1) / ti.bn;
@@ -166,6 +166,15 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false) {
 size_t fused_workspace(const fge_params *p, int norm) {
     const Plan p1 = make_plan(p, norm, false), p2 = make_plan(p, norm, true);
     if (p1.generic) return p1.ws_generic;
+    const size_t a = p1.ws_stats + p1.ws_marks, b = p2.ws_stats + p2.ws_marks;
+    return a > b ? a : b;
+}
+
+// The gated tile kernel takes 16-bit operands in shapes the vectorised kernels take.
+bool gated_fast(const fge_params *p, int norm) { return p->in_dtype != FGE_F32 && vectorisable(p, norm, true); }
+
+size_t gated_workspace(const fge_params *p, int norm) {
+    const Plan p1 = make_plan(p, norm, false, TILE_GATED), p2 = make_plan(p, norm, true, TILE_GATED);
     const size_t a = p1.ws_stats + p1.ws_marks, b = p2.ws_stats + p2.ws_marks;
     return a > b ? a : b;
 }
@@ -292,6 +301,8 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
     return launch_tiles(tile_args(X, W, b, act, norm, p, pl, out), p, pl, s);
 }
 
+int launch_finish(const Plan &pl, int act, int norm, const fge_params *p, void *out, hipStream_t s);
+
 int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream_t s) {
     int rc = check_common(p, act, norm, true);
     if (rc) return rc;
@@ -302,6 +313,10 @@ int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream
     if (!pl.needs_finish) return FGE_OK;
     if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
     if (!p->workspace || p->workspace_bytes < fused_workspace(p, norm)) return FGE_ERR_WORKSPACE;
+    return launch_finish(pl, act, norm, p, out, s);
+}
+
+int launch_finish(const Plan &pl, int act, int norm, const fge_params *p, void *out, hipStream_t s) {
     const RowArgs r = row_args(out, out, act, norm, p, pl);
     const int64_t rows = (int64_t)r.batch * r.M;
     const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
@@ -325,18 +340,20 @@ int do_gemm_bias(const void *X, const void *W, const float *b, const fge_params 
     return launch_tiles(tile_args(X, W, b, FGE_ACT_NONE, FGE_NORM_NONE, p, pl, Y), p, pl, s);
 }
 
-int do_act(const void *Y, int act, const fge_params *p, void *A, hipStream_t s) {
+// A = act(Y), or act(Y) * U when U is given (the gate of the gated sequence)
+int do_act(const void *Y, int act, const fge_params *p, void *A, hipStream_t s, const void *U = nullptr) {
     int rc = check_common(p, act, FGE_NORM_NONE, false);
     if (rc) return rc;
     if (!Y || !A) return FGE_ERR_NULL;
-    if (!aligned16(Y) || !aligned16(A)) return FGE_ERR_ALIGN;
+    if (!aligned16(Y) || !aligned16(A) || !aligned16(U)) return FGE_ERR_ALIGN;
     if (!vectorisable(p, FGE_NORM_NONE, false)) {
         GenArgs g = gen_args(p);
-        g.X = Y; g.dst = A; g.act = act;
+        g.X = Y; g.W = U; g.dst = A; g.act = act;
         return hip_status(launch_generic_act(p->out_dtype, s, g));
     }
     const Plan pl = make_plan(p, FGE_NORM_NONE);
-    const RowArgs r = row_args(Y, A, act, FGE_NORM_NONE, p, pl);
+    RowArgs r = row_args(Y, A, act, FGE_NORM_NONE, p, pl);
+    r.in2 = U;
     const int cw = p->out_dtype == FGE_F32 ? 4 : 8;
     const int64_t chunks = (int64_t)r.batch * r.M * (r.N / cw);
     int64_t blocks = (chunks + 255) / 256;
@@ -424,6 +441,64 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
     if ((rc = do_gemm_bias(X, W, b, p, Y, s))) return rc;
     if ((rc = do_act(Y, act, p, A, s))) return rc;
     return do_rownorm(A, norm, p, out, s);
+}
+
+// ---- gated form: out = rowop(act(post*(alpha*X.W1^T + b1)) * (post*(alpha*X.W2^T + b2)))
+
+int unfused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, const float *b1, const float *b2,
+                                int act, int norm, const fge_params *p, void *out, void *stream) {
+    int rc = check_common(p, act, norm, true);
+    if (rc) return rc;
+    if (!X || !W1 || !W2 || !out) return FGE_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(out) || !aligned16(b1) || !aligned16(b2))
+        return FGE_ERR_ALIGN;
+    if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
+    const Plan pl = make_plan(p, norm);
+    if (!p->workspace || p->workspace_bytes < 2 * pl.ws_buf) return FGE_ERR_WORKSPACE;
+    void *G = p->workspace;
+    void *U = static_cast<char *>(p->workspace) + pl.ws_buf;
+    void *A = pl.n_bufs == 2 ? G : out;             // the gate works in place where a row op follows
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = do_gemm_bias(X, W1, b1, p, G, s))) return rc;
+    if ((rc = do_gemm_bias(X, W2, b2, p, U, s))) return rc;
+    if ((rc = do_act(G, act, p, A, s, U))) return rc;
+    return do_rownorm(A, norm, p, out, s);
+}
+
+int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, const float *b1, const float *b2,
+                              int act, int norm, const fge_params *p, void *out, void *stream) {
+    int rc = check_common(p, act, norm, true);
+    if (rc) return rc;
+    if (!gated_fast(p, norm))                       // everything the gated tile kernel does not take
+        return unfused_gated_gemm_epilogue(X, W1, W2, b1, b2, act, norm, p, out, stream);
+    if (!X || !W1 || !W2 || !out) return FGE_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(out) || !aligned16(b1) || !aligned16(b2))
+        return FGE_ERR_ALIGN;
+    if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    const Plan pl = make_plan(p, norm, capturing(s), TILE_GATED);
+    if (pl.split) {
+        if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
+        if (!p->workspace || p->workspace_bytes < gated_workspace(p, norm)) return FGE_ERR_WORKSPACE;
+    }
+    TileArgs a = tile_args(X, W1, b1, act, norm, p, pl, out);
+    a.W2 = W2; a.b2 = b2;
+    const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
+                    a.coop ? 1u : (unsigned)pl.pr.batch);
+    rc = hip_status(p->in_dtype == FGE_BF16 ? launch_gated_bf16(p->out_dtype, grid, s, a)
+                                            : launch_gated_f16(p->out_dtype, grid, s, a));
+    if (rc || !pl.needs_finish) return rc;
+    return launch_finish(pl, act, norm, p, out, s);
+}
+
+size_t fge_gated_workspace_bytes(int fused, int act, int norm, const fge_params *p) {
+    if (check_common(p, act, norm, true)) return (size_t)-1;
+    return fused && gated_fast(p, norm) ? gated_workspace(p, norm) : 2 * make_plan(p, norm).ws_buf;
+}
+
+const char *fge_gated_tile_name(int act, int norm, const fge_params *p) {
+    if (check_common(p, act, norm, true)) return nullptr;
+    return gated_fast(p, norm) ? tile_info(TILE_GATED).name : "unfused_sequence";
 }
 
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p) {

@@ -25,7 +25,9 @@ namespace fge {
 
 struct TileArgs {
     const void *X, *W;
+    const void *W2;             // gated form: second weight matrix (else unused)
     const float *b, *gamma, *beta;
+    const float *b2;            // gated form: bias of the second product (may be null)
     void *out;
     float *aux;
     float2 *ws;                 // split rows: [batch*M][tiles_n * waves across] strip pairs for the

@@ -4,7 +4,7 @@
 // on the vector ALU, scalar loads and stores, rows re-read from memory per pass).
 //
 //   generic_gemm_kernel : dst = act(post*(alpha*X.W^T + b))   32x32 tile, LDS staged, fp32 FMA
-//   generic_act_kernel  : dst = act(src)                      elementwise
+//   generic_act_kernel  : dst = act(src) [* second operand]   elementwise
 //   generic_row_kernel  : out = rowop(src)                    one wave per row, passes over src
 #include "fge_launch.h"
 
@@ -66,8 +66,9 @@ __global__ __launch_bounds__(256) void generic_act_kernel(const GenArgs a) {
             const int64_t rowg = idx / a.N;
             const int c = (int)(idx - rowg * a.N);
             const int64_t off = (rowg / a.M) * a.bsd + (rowg % a.M) * a.ldd + c;
-            const float v = Store<T>::get(reinterpret_cast<const T *>(a.X) + off);
-            Store<T>::put(reinterpret_cast<T *>(a.dst) + off, activate<ACT>(v, a.lo, a.hi));
+            float v = activate<ACT>(Store<T>::get(reinterpret_cast<const T *>(a.X) + off), a.lo, a.hi);
+            if (a.W != nullptr) v *= Store<T>::get(reinterpret_cast<const T *>(a.W) + off);   // gate
+            Store<T>::put(reinterpret_cast<T *>(a.dst) + off, v);
         }
     });
 }

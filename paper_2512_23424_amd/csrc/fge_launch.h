@@ -4,7 +4,8 @@
 
 namespace fge {
 
-enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_64x128 = 5, TILE_COUNT = 6 };
+enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_64x128 = 5,
+              TILE_GATED = 6, TILE_COUNT = 7 };
 
 // coop_per_cu: workgroups of this tile's cooperative kernel that are resident on one CU at the
 // same time (from the compiler's register / LDS report; a lower bound is safe), 0 if the tile
@@ -20,6 +21,8 @@ inline const TileInfo &tile_info(int id) {
         // persistent narrow-K kernel, fp32 operands, always the split product
         {64, 512, 512, 8, 0, "panel64x512_w1x8_splitbf16", "panel64x512_w1x8_splitbf16"},
         {64, 128, 256, 2, 2, "64x128_w2x2", "64x128_w2x2_splitbf16"},
+        // gated form, 16-bit operands: 256 rows x 128 output columns (two 256x128 products)
+        {256, 128, 512, 4, 1, "gated256x128_w2x4", nullptr},
     };
     return t[id];
 }
@@ -34,7 +37,8 @@ hipError_t launch_tile_f16(int tile, int out_dtype, dim3 grid, hipStream_t s, co
 hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 
 // Element-granular kernels (fge_generic.hip) for shapes the vectorised kernels do not take.
-// gemm: dst = act(post*(alpha*X.W^T + b)); act: dst = act(X) with X laid out like dst; row:
+// gemm: dst = act(post*(alpha*X.W^T + b)); act: dst = act(X) [* W if W is set] with X (and W) laid
+// out like dst; row:
 // dst = rowop(X) with X rows x N at strides (ldx, bsx).  M rows per problem, `batch` problems.
 struct GenArgs {
     const void *X, *W;
@@ -127,8 +131,30 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     return hipGetLastError();
 }
 
+// The gated tile kernel (16-bit operands only): ordinary or cooperative launch.
+template <typename InT>
+inline hipError_t launch_gated_any(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
+    typedef typename NarrowOut<InT>::type NarrowT;
+#define FGE_GATED(OT, COOP)                                                                     \
+    do {                                                                                        \
+        auto kern = tile_kernel<InT, OT, 256, 256, 2, 4, COOP, false, false, true>;             \
+        if (COOP) {                                                                             \
+            static const int resident = resident_workgroups(reinterpret_cast<const void *>(kern), 512); \
+            if ((int)grid.x > resident) return hipErrorCooperativeLaunchTooLarge;               \
+        }                                                                                       \
+        hipLaunchKernelGGL(kern, grid, dim3(512), 0, s, a);                                     \
+    } while (0)
+    if (out_dtype != FGE_F32) { if (a.coop) FGE_GATED(NarrowT, true); else FGE_GATED(NarrowT, false); }
+    else                      { if (a.coop) FGE_GATED(float, true);   else FGE_GATED(float, false); }
+#undef FGE_GATED
+    return hipGetLastError();
+}
+hipError_t launch_gated_bf16(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
+hipError_t launch_gated_f16(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
+
 // Whether launch_tile_any has a cooperative kernel for this tile and operand type.
 inline bool tile_has_coop(int tile, int in_dtype) {
+    if (tile == TILE_GATED) return true;
     return in_dtype != FGE_F32 ? (tile == TILE_128x128 || tile == TILE_256x256) : tile == TILE_64x128;
 }
 

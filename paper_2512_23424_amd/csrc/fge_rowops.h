@@ -8,6 +8,7 @@ namespace fge {
 
 struct RowArgs {
     const void *in;             // rows x N, element type T, same strides as out
+    const void *in2;            // act only: optional second operand, out = act(in) * in2
     void *out;
     const float *gamma, *beta;
     float *aux;
@@ -19,7 +20,8 @@ struct RowArgs {
     int tiles_n, bn;            // finish only: column strips per row and their width
 };
 
-// K2: A = act(Y), elementwise, 16 bytes per lane per step.
+// K2: A = act(Y) (times a second operand in the gated sequence), elementwise, 16 bytes per lane
+// per step.
 template <typename T>
 __global__ __launch_bounds__(256) void act_kernel(const RowArgs a) {
     constexpr int CW = Store<T>::CW;
@@ -37,6 +39,12 @@ __global__ __launch_bounds__(256) void act_kernel(const RowArgs a) {
             Store<T>::unpack(*reinterpret_cast<const uint4 *>(in + off), v);
 #pragma unroll
             for (int e = 0; e < CW; ++e) v[e] = activate<ACT>(v[e], a.lo, a.hi);
+            if (a.in2 != nullptr) {                                   // gate
+                float u[CW];
+                Store<T>::unpack(*reinterpret_cast<const uint4 *>(reinterpret_cast<const T *>(a.in2) + off), u);
+#pragma unroll
+                for (int e = 0; e < CW; ++e) v[e] *= u[e];
+            }
             *reinterpret_cast<uint4 *>(out + off) = Store<T>::pack(v);
         }
     });

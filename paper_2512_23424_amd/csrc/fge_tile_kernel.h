@@ -93,10 +93,16 @@ template <> struct Mma<float> {
 // Relative error per product <= about 2^-16.5, against 2^-24 of the fp32 instruction, at less
 // than a fifth of its matrix-pipe time (3 x 8 passes per 16 k instead of 8 x 16 passes).
 template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N, bool COOP = false, bool FULL = false,
-          bool SPLIT = false>
+          bool SPLIT = false, bool GATED = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN <= 64 * 128 ? 2 : 1))
 void tile_kernel(const TileArgs a) {
     static_assert(!SPLIT || sizeof(InT) == 4, "only fp32 operands are split");
+    // GATED: the tile is act(X.W1^T + b1) * (X.W2^T + b2) over BN/2 output columns.  The B panel
+    // holds the BN/2 rows of W1 and, below them, the same rows of W2; each wave's column blocks
+    // are 32 columns of the first product and the same 32 columns of the second, so the gate is
+    // applied register by register before the shared epilogue sees a tile of BN/2 columns.
+    static_assert(!GATED || (sizeof(InT) == 2 && BN / WAVES_N == 64 && !SPLIT), "gated form: two 32-column blocks per wave");
+    constexpr int BNO = GATED ? BN / 2 : BN;         // output columns per tile
     constexpr int NT = 64 * WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int MB = WTM / 32, NB = WTN / 32;
@@ -158,7 +164,7 @@ void tile_kernel(const TileArgs a) {
         z = blockIdx.z;
         rowblock = z * a.tiles_m + tm;
     }
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int m0 = tm * BM, n0 = tn * BNO;
 
     const InT *X = reinterpret_cast<const InT *>(a.X) + (int64_t)z * a.bsx;
     const InT *W = reinterpret_cast<const InT *>(a.W);
@@ -180,8 +186,12 @@ void tile_kernel(const TileArgs a) {
     for (int i = 0; i < A_LD; ++i)
         gA[i] = X + (int64_t)min(m0 + ld_row + i * RSTEP, a.M - 1) * a.ldx + ld_gc * CW;
 #pragma unroll
-    for (int i = 0; i < B_LD; ++i)
-        gB[i] = W + (int64_t)min(n0 + ld_row + i * RSTEP, a.N - 1) * a.ldw + ld_gc * CW;
+    for (int i = 0; i < B_LD; ++i) {
+        const int prow = ld_row + i * RSTEP;         // panel row; gated: rows >= BNO come from W2
+        const bool second = GATED && prow >= BNO;
+        const InT *Wm = second ? reinterpret_cast<const InT *>(a.W2) : W;
+        gB[i] = Wm + (int64_t)min(n0 + prow - (second ? BNO : 0), a.N - 1) * a.ldw + ld_gc * CW;
+    }
 
     // full tile: asynchronous global -> LDS, no registers involved; completion is tracked by
     // the vector-memory counter (wait for it, then barrier, before anyone reads the tile)
@@ -216,7 +226,10 @@ void tile_kernel(const TileArgs a) {
     };
 
     // ---------------- fragment read plan
-    const int fa_row = wave_m * WTM + l32, fb_row = wave_n * WTN + l32;
+    // B fragment of column block j sits FB_STEP panel rows below block 0's (gated: the second
+    // product's rows start BNO rows down)
+    constexpr int FB_STEP = GATED ? BNO : 32;
+    const int fa_row = wave_m * WTM + l32, fb_row = wave_n * (GATED ? 32 : WTN) + l32;
     // chunk pair u (0..3) of a panel row: lanes 0-31 take chunk 2u, lanes 32-63 chunk 2u+1.
     // A k-step consumes FR pairs.  Which k land in which lane and slot does not matter as long
     // as both operands use the same assignment - the sum over k is complete either way.
@@ -247,7 +260,7 @@ void tile_kernel(const TileArgs a) {
         for (int c = 0; c < FR; ++c) {
             const int off = fsw[(t & (KS - 1)) * FR + c];
             fr[t & 1][q][c] = q < MB ? *reinterpret_cast<const u32x4 *>(sA + q * 32 * ROWB + off)
-                                     : *reinterpret_cast<const u32x4 *>(sB + (q - MB) * 32 * ROWB + off);
+                                     : *reinterpret_cast<const u32x4 *>(sB + (q - MB) * FB_STEP * ROWB + off);
         }
     };
     // prefetch order = order of first use: A0, B0..B(NB-1), A1..A(MB-1)
@@ -336,11 +349,35 @@ void tile_kernel(const TileArgs a) {
     // mainloop's last fragment reads are behind the barrier above.  The 64-row tiles are the
     // ones chosen to span N; they take the joint form (one exchange per tile).
     constexpr bool JOINT = BM == 64;
-    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 32, JOINT, false, COOP, FULL>;
-    static_assert(WAVES_M * WAVES_N * Epi::PATCH_FLOATS * 4 <= 2 * STAGE, "store patches fit the panels");
-    Epi epi(a, out, xch, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, BM, z, m0, n0, tn,
-            wave_n, lane);
-    epi.template tile<NT>(acc, wave_m * WTM, rowblock, tid);
+    if constexpr (GATED) {
+        // gate in the accumulator layout; the epilogue then takes finished values (no scale, bias
+        // or activation of its own) of a tile that is one 32-column block per wave wide
+        const int col = n0 + wave_n * 32 + l32;
+        const float scale = a.post * a.alpha;
+        const float bias1 = (a.b != nullptr && col < a.N) ? a.post * a.b[col] : 0.0f;
+        const float bias2 = (a.b2 != nullptr && col < a.N) ? a.post * a.b2[col] : 0.0f;
+        floatx16 gated[MB][1];
+        dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    gated[i][0][r] = activate<ACT>(scale * acc[i][0][r] + bias1, a.lo, a.hi) * (scale * acc[i][1][r] + bias2);
+        });
+        TileArgs ag = a;
+        ag.act = FGE_ACT_NONE; ag.alpha = 1.0f; ag.post = 1.0f; ag.b = nullptr;
+        using Epi = TileEpilogue<OutT, MB, 1, WAVES_N, 32, false, false, COOP, false>;
+        static_assert(WAVES_M * WAVES_N * Epi::PATCH_FLOATS * 4 <= 2 * STAGE, "store patches fit the panels");
+        Epi epi(ag, out, xch, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, BM, z, m0, n0, tn,
+                wave_n, lane);
+        epi.template tile<NT>(gated, wave_m * WTM, rowblock, tid);
+    } else {
+        using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 32, JOINT, false, COOP, FULL>;
+        static_assert(WAVES_M * WAVES_N * Epi::PATCH_FLOATS * 4 <= 2 * STAGE, "store patches fit the panels");
+        Epi epi(a, out, xch, reinterpret_cast<float *>(smem) + wave * Epi::PATCH_FLOATS, BM, z, m0, n0, tn,
+                wave_n, lane);
+        epi.template tile<NT>(acc, wave_m * WTM, rowblock, tid);
+    }
     if constexpr (COOP) __syncthreads();             // patches are panel memory of the next tile
     }
 }

@@ -32,7 +32,7 @@ ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF, ACT_SILU, ACT_CLAMP = range(6)
 NORM_NONE, NORM_SOFTMAX, NORM_LAYERNORM, NORM_RMSNORM, NORM_LOGSUMEXP = range(5)
 F32, BF16, F16 = 0, 1, 2
 
-TENSOR_ID = {"X": 0, "W": 1, "b": 2, "gamma": 3, "beta": 4}
+TENSOR_ID = {"X": 0, "W": 1, "b": 2, "gamma": 3, "beta": 4, "W2": 5, "b2": 6}   # W2, b2: gated form
 
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
@@ -221,3 +221,13 @@ def as_f64(a: Optional[np.ndarray]) -> Optional[np.ndarray]:
     if a.dtype == np.uint16:
         return bf16_bits_to_f32(a).astype(np.float64)
     return a.astype(np.float64)
+
+
+def generate_gated(w: Workload) -> Dict[str, Optional[np.ndarray]]:
+    """Tensors of the gated form of a workload: those of generate() with W, b as the first
+    product's, plus W2 (drawn like W) and b2 (drawn like b) from streams of their own."""
+    out = generate(w)
+    out["W2"] = draw(w.seed, "W2", (w.N, w.K), w.dist["W"], w.in_dtype)
+    d = w.dist.get("b")
+    out["b2"] = None if d is None else draw(w.seed, "b2", (w.N,), d, F32)
+    return out
