@@ -3,8 +3,8 @@
  *
  * The operation is the fused operator chain that a kernel generator emits for a dense layer
  * followed by an activation and a row-wise reduction / normalisation (the paper's "fused
- * operations" and "normalization operations" categories, Section 4; the reason for fusing -
- * no intermediate memory traffic, one launch instead of several - is its Section 5.3):
+ * operations" and "normalization operations" categories, Section 3.6; the reason for fusing -
+ * no intermediate memory traffic, one launch instead of several - is its Section 4.3):
  *
  *     Y   = post_scale * (alpha * X . W^T + b)          X: rows x K,  W: N x K,  b: N
  *     A   = act(Y)                                      elementwise
@@ -97,8 +97,22 @@ typedef enum {
  *   into two bf16 terms, x = xh + xl:  x*w ~= xl*wh + xh*wl + xh*wh with fp32 accumulation.
  *   Relative error per product <= about 2^-16.5 (a few 1e-5 on the final result, inside the
  *   1e-4 the fp32 path is held to, and exact for operands that bf16 holds exactly) at less than a
- *   fifth of the matrix-pipe time.  bf16 operands are not affected. */
-enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2 };
+ *   fifth of the matrix-pipe time.  bf16 operands are not affected.
+ *   FGE_FLAG_TILE(t) : run the tile kernels with tile configuration t (an fge_tile) instead of
+ *   the library's own choice - for tuning and tests.  A configuration without kernels for the
+ *   operand type (or the narrow-K kernel outside K <= 64, N <= 512, fp32) yields
+ *   FGE_ERR_UNSUPPORTED.  Ignored by the gated form and by shapes that take the element-granular
+ *   kernels. */
+enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_TILE_MASK = 0xF00 };
+#define FGE_FLAG_TILE(t) ((((int)(t)) + 1) << 8)
+
+/* Tile configurations (rows x columns of one workgroup's output tile).  16-bit operands: 64x64,
+ * 64x512, 128x128, 256x256; fp32 operands: 64x64, 64x512, 64x128 and the persistent narrow-K
+ * kernel. */
+typedef enum {
+    FGE_TILE_64x64 = 0, FGE_TILE_64x512 = 1, FGE_TILE_128x128 = 2, FGE_TILE_256x256 = 3,
+    FGE_TILE_NARROW_K = 4, FGE_TILE_64x128 = 5
+} fge_tile;
 
 typedef struct fge_params {
     int32_t M, N, K, batch;        /* rows per problem, columns, contraction length, problems  */
@@ -135,7 +149,7 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p);
 
 /* ---- the gated form (the "SiLU-and-Mul" / "GELU-and-Mul" fused operators of the paper's
- * benchmark section, Section 4, followed by the optional row operation):
+ * benchmark section, Section 3.6, followed by the optional row operation):
  *
  *     out = rowop_N( act(post_scale*(alpha*X.W1^T + b1)) * (post_scale*(alpha*X.W2^T + b2)) )
  *

@@ -7,7 +7,7 @@ constant (Section 3.2.3, the element error of the Verifier).
 
 Secondary gate: the paper's own pass rule (same section): element error is relative above the
 constant and absolute below it, and the fraction of elements whose error exceeds tau must not
-exceed tau (tau = 1e-3 for fp32 in Section 5.1; no bf16 value is given there)."""
+exceed tau (tau = 1e-3 for fp32 in Section 4.1; no bf16 value is given there)."""
 import numpy as np
 
 

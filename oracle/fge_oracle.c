@@ -12,8 +12,8 @@
  *
  *   - the chain itself (a dense contraction, a bias, an elementwise activation, a row-wise
  *     normalisation) is the "fused operator" pattern of the paper's benchmark section
- *     (Section 4: matmul, activations, Softmax, LayerNorm, RMSNorm and fused variants) and of
- *     its performance discussion (Section 5.3: eager mode composes LayerNorm from mean,
+ *     (Section 3.6: matmul, activations, Softmax, LayerNorm, RMSNorm and fused variants) and of
+ *     its performance discussion (Section 4.3: eager mode composes LayerNorm from mean,
  *     variance and normalisation steps);
  *   - RMSNorm follows the paper's Unified-Sketch example (Fig. 2): sum of squares over the
  *     reduced axis, divide by its length, add eps, square root, divide the input by it;
@@ -147,7 +147,7 @@ int fge_oracle_threads(void) { return 1; }
 #endif
 
 /* Gated variant (the "SiLU-and-Mul" / "GELU-and-Mul" fused operators the paper's benchmark
- * section lists among the fused operations, Section 4): two products sharing X,
+ * section lists among the fused operations, Section 3.6): two products sharing X,
  *     G = post_scale * (alpha * X.W1^T + b1),   U = post_scale * (alpha * X.W2^T + b2),
  *     A = act(G) * U   elementwise,             out = rowop_N(A).
  * Gate step: A[t] = act(G[t]) * U[t], written into G. */

@@ -50,12 +50,33 @@ struct Plan {
     size_t ws_generic;           // fused, generic: bytes of the fp32 rows x N intermediate
 };
 
+// Tile asked for through the flags (FGE_FLAG_TILE), -1 for the automatic choice.
+inline int forced_tile(const fge_params *p) { return ((p->flags & FGE_FLAG_TILE_MASK) >> 8) - 1; }
+
+// A forced tile must be one that has kernels for the operand type; the narrow-K kernel also
+// keeps its shape limits.
+bool forced_tile_ok(const fge_params *p) {
+    const int t = forced_tile(p);
+    if (t < 0) return true;
+    const bool f32 = p->in_dtype == FGE_F32;
+    switch (t) {
+    case TILE_64x64: case TILE_64x512: return true;
+    case TILE_128x128: case TILE_256x256: return !f32;
+    case TILE_64x128: return f32;
+    case TILE_PANEL:
+        return f32 && !(p->flags & FGE_FLAG_IEEE_FP32) && p->K <= 64 && p->N <= 512 &&
+               (p->batch == 1 || (p->batch_stride_x == (int64_t)p->M * p->ldx && p->batch_stride_o == (int64_t)p->M * p->ldo));
+    default: return false;
+    }
+}
+
 // Checks everything that does not depend on the path (fused / stage) being run.
 int check_common(const fge_params *p, int act, int norm, bool need_in) {
     if (p == nullptr) return FGE_ERR_NULL;
     if (act < FGE_ACT_NONE || act > FGE_ACT_CLAMP) return FGE_ERR_BAD_ENUM;
     if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
-    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32)) return FGE_ERR_BAD_ENUM;
+    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32 | FGE_FLAG_TILE_MASK)) return FGE_ERR_BAD_ENUM;
+    if (!forced_tile_ok(p)) return FGE_ERR_UNSUPPORTED;
     if (p->in_dtype < FGE_F32 || p->in_dtype > FGE_F16 || p->out_dtype < FGE_F32 || p->out_dtype > FGE_F16)
         return FGE_ERR_BAD_ENUM;
     // out is fp32 or the 16-bit type that goes with the operands (bf16 with fp32 / bf16, fp16 with fp16)
@@ -129,7 +150,9 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
         pr.batch = 1;
         pr.bsx = pr.bso = 0;
     }
-    pl.tile = force_tile >= 0 ? force_tile : pick_tile(pr, p->in_dtype, norm, (p->flags & FGE_FLAG_IEEE_FP32) != 0);
+    pl.tile = force_tile >= 0        ? force_tile
+              : forced_tile(p) >= 0 ? forced_tile(p)
+                                    : pick_tile(pr, p->in_dtype, norm, (p->flags & FGE_FLAG_IEEE_FP32) != 0);
     const TileInfo &ti = tile_info(pl.tile);
     pl.tiles_m = (pr.M + ti.bm - 1) / ti.bm;
     pl.tiles_n = (pr.N + ti.bn - 1) / ti.bn;

@@ -3,7 +3,7 @@
 This module only *draws numbers*: it holds no arithmetic of the chain itself, so both the
 CPU float64 oracle and the HIP path can be fed from it without sharing any of the method's
 code.  The paper evaluates on operator suites (matmul / activation / softmax / LayerNorm /
-RMSNorm families, Section 4 "benchmark" paragraph); the five workloads below stand in for
+RMSNorm families, Section 3.6 "benchmark" paragraph); the five workloads below stand in for
 those families with fixed shapes and value distributions.
 
 Generator (counter based, order independent, reproducible on any host):

@@ -13,7 +13,7 @@ from paper_2512_23424_amd import inputs as I
 # max rel err: fp32 / bf16-in fp32-accumulate / fp16-in fp32-accumulate (one fp16 rounding of the
 # output is 2^-11 = 4.9e-4; the gate is the paper's float16 threshold)
 TOL = {I.F32: 1e-4, I.BF16: 2e-2, I.F16: 4e-3}
-# the paper's pass rule (fp32 and float16 values from its setup section, Section 5.1)
+# the paper's pass rule (fp32 and float16 values from its setup section, Section 4.1)
 TAU = {I.F32: 1e-3, I.BF16: 2e-2, I.F16: 4e-3}
 
 

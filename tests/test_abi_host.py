@@ -119,3 +119,27 @@ def test_status_strings_and_tile_names():
     assert B.fge_fused_needs_finish(1, 1, _params(N=64, ldo=64)) is False
     with pytest.raises(B.FgeError):
         B.fge_fused_needs_finish(1, 1, _params(M=0))
+
+
+def test_forced_tile_configurations():
+    """FGE_FLAG_TILE picks the tile configuration; one without kernels for the operand type is
+    refused before anything is launched."""
+    def tile(t):
+        return (t + 1) << 8
+    f32 = dict(M=512, N=1024, K=256, ldx=256, ldw=256, ldo=1024)
+    assert B.fge_tile_name(True, 2, 2, _params(**f32, flags=tile(0))) == "64x64_w2x2_splitbf16"
+    assert B.fge_tile_name(True, 2, 2, _params(**f32, flags=tile(1))) == "64x512_w1x4_splitbf16"
+    assert B.fge_tile_name(True, 2, 2, _params(**f32, flags=tile(5) | B.FLAG_IEEE_FP32)) == "64x128_w2x2"
+    for t in (2, 3):                                           # 128x128, 256x256: 16-bit operands only
+        assert _call(_params(**f32, flags=tile(t))) == 4
+    assert _call(_params(**f32, flags=tile(4))) == 4           # narrow-K kernel needs K <= 64, N <= 512
+    assert _call(_params(**f32, flags=tile(6))) == 4 and _call(_params(**f32, flags=tile(14))) == 4
+    b16 = dict(f32, in_dtype=1, out_dtype=1)
+    assert B.fge_tile_name(True, 2, 2, _params(**b16, flags=tile(3))) == "256x256_w2x4"
+    assert B.fge_tile_name(True, 2, 2, _params(**b16, flags=tile(2))) == "128x128_w2x2"
+    assert _call(_params(**b16, flags=tile(5))) == 4           # 64x128: fp32 operands only
+    nk = _params(M=100, N=328, K=40, ldx=40, ldw=40, ldo=328, flags=tile(4))
+    assert B.fge_tile_name(True, 5, 4, nk) == "panel64x512_w1x8_splitbf16"
+    # a forced tile changes the split-row bookkeeping accordingly
+    p = _params(**b16, flags=tile(0))
+    assert B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p)) == 512 * (16 * 2) * 8

@@ -302,7 +302,7 @@ def test_chain_matches_library_composition(name):
 
 def test_gated_chain_by_hand_and_special_cases():
     """The gated variant (act(G) * U, the SiLU-and-Mul / GELU-and-Mul operators of the paper's
-    Section 4): a hand-computed case, reductions to the plain chain, and the scaling of each
+    Section 3.6): a hand-computed case, reductions to the plain chain, and the scaling of each
     product - a swapped operand, a gate applied to the wrong factor or a bias added to the wrong
     product fails one of these."""
     X = np.array([[1.0, 2.0], [0.0, -1.0]])
