@@ -113,28 +113,30 @@ bool vectorisable(const fge_params *p, int norm, bool need_in) {
 
 constexpr int PANEL_MIN_ROWS = 4096;   // below this the persistent kernel cannot fill the chip
 
-int pick_tile(const Problem &pr, int in_dtype, int norm, bool ieee_fp32) {
-    // fp32, narrow K, row fits one tile, many rows: bound by the output stream (the kernel for it
-    // exists with the split product only)
-    if (in_dtype == FGE_F32 && !ieee_fp32 && pr.K <= 64 && pr.N <= 512 && pr.batch == 1 && pr.M >= PANEL_MIN_ROWS)
-        return TILE_PANEL;
-    // A tile spanning the whole row finishes the row operation without a second pass.
-    if (norm != FGE_NORM_NONE) {
-        if (pr.N <= 64) return TILE_64x64;
-        if (pr.N <= 512) return TILE_64x512;
+// Tile choice (checked against an exhaustive search over the configurations on a sweep of
+// shapes).  The rule is the same everywhere: the largest tile of the operand type's list that
+// still gives every CU a workgroup and is not much wider than the row; whether the rows end up
+// split over column tiles matters little, since split rows cost one small exchange.
+int pick_tile(const Problem &pr, int in_dtype, int /*norm*/, bool ieee_fp32) {
+    auto count = [&](int t) {
+        const TileInfo &ti = tile_info(t);
+        return (int64_t)((pr.M + ti.bm - 1) / ti.bm) * ((pr.N + ti.bn - 1) / ti.bn) * pr.batch;
+    };
+    auto fits = [&](int t) { return tile_info(t).bn <= (pr.N > 32 ? 2 * pr.N : 64); };
+    if (in_dtype == FGE_F32) {
+        // narrow K, a row of 257..512 columns (all eight waves of the kernel busy), many rows:
+        // bound by the output stream; the kernel for it exists with the split product only
+        if (!ieee_fp32 && pr.K <= 64 && pr.N > 256 && pr.N <= 512 && pr.batch == 1 && pr.M >= PANEL_MIN_ROWS)
+            return TILE_PANEL;
+        // very large problems: the wide tile halves the operand traffic per flop
+        if (fits(TILE_64x512) && pr.K >= 1024 && count(TILE_64x512) >= 2 * NUM_CU) return TILE_64x512;
+        // otherwise 64x128 tiles, two or three of which share a CU so that one's epilogue hides
+        // behind another's MFMAs
+        // (given at least two per CU; with fewer, 64x64 tiles fill the chip better)
+        return fits(TILE_64x128) && count(TILE_64x128) >= 2 * NUM_CU ? TILE_64x128 : TILE_64x64;
     }
-    // Otherwise the largest tile that still gives every CU at least one workgroup.  fp32 is
-    // bound by the MFMA rate, not by operand traffic: it takes 64x128 tiles, two or three of
-    // which share a CU so that one's epilogue hides behind another's MFMAs.
-    const int bf16_order[3] = {TILE_256x256, TILE_128x128, TILE_64x64};
-    const int f32_order[2] = {TILE_64x128, TILE_64x64};
-    const int *order = in_dtype != FGE_F32 ? bf16_order : f32_order;     // 16-bit operands share the list
-    const int n_order = in_dtype != FGE_F32 ? 3 : 2;
-    for (int t = 0; t < n_order; ++t) {
-        const TileInfo &ti = tile_info(order[t]);
-        const int64_t n = (int64_t)((pr.M + ti.bm - 1) / ti.bm) * ((pr.N + ti.bn - 1) / ti.bn) * pr.batch;
-        if (n >= NUM_CU || t == n_order - 1) return order[t];
-    }
+    if (fits(TILE_256x256) && count(TILE_256x256) >= NUM_CU) return TILE_256x256;
+    if (fits(TILE_128x128) && count(TILE_128x128) >= NUM_CU) return TILE_128x128;
     return TILE_64x64;
 }
 

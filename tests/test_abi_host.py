@@ -106,9 +106,12 @@ def test_status_strings_and_tile_names():
     # fp32 operands run the split-bf16 product unless the caller asks for the fp32 instruction
     assert B.fge_tile_name(True, 1, 1, _params(N=64, ldo=64)) == "64x64_w2x2_splitbf16"
     assert B.fge_tile_name(True, 1, 1, _params(N=64, ldo=64, flags=B.FLAG_IEEE_FP32)) == "64x64_w2x2"
-    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512, flags=B.FLAG_IEEE_FP32)) == "64x512_w1x4"
+    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512, flags=B.FLAG_IEEE_FP32)) == "64x128_w2x2"
     assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512)) == "panel64x512_w1x8_splitbf16"
-    assert B.fge_tile_name(True, 5, 4, _params(M=1000, N=512, ldo=512)) == "64x512_w1x4_splitbf16"
+    assert B.fge_tile_name(True, 5, 4, _params(M=1000, N=512, ldo=512)) == "64x64_w2x2_splitbf16"     # few tiles
+    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=256, ldo=256)) == "64x128_w2x2_splitbf16"  # row too narrow for it
+    huge = _params(M=4096, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096)
+    assert B.fge_tile_name(True, 2, 2, huge) == "64x512_w1x4_splitbf16"
     big = _params(M=8192, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, in_dtype=1, out_dtype=1)
     assert B.fge_tile_name(True, 4, 3, big) == "256x256_w2x4"
     assert B.fge_fused_needs_finish(4, 3, big) is False      # the tiles finish their rows themselves

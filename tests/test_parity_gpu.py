@@ -90,11 +90,14 @@ def test_narrow_k_persistent_kernel(norm, shape):
                              "beta": ("normal", 0.0, 0.1)})
         t = I.generate(w)
         d = {k: H.to_device(v) for k, v in t.items()}
-        p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(odt), device="cuda"))
+        # rows of up to 256 columns are not given to this kernel by default (half its waves would
+        # idle): it is asked for explicitly, which keeps its narrow-row handling under test
+        flags = 0 if N > 256 else (4 + 1) << 8
+        p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(odt), device="cuda"), flags=flags)
         assert B.fge_tile_name(True, act, norm, p).startswith("panel")
         ref, raux = H.oracle_chain(w, t)
         for path in ("fused", "unfused"):
-            got, gaux = H.run_gpu(w, t, path, dev=d)
+            got, gaux = H.run_gpu(w, t, path, dev=d, flags=flags)
             if odt == I.BF16:
                 # unfused keeps Y and A in bf16: |a| up to ~8 carries 2^-9*8 absolute error into
                 # the exponentials of a softmax, hence the wider gate for that path
@@ -107,7 +110,7 @@ def test_narrow_k_persistent_kernel(norm, shape):
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
 @pytest.mark.parametrize("case", [(I.BF16, 4100, 136, 4000, "256x256_w2x4"), (I.BF16, 2050, 200, 2040, "128x128_w2x2"),
                                   (I.F16, 4100, 136, 4000, "256x256_w2x4"), (I.F16, 2050, 200, 2040, "128x128_w2x2"),
-                                  (I.F32, 1030, 100, 2040, "64x128_w2x2_splitbf16")])
+                                  (I.F32, 2060, 100, 2040, "64x128_w2x2_splitbf16")])
 def test_split_rows_one_kernel_and_two_pass(norm, case):
     """Rows split over column tiles, large enough for the one-kernel form (the tiles of a row
     block exchange statistics and finish their rows themselves): ragged M / N / K, a partial
@@ -305,7 +308,7 @@ def test_graph_capture_and_replay():
     nodes, and on a capturing stream split rows take the two-pass form (a replay repeats the
     recorded arguments, so arrival marks could not tell one replay from the next).  Every
     replay - with eager work and synchronisations between them - reproduces the eager result."""
-    for (dt, M, K, N) in [(I.BF16, 4100, 136, 4000), (I.F32, 1030, 100, 2040), (I.F32, 5000, 40, 328)]:
+    for (dt, M, K, N) in [(I.BF16, 4100, 136, 4000), (I.F32, 2060, 100, 2040), (I.F32, 5000, 40, 328)]:
         w = I.Workload(name="graph", M=M, K=K, N=N, in_dtype=dt, out_dtype=dt, act=I.ACT_SILU,
                        norm=I.NORM_RMSNORM, eps=1e-5,
                        dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1), "gamma": ("normal", 1.0, 0.1)})
