@@ -148,6 +148,13 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
  * arguments; 0 is a valid answer.  Returns (size_t)-1 when the arguments are invalid. */
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p);
 
+/* Where the one-kernel form of split rows reports a wait that ran out: byte offset into the
+ * workspace of an int32 that such a launch sets to 1 (it never clears it; the result of that
+ * launch is then invalid).  (size_t)-1 when fused_gemm_epilogue does not take that form for
+ * these arguments.  A caller that wants the check clears the word before the call and reads it
+ * after synchronising. */
+size_t fge_fault_word_offset(int act, int norm, const fge_params *p);
+
 /* ---- the gated form (the "SiLU-and-Mul" / "GELU-and-Mul" fused operators of the paper's
  * benchmark section, Section 3.6, followed by the optional row operation):
  *

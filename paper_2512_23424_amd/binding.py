@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).restype = ci
         L.fge_gated_workspace_bytes.argtypes = [ci, ci, ci, pp]
         L.fge_gated_workspace_bytes.restype = ctypes.c_size_t
+        L.fge_fault_word_offset.argtypes = [ci, ci, pp]
+        L.fge_fault_word_offset.restype = ctypes.c_size_t
         L.fge_gated_tile_name.argtypes = [ci, ci, pp]
         L.fge_gated_tile_name.restype = ctypes.c_char_p
         _lib = L
@@ -233,3 +235,9 @@ def fge_gated_workspace_bytes(fused: bool, act, norm, p: FgeParams) -> int:
 def fge_gated_tile_name(act, norm, p: FgeParams) -> str:
     s = lib().fge_gated_tile_name(_code(ACT, act), _code(NORM, norm), ctypes.byref(p))
     return "" if s is None else s.decode()
+
+
+def fge_fault_word_offset(act, norm, p: FgeParams) -> Optional[int]:
+    """Offset of the fault word in the workspace, or None when the call takes no cooperative form."""
+    n = lib().fge_fault_word_offset(_code(ACT, act), _code(NORM, norm), ctypes.byref(p))
+    return None if n == ctypes.c_size_t(-1).value else n

@@ -526,6 +526,12 @@ const char *fge_gated_tile_name(int act, int norm, const fge_params *p) {
     return gated_fast(p, norm) ? tile_info(TILE_GATED).name : "unfused_sequence";
 }
 
+size_t fge_fault_word_offset(int act, int norm, const fge_params *p) {
+    if (check_common(p, act, norm, true)) return (size_t)-1;
+    const Plan pl = make_plan(p, norm);
+    return pl.coop ? pl.ws_stats + pl.ws_marks - 256 : (size_t)-1;
+}
+
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return (size_t)-1;
     const Plan pl = make_plan(p, norm);

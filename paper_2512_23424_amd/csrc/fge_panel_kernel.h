@@ -37,9 +37,6 @@ __device__ __forceinline__ void mfma_bf16(const u32x4 &a, const u32x4 &b, floatx
                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-#ifndef PANEL_JOINT
-#define PANEL_JOINT false
-#endif
 struct PanelShape {
     static constexpr int BM = 64, BN = 512, WAVES_N = 8, MB = 2, NB = 2, KMAX = 64;
     static constexpr int THREADS = 64 * WAVES_N;
@@ -56,7 +53,7 @@ void panel_kernel(const TileArgs a) {
     constexpr int XROWB = 256;                        // LDS bytes per X row: 64 fp32
     constexpr int XTILE = BM * XROWB;                 // 16 KB
     constexpr int X_LD = BM * 16 / NT;                // 16-byte chunks per thread per tile (2)
-    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, PANEL_JOINT, true, false, FULL, STREAM>;
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, false, true, false, FULL, STREAM>;
 
     __shared__ __attribute__((aligned(16))) unsigned char xs[2 * XTILE];
     __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];

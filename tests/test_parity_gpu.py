@@ -141,10 +141,16 @@ def test_split_rows_one_kernel_and_two_pass(norm, case):
                       gamma=d["gamma"], beta=d["beta"], aux_out=aux)
     ws = torch.empty(B.fge_workspace_bytes(True, w.act, norm, p), dtype=torch.uint8, device="cuda")
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+    off = B.fge_fault_word_offset(w.act, norm, p)
+    assert off is not None and off % 4 == 0 and off + 4 <= ws.numel()
+    ws.zero_()
     for o in outs:
         B.fused_gemm_epilogue(d["X"], d["W"], d["b"], w.act, norm, p, o)
     torch.cuda.synchronize()
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert int(ws[off:off + 4].view(torch.int32)[0]) == 0        # no wait ran out
+    p.flags = B.FLAG_TWO_PASS
+    assert B.fge_fault_word_offset(w.act, norm, p) is None
     assert np.array_equal(H.to_host_f64(outs[0]), H.run_gpu(w, t, "fused", dev=d)[0])
 
 
