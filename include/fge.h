@@ -164,8 +164,9 @@ size_t fge_fault_word_offset(int act, int norm, const fge_params *p);
  * else is as for fused_gemm_epilogue.  The fused call runs one tile kernel that forms both
  * products from one staged X panel and applies the gate to the accumulators, for bf16 / fp16
  * operands in shapes the fast kernels take; every other case (fp32 operands, odd extents) runs
- * the unfused sequence: two GEMMs into the workspace, the gate as an elementwise kernel, the row
- * operation.  fge_gated_workspace_bytes gives the workspace either call needs;
+ * the unfused sequence: two GEMMs into the workspace (fp32 operands always on the fp32 matrix
+ * instruction here: the gate multiplies two products and their errors), the gate as an
+ * elementwise kernel, the row operation.  fge_gated_workspace_bytes gives the workspace either call needs;
  * fge_gated_tile_name names what the fused call runs ("unfused_sequence" for the fallback). */
 int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, const float *b1,
                               const float *b2, int act, int norm, const fge_params *p, void *out,

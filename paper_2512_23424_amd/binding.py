@@ -162,7 +162,7 @@ def _check(rc: int, where: str) -> None:
 def fge_workspace_bytes(fused: bool, act, norm, p: FgeParams) -> int:
     n = lib().fge_workspace_bytes(int(bool(fused)), _code(ACT, act), _code(NORM, norm), ctypes.byref(p))
     if n == ctypes.c_size_t(-1).value:
-        raise FgeError(3, "fge_workspace_bytes (invalid arguments)")
+        raise FgeError(4, "fge_workspace_bytes (invalid or unsupported arguments)")
     return n
 
 
@@ -228,7 +228,7 @@ def unfused_gated_gemm_epilogue(X, W1, W2, b1, b2, act, norm, p: FgeParams, out,
 def fge_gated_workspace_bytes(fused: bool, act, norm, p: FgeParams) -> int:
     n = lib().fge_gated_workspace_bytes(int(bool(fused)), _code(ACT, act), _code(NORM, norm), ctypes.byref(p))
     if n == ctypes.c_size_t(-1).value:
-        raise FgeError(3, "fge_gated_workspace_bytes (invalid arguments)")
+        raise FgeError(4, "fge_gated_workspace_bytes (invalid or unsupported arguments)")
     return n
 
 

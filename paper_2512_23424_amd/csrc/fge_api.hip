@@ -471,9 +471,14 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
 // ---- gated form: out = rowop(act(post*(alpha*X.W1^T + b1)) * (post*(alpha*X.W2^T + b2)))
 
 int unfused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, const float *b1, const float *b2,
-                                int act, int norm, const fge_params *p, void *out, void *stream) {
-    int rc = check_common(p, act, norm, true);
+                                int act, int norm, const fge_params *p_in, void *out, void *stream) {
+    int rc = check_common(p_in, act, norm, true);
     if (rc) return rc;
+    // fp32 operands: the gate multiplies two products, and with it their errors - two split-bf16
+    // products would leave the 1e-4 the fp32 path is held to, so both use the fp32 instruction
+    fge_params q = *p_in;
+    if (q.in_dtype == FGE_F32) q.flags |= FGE_FLAG_IEEE_FP32;
+    const fge_params *p = &q;
     if (!X || !W1 || !W2 || !out) return FGE_ERR_NULL;
     if (!aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(out) || !aligned16(b1) || !aligned16(b2))
         return FGE_ERR_ALIGN;

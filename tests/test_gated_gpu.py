@@ -98,3 +98,21 @@ def test_gated_exact_integers_and_fp32_result():
         got, _, _ = _run(w, d, path)
         if path == "fused":
             assert np.array_equal(got, ref)
+
+
+def test_gated_fp32_keeps_the_fp32_gate():
+    """The gate multiplies two products and their errors: with fp32 operands both products run on
+    the fp32 matrix instruction, which keeps the chain inside 1e-4 (two split-bf16 products left
+    it on this shape)."""
+    w = I.Workload(name="g32", M=583, K=84, N=316, in_dtype=I.F32, out_dtype=I.F32, act=I.ACT_GELU_ERF,
+                   norm=I.NORM_LAYERNORM, alpha=0.9, post_scale=1.3, eps=1e-5,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.6 / 84 ** 0.5), "b": ("uniform", -0.5, 0.5),
+                         "gamma": ("normal", 1.0, 0.1), "beta": ("normal", 0.0, 0.1)})
+    t = I.generate_gated(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    ref, _ = _oracle(w, t)
+    for path in ("fused", "unfused"):
+        got, _, _ = _run(w, d, path)
+        err = H.C.max_rel_err(got, ref)
+        print(f"gated fp32 {path}: {err:.3e}", flush=True)
+        assert err <= 2e-5
