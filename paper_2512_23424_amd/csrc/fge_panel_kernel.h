@@ -5,9 +5,10 @@
 //   * persistent workgroups (one per CU, 8 waves side by side along N) walk over 64-row tiles;
 //     W never leaves the registers: each wave keeps the MFMA B fragments of its 64 columns,
 //     already split, for the whole launch;
-//   * the X tile of the next step is copied global -> LDS asynchronously while the current one
-//     is multiplied and its epilogue runs; the stores of a tile are queued only after that copy
-//     has landed, so nothing ever waits on a store;
+//   * every wave multiplies all 64 rows of a tile, so the fp32 X tile is split into its bf16
+//     parts once per workgroup (each thread fetches and splits 8 values) and parked in LDS as
+//     two bf16 images; the fetch of the next tile is issued before the current product and its
+//     result is parked before the current tile's stores are queued, so nothing waits on a store;
 //   * the product uses the bf16 matrix instruction on a two-term split of the fp32 operands,
 //         x = xh + xl,  w = wh + wl  (xh, wh: bf16 roundings; xl, wl: bf16 roundings of the rest)
 //         x*w ~= xh*wh + xh*wl + xl*wh          (fp32 accumulate)
@@ -50,12 +51,13 @@ void panel_kernel(const TileArgs a) {
     constexpr int BM = PanelShape::BM, BN = PanelShape::BN, WAVES_N = PanelShape::WAVES_N;
     constexpr int MB = PanelShape::MB, NB = PanelShape::NB, NT = PanelShape::THREADS;
     constexpr int WTN = NB * 32;
-    constexpr int XROWB = 256;                        // LDS bytes per X row: 64 fp32
-    constexpr int XTILE = BM * XROWB;                 // 16 KB
-    constexpr int X_LD = BM * 16 / NT;                // 16-byte chunks per thread per tile (2)
-    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, false, true, false, FULL, STREAM>;
+    constexpr int SROWB = 128;                        // LDS bytes per row of a bf16 image: 64 values
+    constexpr int SIMG = BM * SROWB;                  // 8 KB; an X buffer is the image of the high
+    constexpr int XBUF = 2 * SIMG;                    // parts followed by the image of the low parts
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, false, false, false, FULL, STREAM>;
+    static_assert(NT == BM * 8, "one thread per (row, 8 values of k) of an X tile");
 
-    __shared__ __attribute__((aligned(16))) unsigned char xs[2 * XTILE];
+    __shared__ __attribute__((aligned(16))) unsigned char xs[2 * XBUF];
     __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];
     __shared__ __attribute__((aligned(16))) float patches[(NT / 64) * Epi::PATCH_FLOATS];
 
@@ -65,11 +67,6 @@ void panel_kernel(const TileArgs a) {
     const float *X = reinterpret_cast<const float *>(a.X);
     const float *W = reinterpret_cast<const float *>(a.W);
     OutT *out = reinterpret_cast<OutT *>(a.out);
-
-    // zero both X buffers once: chunks past K are never written by the copies below
-#pragma unroll
-    for (int i = 0; i < 2 * XTILE / 16 / NT; ++i)
-        *reinterpret_cast<u32x4 *>(xs + (i * NT + tid) * 16) = u32x4{0u, 0u, 0u, 0u};
 
     // ---------------- W fragments of this wave's 64 columns, split once, kept in registers
     // fragment (j, t): column wave_n*64 + j*32 + l32, k = 16t + 8h .. +7
@@ -91,45 +88,48 @@ void panel_kernel(const TileArgs a) {
         }
     }
 
-    // ---------------- X tile copy plan.  LDS image: row-major, 16 chunks of 16 bytes per row,
-    // chunk c stored at c ^ (row & 15) so that the 16 rows read by a quarter wave hit all 64
-    // banks.  A wave's copy instruction fills 1024 contiguous bytes (4 rows), lane l at +16*l.
-    int x_row[X_LD], x_gc[X_LD];
+    // ---------------- X tiles.  Every wave multiplies all 64 rows, so the tile is split once for
+    // the workgroup: thread (row, c) = (tid / 8, tid % 8) fetches the 8 values k = 8c .. 8c+7 of
+    // its row into registers while the previous tile is multiplied, splits them, and parks the two
+    // 16-byte bf16 chunks in LDS.  Image: 128-byte rows, chunk c stored at c ^ ((row >> 1) & 7),
+    // which keeps the fragment reads below (32 rows x 2 chunks per instruction) off each other's
+    // banks.  Values past K are zero.
+    const int s_row = tid >> 3, s_c = tid & 7;
+    const int s_off = s_row * SROWB + ((s_c ^ ((s_row >> 1) & 7)) << 4);
+    floatx4 xin[2];
+    auto load_x = [&](int m0) __attribute__((always_inline)) {
+        const float *g = X + (int64_t)min(m0 + s_row, a.M - 1) * a.ldx + s_c * 8;
 #pragma unroll
-    for (int i = 0; i < X_LD; ++i) {
-        x_row[i] = (i * (NT / 64) + wave) * 4 + (lane >> 4);
-        x_gc[i] = (lane & 15) ^ (x_row[i] & 15);
-    }
-    auto dma_x = [&](int buf, int m0) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < X_LD; ++i) {
-            if (x_gc[i] * 4 < a.K) {
-                const float *g = X + (int64_t)min(m0 + x_row[i], a.M - 1) * a.ldx + x_gc[i] * 4;
-                unsigned char *s = xs + buf * XTILE + (i * (NT / 64) + wave) * 1024;
-                lds_dma16(g, s);
-            }
+        for (int c = 0; c < 2; ++c) {
+            xin[c] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (s_c * 8 + 4 * c < a.K) xin[c] = *reinterpret_cast<const floatx4 *>(g + 4 * c);
         }
     };
+    auto park_x = [&](int buf) __attribute__((always_inline)) {
+        const float f[8] = {xin[0][0], xin[0][1], xin[0][2], xin[0][3], xin[1][0], xin[1][1], xin[1][2], xin[1][3]};
+        u32x4 hi, lo;
+        split_bf16x8(f, hi, lo);
+        *reinterpret_cast<u32x4 *>(xs + buf * XBUF + s_off) = hi;
+        *reinterpret_cast<u32x4 *>(xs + buf * XBUF + SIMG + s_off) = lo;
+    };
 
-    // A fragment (i, t): row i*32 + l32, k = 16t + 8h .. +7 = chunks 4t + 2h and 4t + 2h + 1
-    // (every wave needs all 64 rows; the split of a fragment is recomputed per wave)
-    int fa_off[MB][4][2];
+    // A fragment (i, t): row i*32 + l32, k = 16t + 8h .. +7 = chunk 2t + h of that row
+    int fa_off[MB][4];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-                fa_off[i][t][c] = (i * 32 + l32) * XROWB + (((4 * t + 2 * h + c) ^ (l32 & 15)) << 4);
+            fa_off[i][t] = (i * 32 + l32) * SROWB + (((2 * t + h) ^ ((l32 >> 1) & 7)) << 4);
 
     Epi epi(a, out, xch, patches + wave * Epi::PATCH_FLOATS, BM, 0, 0, 0, 0, wave_n, lane);
 
     // ---------------- persistent loop over 64-row tiles
     const int ntiles = a.tiles_m;
     int tile = blockIdx.x;
-    __syncthreads();                                  // zero fill is complete
-    if (tile < ntiles) dma_x(0, tile * BM);
-    lds_dma_wait();
+    if (tile < ntiles) {
+        load_x(tile * BM);
+        park_x(0);
+    }
     // Whole-row logsumexp leaves `out` final without any exchange between the waves; only aux
     // needs all strips of a row.  The strips' pairs are parked in LDS and merged one iteration
     // later, behind the barrier the loop has anyway.
@@ -137,10 +137,11 @@ void panel_kernel(const TileArgs a) {
     int it = 0;
     for (; tile < ntiles; tile += gridDim.x, ++it) {
         const int buf = it & 1;
-        __syncthreads();    // tile `it` has landed for every wave; reads of the other buffer are over
+        __syncthreads();    // tile `it` is parked by every wave; reads of the other buffer are over
         if (epi.defer_lse && it > 0) epi.flush_lse(tid, (it - 1) & 1, (tile - (int)gridDim.x) * BM);
         const int next = tile + gridDim.x;
-        if (next < ntiles) dma_x(buf ^ 1, next * BM);
+        if (next < ntiles) load_x(next * BM);
+        __builtin_amdgcn_sched_barrier(0);            // the fetch stays ahead of the product
 
         floatx16 acc[MB][NB];
 #pragma unroll
@@ -154,10 +155,8 @@ void panel_kernel(const TileArgs a) {
             u32x4 ahi[MB], alo[MB];
 #pragma unroll
             for (int i = 0; i < MB; ++i) {
-                const floatx4 x0 = *reinterpret_cast<const floatx4 *>(xs + buf * XTILE + fa_off[i][t][0]);
-                const floatx4 x1 = *reinterpret_cast<const floatx4 *>(xs + buf * XTILE + fa_off[i][t][1]);
-                const float f[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
-                split_bf16x8(f, ahi[i], alo[i]);
+                ahi[i] = *reinterpret_cast<const u32x4 *>(xs + buf * XBUF + fa_off[i][t]);
+                alo[i] = *reinterpret_cast<const u32x4 *>(xs + buf * XBUF + SIMG + fa_off[i][t]);
             }
             // small terms first; the MB*NB accumulators keep successive MFMAs independent
 #pragma unroll
@@ -173,7 +172,10 @@ void panel_kernel(const TileArgs a) {
 #pragma unroll
                 for (int j = 0; j < NB; ++j) mfma_bf16(ahi[i], whi[j][t], acc[i][j]);
         }
-        // the epilogue waits for the copy of the next tile before it queues its stores
+        // the next tile has had the whole product to arrive; it is parked before this tile's
+        // stores are queued, so the wait never sits behind them
+        if (next < ntiles) park_x(buf ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
         epi.m0 = tile * BM;
         epi.lse_par = buf;
         epi.template tile<NT>(acc, 0, 0, tid);
