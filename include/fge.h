@@ -32,9 +32,12 @@
  * that no work was enqueued.  FGE_ERR_UNSUPPORTED is left for requests beyond the index range
  * (more than 2^30 rows in total) and operand / output type pairs outside the set below.
  *
- * Supported set.  in_dtype in {FGE_F32, FGE_BF16, FGE_F16}; out_dtype FGE_F32 or the 16-bit type
- * that goes with the operands (FGE_BF16 with fp32 and bf16 operands, FGE_F16 with fp16 operands;
- * other pairs yield FGE_ERR_UNSUPPORTED).  Accumulation and all epilogue arithmetic are fp32;
+ * Supported set.  in_dtype in {FGE_F32, FGE_BF16, FGE_F16, FGE_F8E4M3}; out_dtype FGE_F32 or the
+ * 16-bit type that goes with the operands (FGE_BF16 with fp32, bf16 and fp8 operands, FGE_F16 with
+ * fp16 operands; other pairs yield FGE_ERR_UNSUPPORTED).  FGE_F8E4M3 is the 8-bit format with 4
+ * exponent and 3 mantissa bits, bias 7, no infinities (largest value 448, 0x7F / 0xFF are NaN) -
+ * the "E4M3" of the OCP 8-bit floating point specification, one byte per element; per-tensor
+ * scales go into alpha.  Accumulation and all epilogue arithmetic are fp32;
  * 16-bit stores round to nearest even.  Any M, N, K, batch >= 1 and any
  * strides >= the extents.  Base pointers (X, W, b, out, gamma, beta, aux_out, workspace) must be
  * 16-byte aligned (else FGE_ERR_ALIGN).  The fast kernels move data in 16-byte units: they run
@@ -66,7 +69,7 @@ typedef enum {
     FGE_ERR_HIP = 7           /* a launch failed; see fge_last_hip_error()                   */
 } fge_status;
 
-typedef enum { FGE_F32 = 0, FGE_BF16 = 1, FGE_F16 = 2 } fge_dtype;
+typedef enum { FGE_F32 = 0, FGE_BF16 = 1, FGE_F16 = 2, FGE_F8E4M3 = 3 } fge_dtype;
 
 /* Activations (step A = act(Y)).  GELU_TANH: 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3)));
  * GELU_ERF: 0.5 y (1 + erf(y / sqrt 2)); SILU: y / (1 + exp(-y)); CLAMP: min(max(y, lo), hi). */

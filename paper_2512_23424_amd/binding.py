@@ -103,6 +103,8 @@ def _dt(t: torch.Tensor) -> int:
         return _codes.BF16
     if t.dtype == torch.float16:
         return _codes.F16
+    if t.dtype == torch.float8_e4m3fn:
+        return _codes.F8E4M3
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 

@@ -23,7 +23,7 @@ constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 CUs
 constexpr int MAX_ROWOP_N = 8192;    // a row must fit the register-resident row kernels
 constexpr int MAX_SPLIT = 1024;      // column strips per row the second pass will merge
 
-inline size_t esize(int dt) { return dt == FGE_F32 ? 4 : 2; }
+inline size_t esize(int dt) { return dt == FGE_F32 ? 4 : dt == FGE_F8E4M3 ? 1 : 2; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -77,9 +77,10 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
     if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
     if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32 | FGE_FLAG_TILE_MASK)) return FGE_ERR_BAD_ENUM;
     if (!forced_tile_ok(p)) return FGE_ERR_UNSUPPORTED;
-    if (p->in_dtype < FGE_F32 || p->in_dtype > FGE_F16 || p->out_dtype < FGE_F32 || p->out_dtype > FGE_F16)
+    if (p->in_dtype < FGE_F32 || p->in_dtype > FGE_F8E4M3 || p->out_dtype < FGE_F32 || p->out_dtype > FGE_F8E4M3)
         return FGE_ERR_BAD_ENUM;
-    // out is fp32 or the 16-bit type that goes with the operands (bf16 with fp32 / bf16, fp16 with fp16)
+    if (p->out_dtype == FGE_F8E4M3) return FGE_ERR_UNSUPPORTED;     // an operand type only
+    // out is fp32 or the 16-bit type that goes with the operands (bf16 with fp32 / bf16 / fp8, fp16 with fp16)
     if (need_in && p->out_dtype != FGE_F32 && p->out_dtype != (p->in_dtype == FGE_F16 ? FGE_F16 : FGE_BF16))
         return FGE_ERR_UNSUPPORTED;
     if (p->M <= 0 || p->N <= 0 || p->K <= 0 || p->batch <= 0) return FGE_ERR_BAD_SHAPE;
@@ -196,7 +197,9 @@ size_t fused_workspace(const fge_params *p, int norm) {
 }
 
 // The gated tile kernel takes 16-bit operands in shapes the vectorised kernels take.
-bool gated_fast(const fge_params *p, int norm) { return p->in_dtype != FGE_F32 && vectorisable(p, norm, true); }
+bool gated_fast(const fge_params *p, int norm) {
+    return (p->in_dtype == FGE_BF16 || p->in_dtype == FGE_F16) && vectorisable(p, norm, true);
+}
 
 size_t gated_workspace(const fge_params *p, int norm) {
     const Plan p1 = make_plan(p, norm, false, TILE_GATED), p2 = make_plan(p, norm, true, TILE_GATED);
@@ -264,6 +267,7 @@ int launch_tiles(const TileArgs &a, const fge_params *p, const Plan &pl, hipStre
                     a.coop ? 1u : (unsigned)pl.pr.batch);
     const hipError_t e = p->in_dtype == FGE_BF16       ? launch_tile_bf16(pl.tile, p->out_dtype, grid, s, a)
                          : p->in_dtype == FGE_F16      ? launch_tile_f16(pl.tile, p->out_dtype, grid, s, a)
+                         : p->in_dtype == FGE_F8E4M3   ? launch_tile_f8(pl.tile, p->out_dtype, grid, s, a)
                          : (p->flags & FGE_FLAG_IEEE_FP32) ? launch_tile_f32(pl.tile, p->out_dtype, grid, s, a)
                                                            : launch_tile_f32s(pl.tile, p->out_dtype, grid, s, a);
     return hip_status(e);

@@ -13,9 +13,11 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 struct bf16_t { uint16_t bits; };   // storage only; arithmetic is always fp32
 struct f16_t { uint16_t bits; };    // IEEE half, storage only
+struct f8_t { uint8_t bits; };      // 8-bit E4M3 (bias 7, no infinities), operand storage only
 
 __device__ __forceinline__ float as_f32(uint32_t v) { return __builtin_bit_cast(float, v); }
 __device__ __forceinline__ uint32_t as_u32(float v) { return __builtin_bit_cast(uint32_t, v); }
@@ -115,6 +117,14 @@ template <> struct Store<f16_t> {
             w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2_t));
         }
         return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+// Operands only: nothing is ever stored in this type.
+template <> struct Store<f8_t> {
+    static constexpr int CW = 16;
+    __device__ static __forceinline__ float get(const f8_t *p) {
+        return __builtin_amdgcn_cvt_f32_fp8((int)p->bits, 0);
     }
 };
 

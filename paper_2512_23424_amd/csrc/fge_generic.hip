@@ -139,6 +139,7 @@ hipError_t launch_generic_gemm(int in_dtype, int dst_dtype, hipStream_t s, const
     } while (0)
     if (in_dtype == FGE_BF16)     FGE_GG(bf16_t, bf16_t);
     else if (in_dtype == FGE_F16) FGE_GG(f16_t, f16_t);
+    else if (in_dtype == FGE_F8E4M3) FGE_GG(f8_t, bf16_t);
     else                          FGE_GG(float, bf16_t);
 #undef FGE_GG
     return hipGetLastError();

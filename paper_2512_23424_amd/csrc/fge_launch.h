@@ -33,6 +33,7 @@ hipError_t launch_tile_f32(int tile, int out_dtype, dim3 grid, hipStream_t s, co
 hipError_t launch_tile_f32s(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_tile_bf16(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_tile_f16(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
+hipError_t launch_tile_f8(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 // Defined in fge_panel_f32.hip: the persistent narrow-K kernel (grid = number of workgroups).
 hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 
@@ -64,7 +65,7 @@ inline int resident_workgroups(const void *kernel, int threads) {
 }
 
 // Which tiles exist for which operand type (tile selection on the host must agree):
-//   bf16, fp16: 64x64, 64x512, 128x128 (+ cooperative), 256x256 (+ cooperative)
+//   bf16, fp16, fp8: 64x64, 64x512, 128x128 (+ cooperative), 256x256 (+ cooperative)
 //   fp32: 64x64, 64x512, 64x128 (+ cooperative) - once with the fp32 matrix instruction and once
 //         with the split-bf16 product (SPLIT)
 // The 16-bit output type that goes with an operand type (the other output type is fp32).
@@ -98,7 +99,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
         if (out_dtype != FGE_F32)  FGE_LAUNCH_COOP1(BM, BN, WM, WN, NarrowT);                   \
         else                       FGE_LAUNCH_COOP1(BM, BN, WM, WN, float);                     \
     } while (0)
-    constexpr bool BF = sizeof(InT) == 2;
+    constexpr bool BF = sizeof(InT) <= 2;
     switch (tile) {
     case TILE_64x64:   FGE_LAUNCH(64, 64, 2, 2); break;
     case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4); break;

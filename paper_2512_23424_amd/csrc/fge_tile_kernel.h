@@ -71,6 +71,17 @@ template <> struct Mma<f16_t> {
                                                    __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
+template <> struct Mma<f8_t> {
+    // One instruction takes 64 k: 32 bytes per lane and operand, here two 16-byte chunks of the
+    // lane's panel row.  Which k sits in which lane half and byte is the same for both
+    // operands, so the sum over k is complete.  (Block scales switched off: both scale
+    // operands zero select the unscaled instruction.)
+    __device__ static __forceinline__ void run(const u32x4 (&a)[2], const u32x4 (&b)[2], floatx16 &c) {
+        const i32x8 av = {(int)a[0].x, (int)a[0].y, (int)a[0].z, (int)a[0].w, (int)a[1].x, (int)a[1].y, (int)a[1].z, (int)a[1].w};
+        const i32x8 bv = {(int)b[0].x, (int)b[0].y, (int)b[0].z, (int)b[0].w, (int)b[1].x, (int)b[1].y, (int)b[1].z, (int)b[1].w};
+        c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, c, 0, 0, 0, 0, 0, 0);
+    }
+};
 template <> struct Mma<float> {
     // A 16-byte fragment holds 4 consecutive k of one row; lanes 0-31 and 32-63 hold different
     // chunks.  The k pairing is the same for both operands, so the sum over k is complete.
@@ -107,11 +118,12 @@ void tile_kernel(const TileArgs a) {
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int MB = WTM / 32, NB = WTN / 32;
     constexpr int ROWB = 128;                        // bytes of K per LDS row
-    constexpr int BK = ROWB / (int)sizeof(InT);      // 64 bf16 / 32 fp32
+    constexpr int BK = ROWB / (int)sizeof(InT);      // 128 fp8 / 64 bf16 / 32 fp32
     constexpr int CW = 16 / (int)sizeof(InT);        // elements per 16-byte chunk
     constexpr int A_LD = BM * 8 / NT, B_LD = BN * 8 / NT;
     constexpr int RSTEP = NT / 8;                    // rows between a thread's successive chunks
-    constexpr int FR = SPLIT ? 2 : 1;                // 16-byte chunks per fragment per k-step
+    constexpr bool F8 = sizeof(InT) == 1;            // 64 k per matrix instruction
+    constexpr int FR = SPLIT || F8 ? 2 : 1;          // 16-byte chunks per fragment per k-step
     constexpr int KS = 4 / FR;                       // k-steps per staged tile
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 16 == 0, "load plan");
@@ -253,14 +265,23 @@ void tile_kernel(const TileArgs a) {
     // left alone, the compiler sinks every fragment read next to its first use.
     constexpr int NM = MB * NB, NR = MB + NB;
     u32x4 fr[2][NR][FR];                              // [0,MB): A fragments, [MB,NR): B fragments
+    // 8-bit operands: fragments are twice as large (64 k per instruction), so the A fragments
+    // get one register set only - block i's next fragment is fetched right behind the last
+    // MFMA of the current k-step that uses it, and is needed again NM - NB MFMAs later.
+    u32x4 fa1[F8 ? MB : 1][FR];
     auto read_frag = [&](int buf, int t, int q) __attribute__((always_inline)) {
         const unsigned char *sA = smem + buf * STAGE + fa_row * ROWB;
         const unsigned char *sB = smem + buf * STAGE + BM * ROWB + fb_row * ROWB;
 #pragma unroll
         for (int c = 0; c < FR; ++c) {
             const int off = fsw[(t & (KS - 1)) * FR + c];
-            fr[t & 1][q][c] = q < MB ? *reinterpret_cast<const u32x4 *>(sA + q * 32 * ROWB + off)
-                                     : *reinterpret_cast<const u32x4 *>(sB + (q - MB) * FB_STEP * ROWB + off);
+            if (q < MB) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(sA + q * 32 * ROWB + off);
+                if constexpr (F8) fa1[q][c] = v;
+                else              fr[t & 1][q][c] = v;
+            } else {
+                fr[t & 1][q][c] = *reinterpret_cast<const u32x4 *>(sB + (q - MB) * FB_STEP * ROWB + off);
+            }
         }
     };
     // prefetch order = order of first use: A0, B0..B(NB-1), A1..A(MB-1)
@@ -284,10 +305,17 @@ void tile_kernel(const TileArgs a) {
                 Mma<bf16_t>::run(lo[m / NB], hi[MB + m % NB], c);
                 Mma<bf16_t>::run(hi[m / NB], lo[MB + m % NB], c);
                 Mma<bf16_t>::run(hi[m / NB], hi[MB + m % NB], c);
+            } else if constexpr (F8) {
+                Mma<InT>::run(fa1[m / NB], fr[t & 1][MB + m % NB], acc[m / NB][m % NB]);
             } else {
                 Mma<InT>::run(fr[t & 1][m / NB][0], fr[t & 1][MB + m % NB][0], acc[m / NB][m % NB]);
             }
-            if (do_read) {
+            if constexpr (F8) {
+                if (do_read) {
+                    if (m < NB) read_frag(rbuf, t + 1, MB + m);                  // B: into the other set
+                    if (m % NB == NB - 1) read_frag(rbuf, t + 1, m / NB);        // A: behind its last use
+                }
+            } else if (do_read) {
 #pragma unroll
                 for (int s = (m * NR) / RSPAN; s < ((m + 1) * NR) / RSPAN && s < NR; ++s) read_frag(rbuf, t + 1, slot(s));
             }

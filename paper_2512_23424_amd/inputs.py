@@ -16,8 +16,8 @@ Generator (counter based, order independent, reproducible on any host):
     normal   : mean + std * sqrt(-2 ln(1 - u(2i))) * cos(2 pi u(2i + 1))   (Box-Muller, cos branch)
 
 Values are produced in float64 and rounded once (round-to-nearest-even) to the storage type
-(fp32, bf16 or fp16).  bf16 tensors are returned as uint16 bit patterns, fp16 tensors as
-numpy float16 arrays.
+(fp32, bf16, fp16 or 8-bit E4M3).  bf16 tensors are returned as uint16 bit patterns, fp16
+tensors as numpy float16 arrays, E4M3 tensors as uint8 bit patterns.
 """
 from __future__ import annotations
 
@@ -30,7 +30,7 @@ import numpy as np
 # activation / row-op / dtype codes: the same integers as the C header's enums.
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF, ACT_SILU, ACT_CLAMP = range(6)
 NORM_NONE, NORM_SOFTMAX, NORM_LAYERNORM, NORM_RMSNORM, NORM_LOGSUMEXP = range(5)
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, F8E4M3 = 0, 1, 2, 3
 
 TENSOR_ID = {"X": 0, "W": 1, "b": 2, "gamma": 3, "beta": 4, "W2": 5, "b2": 6}   # W2, b2: gated form
 
@@ -89,11 +89,42 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def f64_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """float64 -> 8-bit E4M3 pattern (sign, 4 exponent bits with bias 7, 3 mantissa bits; no
+    infinities, largest finite value 448) with one round-to-nearest-even step.  Values are
+    rounded on the grid of their binade - spacing 2^(e-3) for 2^e <= |x| < 2^(e+1), 2^-9 below
+    the smallest normal 2^-6 - and magnitudes that round beyond 448 saturate to 448."""
+    x = np.asarray(x, dtype=np.float64)
+    a = np.abs(x)
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -20)))
+    e = np.clip(e, -6.0, 8.0)
+    q = np.exp2(e - 3.0)                            # grid spacing (exact powers of two)
+    r = np.minimum(np.rint(a / q) * q, 448.0)       # rint rounds halves to even
+    e2 = np.clip(np.floor(np.log2(np.maximum(r, 2.0 ** -20))), -6.0, 8.0)   # rounding may reach the next binade
+    normal = r >= 2.0 ** -6
+    expo = np.where(normal, e2 + 7.0, 0.0)
+    mant = np.where(normal, (r / np.exp2(e2) - 1.0) * 8.0, r * 512.0)
+    bits = (expo.astype(np.uint8) << np.uint8(3)) | mant.astype(np.uint8)
+    return (bits | (np.signbit(x).astype(np.uint8) << np.uint8(7))).astype(np.uint8)
+
+
+def e4m3_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Value of each 8-bit E4M3 pattern (NaN for 0x7F / 0xFF), through a 256-entry table."""
+    codes = np.arange(256)
+    expo, mant = (codes >> 3) & 15, codes & 7
+    mag = np.where(expo == 0, mant * 2.0 ** -9, (1.0 + mant / 8.0) * np.exp2(expo.astype(np.float64) - 7.0))
+    mag = np.where((expo == 15) & (mant == 7), np.nan, mag)
+    table = np.where(codes >= 128, -mag, mag)
+    return table[np.asarray(bits, dtype=np.uint8)]
+
+
 def _store(v64: np.ndarray, dtype: int) -> np.ndarray:
     """One rounding (to nearest even) from float64 to the storage type; fp16 tensors are numpy
     float16 arrays (numpy converts double to half directly, without an fp32 step)."""
     if dtype == BF16:
         return f64_to_bf16_bits(v64)
+    if dtype == F8E4M3:
+        return f64_to_e4m3_bits(v64)
     return v64.astype(np.float16 if dtype == F16 else np.float32)
 
 
@@ -105,7 +136,7 @@ def draw(seed: int, tensor: str, shape: Tuple[int, ...], dist: Tuple, dtype: int
     ("int" draws integers lo..hi inclusive, exactly representable in bf16 and fp32)."""
     key = stream_key(seed, TENSOR_ID[tensor])
     n = int(np.prod(shape))
-    out = np.empty(n, dtype={BF16: np.uint16, F16: np.float16}.get(dtype, np.float32))
+    out = np.empty(n, dtype={BF16: np.uint16, F16: np.float16, F8E4M3: np.uint8}.get(dtype, np.float32))
     for s in range(0, n, _CHUNK):
         c = min(_CHUNK, n - s)
         if dist[0] == "normal":
@@ -194,6 +225,17 @@ WORKLOADS: Dict[str, Workload] = {
 }
 
 
+# Beyond the five: the headline shape with 8-bit E4M3 operands.  Unit-variance X and W are
+# stored as they are (E4M3 keeps 3 mantissa bits at any magnitude within its range) and the
+# per-tensor scale 1/sqrt(K) goes into alpha, as 8-bit pipelines do.
+EXTRA_WORKLOADS: Dict[str, Workload] = {
+    "cfg3_f8": _wl("cfg3_f8", 8192, 4096, 4096, in_dtype=F8E4M3, out_dtype=BF16, act=ACT_SILU,
+                   norm=NORM_RMSNORM, eps=1e-6, alpha=1.0 / 64.0,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 1.0),
+                         "gamma": ("normal", 1.0, 0.1)}),
+}
+
+
 def scaled(w: Workload, **kw) -> Workload:
     """Same chain and distributions at another shape (parity-test sizes)."""
     d = dict(w.__dict__)
@@ -215,11 +257,13 @@ def generate(w: Workload, rows: Optional[np.ndarray] = None) -> Dict[str, Option
 
 
 def as_f64(a: Optional[np.ndarray]) -> Optional[np.ndarray]:
-    """Exact float64 value of stored bits (uint16 arrays are bf16 patterns)."""
+    """Exact float64 value of stored bits (uint16 arrays are bf16 patterns, uint8 arrays E4M3)."""
     if a is None:
         return None
     if a.dtype == np.uint16:
         return bf16_bits_to_f32(a).astype(np.float64)
+    if a.dtype == np.uint8:
+        return e4m3_bits_to_f64(a)
     return a.astype(np.float64)
 
 

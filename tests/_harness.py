@@ -12,9 +12,9 @@ from paper_2512_23424_amd import inputs as I
 
 # max rel err: fp32 / bf16-in fp32-accumulate / fp16-in fp32-accumulate (one fp16 rounding of the
 # output is 2^-11 = 4.9e-4; the gate is the paper's float16 threshold)
-TOL = {I.F32: 1e-4, I.BF16: 2e-2, I.F16: 4e-3}
+TOL = {I.F32: 1e-4, I.BF16: 2e-2, I.F16: 4e-3, I.F8E4M3: 2e-2}
 # the paper's pass rule (fp32 and float16 values from its setup section, Section 4.1)
-TAU = {I.F32: 1e-3, I.BF16: 2e-2, I.F16: 4e-3}
+TAU = {I.F32: 1e-3, I.BF16: 2e-2, I.F16: 4e-3, I.F8E4M3: 2e-2}
 
 
 def to_device(a: Optional[np.ndarray]) -> Optional[torch.Tensor]:
@@ -22,6 +22,8 @@ def to_device(a: Optional[np.ndarray]) -> Optional[torch.Tensor]:
         return None
     if a.dtype == np.uint16:
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    if a.dtype == np.uint8:                     # 8-bit E4M3 bit patterns
+        return torch.from_numpy(a).cuda().view(torch.float8_e4m3fn)
     return torch.from_numpy(a).cuda()
 
 

@@ -58,7 +58,9 @@ def test_argument_errors_are_reported_before_any_launch():
     assert _call(_params(), out=None) == 1
     assert _call(_params(), act=6) == 2 and _call(_params(), act=-1) == 2
     assert _call(_params(), norm=5) == 2
-    assert _call(_params(in_dtype=3)) == 2 and _call(_params(out_dtype=-1)) == 2
+    assert _call(_params(in_dtype=4)) == 2 and _call(_params(out_dtype=-1)) == 2
+    assert _call(_params(in_dtype=3, out_dtype=3)) == 4       # E4M3 is an operand type only
+    assert _call(_params(in_dtype=3, out_dtype=2)) == 4       # ... that goes with fp32 or bf16 results
     assert _call(_params(in_dtype=2, out_dtype=1)) == 4       # fp16 operands with a bf16 result
     assert _call(_params(in_dtype=1, out_dtype=2)) == 4
     assert _call(_params(M=0)) == 3 and _call(_params(K=-8)) == 3 and _call(_params(batch=0)) == 3

@@ -88,3 +88,31 @@ def test_fp16_storage_rounds_once_to_nearest_even():
     t = I.generate(w)
     assert t["X"].dtype == np.float16 and t["W"].dtype == np.float16
     assert np.array_equal(I.as_f64(t["X"]), t["X"].astype(np.float64))
+
+
+def test_e4m3_storage_patterns_and_rounding():
+    """8-bit E4M3 (bias 7, 3 mantissa bits, no infinities): hand-made patterns, ties to even,
+    subnormals, saturation at 448, and the whole code table against torch's CPU conversion of
+    the same format (float8_e4m3fn), a routine independent of this module."""
+    import torch
+    enc, dec = I.f64_to_e4m3_bits, I.e4m3_bits_to_f64
+    val = dec(np.arange(256, dtype=np.uint8))
+    assert val[0x38] == 1.0 and val[0x7E] == 448.0 and val[0x01] == 2.0 ** -9 and val[0x08] == 2.0 ** -6
+    assert val[0xB8] == -1.0 and np.isnan(val[0x7F]) and np.isnan(val[0xFF]) and val[0x80] == 0.0
+    tb = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.nan_to_num(val, nan=7e9), np.nan_to_num(tb, nan=7e9))
+    # grid spacing is 1/8 in [1, 2): 1.0625 is a tie between 1.0 (even) and 1.125; 1.1875 between 1.125 and 1.25 (even)
+    assert list(enc(np.array([1.0625, 1.1875, 1.07, -1.0625]))) == [0x38, 0x3A, 0x39, 0xB8]
+    # below the smallest normal the grid is 2^-9; half of it is a tie with zero (even)
+    assert list(enc(np.array([2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -10, 0.9 * 2.0 ** -6, 0.0]))) == [0x01, 0x00, 0x02, 0x07, 0x00]
+    # rounding up across a binade and saturation
+    assert list(enc(np.array([1.97, 15.9, 448.0, 1e6, -1e6]))) == [0x40, 0x58, 0x7E, 0x7E, 0xFE]
+    # every finite pattern survives a round trip; random values agree with torch below the saturation range
+    finite = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    assert np.array_equal(enc(dec(finite)) & 0x7F, finite & 0x7F)
+    rng = np.random.default_rng(0)
+    v = np.concatenate([rng.normal(0, 1, 5000), rng.normal(0, 0.01, 5000), rng.uniform(-440, 440, 2000)]).astype(np.float32)
+    ref = torch.from_numpy(v).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(enc(v.astype(np.float64)), ref)
+    x = I.draw(0, "X", (64, 64), ("normal", 0.0, 1.0), I.F8E4M3)
+    assert x.dtype == np.uint8 and np.array_equal(enc(I.as_f64(x)), x)
