@@ -27,7 +27,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}      # dense MFMA peaks of MI355X
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3, "f8": 5000.0}      # dense MFMA peaks of MI355X
 PEAK_HBM_GBS = 8000.0
 # which roof binds each workload's dominant kernel
 BOUND = {"cfg1": "mfma", "cfg2": "mfma", "cfg3": "mfma", "cfg4": "mfma", "cfg5": "hbm"}
@@ -117,6 +117,53 @@ def gated_ffn(torch, B, I, timed, log):
          "frac_mfma": round(flops / (tf_ * 1e-3) / 1e12 / PEAK_TFLOPS["bf16"], 4),
          "speedup_vs_unfused": round(tu_ / tf_, 3), "parity_err": float(f"{err:.3e}")}
     log(f"[bench] gated: {json.dumps(r)}")
+    return r
+
+
+def fp8_operands(torch, B, I, timed, log):
+    """cfg3's chain and shape with 8-bit E4M3 operands (bf16 out): fused against the unfused
+    sequence of the same library, parity of sampled rows against the oracle on the same bytes."""
+    from oracle import compare as C
+    from oracle import oracle as O
+    w = I.EXTRA_WORKLOADS["cfg3_f8"]
+    log("[bench] generating the 8-bit workload ...")
+    t = I.generate(w)
+    W = torch.from_numpy(t["W"]).cuda().view(torch.float8_e4m3fn)
+    X = torch.from_numpy(t["X"]).cuda().view(torch.float8_e4m3fn)
+    gamma = torch.from_numpy(t["gamma"]).cuda()
+    sets = [(X, torch.empty(w.M, w.N, dtype=torch.bfloat16, device="cuda")),
+            (X.clone(), torch.empty(w.M, w.N, dtype=torch.bfloat16, device="cuda"))]
+    ps = []
+    for Xs, out in sets:
+        p = B.make_params(Xs, W, out, alpha=w.alpha, eps=w.eps, gamma=gamma)
+        n = max(B.fge_workspace_bytes(True, w.act, w.norm, p), B.fge_workspace_bytes(False, w.act, w.norm, p), 16)
+        ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), n
+        ps.append((p, ws))
+
+    def fused(i):
+        B.fused_gemm_epilogue(sets[i][0], W, None, w.act, w.norm, ps[i][0], sets[i][1])
+
+    def unfused(i):
+        B.unfused_gemm_epilogue(sets[i][0], W, None, w.act, w.norm, ps[i][0], sets[i][1])
+    rows = np.unique(np.concatenate([[0, w.M - 1], np.random.default_rng(5).integers(0, w.M, 6)]))
+    sets[0][1].fill_(float("nan"))
+    fused(0)
+    torch.cuda.synchronize()
+    got = sets[0][1][torch.from_numpy(rows).cuda()].to(torch.float64).cpu().numpy()
+    ref, _ = O.chain(I.as_f64(t["X"][rows]), I.as_f64(t["W"]), None, I.as_f64(t["gamma"]), None, alpha=w.alpha,
+                     act=w.act, norm=w.norm, eps=w.eps)
+    err = C.max_rel_err(got, ref)
+    if not (err <= 2e-2):
+        raise SystemExit(f"bench.py: 8-bit result off the oracle: {err:.3e}")
+    tf_ = timed(fused, 30, 10)
+    tu_ = timed(unfused, 15, 3)
+    r = {"workload": "cfg3's chain, E4M3 operands, bf16 out, M=8192 K=4096 N=4096",
+         "tile": B.fge_tile_name(True, w.act, w.norm, ps[0][0]), "ms_fused": round(tf_, 5),
+         "ms_unfused": round(tu_, 5), "tflops": round(w.flops / (tf_ * 1e-3) / 1e12, 2),
+         "frac_mfma": round(w.flops / (tf_ * 1e-3) / 1e12 / PEAK_TFLOPS["f8"], 4),
+         "speedup_vs_unfused": round(tu_ / tf_, 3), "parity_err": float(f"{err:.3e}")}
+    log(f"[bench] 8-bit operands: {json.dumps(r)}")
     return r
 
 
@@ -371,6 +418,7 @@ def main() -> int:
     gated = None
     if not args.no_others:
         gated = gated_ffn(torch, B, I, timed, log)
+    f8 = None if args.no_others else fp8_operands(torch, B, I, timed, log)
     geo = math.exp(sum(math.log(s) for s in sp) / len(sp)) if sp else None
 
     line = {
@@ -382,7 +430,7 @@ def main() -> int:
                                f"{'bf16 in/out' if dt == 'bf16' else 'fp32'}, fp32 accumulate, "
                                f"act={w.act} rowop={w.norm} (codes of include/fge.h)",
                    "tile": head["tile"], "speedup_vs_unfused": head.get("speedup_vs_unfused")},
-        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated,
+        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated, "fp8_operands": f8,
         "speedup_geomean": None if geo is None else round(geo, 3),
         "paper_context": "paper reports 1.46x geomean over PyTorch eager (Triton, Ascend 910B, "
                          "KernelBench L1); no number for this chain",

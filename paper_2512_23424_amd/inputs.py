@@ -185,7 +185,7 @@ class Workload:
     @property
     def algorithmic_bytes(self) -> int:
         """Every operand and result moved exactly once."""
-        isz = 4 if self.in_dtype == F32 else 2
+        isz = {F32: 4, F8E4M3: 1}.get(self.in_dtype, 2)
         osz = 4 if self.out_dtype == F32 else 2
         vecs = sum(1 for t in ("b", "gamma", "beta") if self.dist.get(t) is not None)
         aux = self.rows * 4 if self.norm == NORM_LOGSUMEXP else 0

@@ -23,7 +23,7 @@ from . import binding as B
 from . import inputs as I
 
 TILES = {"64x64": 0, "64x512": 1, "128x128": 2, "256x256": 3, "narrow_k": 4, "64x128": 5}
-_TOL = {I.F32: 1e-4, I.BF16: 2e-2, I.F16: 4e-3}
+_TOL = {I.F32: 1e-4, I.BF16: 2e-2, I.F16: 4e-3, I.F8E4M3: 2e-2}
 
 
 def flag_tile(tile: int) -> int:
@@ -97,12 +97,14 @@ def _upload(a):
         return None
     if a.dtype == np.uint16:
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    if a.dtype == np.uint8:
+        return torch.from_numpy(a).cuda().view(torch.float8_e4m3fn)
     return torch.from_numpy(a).cuda()
 
 
 def main(argv: List[str]) -> int:
     name = argv[1] if len(argv) > 1 else "cfg2"
-    w = I.WORKLOADS[name]
+    w = I.WORKLOADS[name] if name in I.WORKLOADS else I.EXTRA_WORKLOADS[name]
     t = {k: _upload(v) for k, v in I.generate(w).items()}
     X = t["X"].view(w.batch, w.M, w.K) if w.batch > 1 else t["X"]
     dt = {I.BF16: torch.bfloat16, I.F16: torch.float16}.get(w.out_dtype, torch.float32)
