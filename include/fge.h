@@ -165,7 +165,7 @@ size_t fge_fault_word_offset(int act, int norm, const fge_params *p);
  *
  * W1 and W2 are both N x K with row stride ldw; b1, b2 fp32 of length N or NULL.  Everything
  * else is as for fused_gemm_epilogue.  The fused call runs one tile kernel that forms both
- * products from one staged X panel and applies the gate to the accumulators, for bf16 / fp16
+ * products from one staged X panel and applies the gate to the accumulators, for bf16 / fp16 / E4M3
  * operands in shapes the fast kernels take; every other case (fp32 operands, odd extents) runs
  * the unfused sequence: two GEMMs into the workspace (fp32 operands always on the fp32 matrix
  * instruction here: the gate multiplies two products and their errors), the gate as an

@@ -196,10 +196,8 @@ size_t fused_workspace(const fge_params *p, int norm) {
     return a > b ? a : b;
 }
 
-// The gated tile kernel takes 16-bit operands in shapes the vectorised kernels take.
-bool gated_fast(const fge_params *p, int norm) {
-    return (p->in_dtype == FGE_BF16 || p->in_dtype == FGE_F16) && vectorisable(p, norm, true);
-}
+// The gated tile kernel takes 16-bit and 8-bit operands in shapes the vectorised kernels take.
+bool gated_fast(const fge_params *p, int norm) { return p->in_dtype != FGE_F32 && vectorisable(p, norm, true); }
 
 size_t gated_workspace(const fge_params *p, int norm) {
     const Plan p1 = make_plan(p, norm, false, TILE_GATED), p2 = make_plan(p, norm, true, TILE_GATED);
@@ -519,8 +517,9 @@ int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, con
     a.W2 = W2; a.b2 = b2;
     const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
                     a.coop ? 1u : (unsigned)pl.pr.batch);
-    rc = hip_status(p->in_dtype == FGE_BF16 ? launch_gated_bf16(p->out_dtype, grid, s, a)
-                                            : launch_gated_f16(p->out_dtype, grid, s, a));
+    rc = hip_status(p->in_dtype == FGE_BF16  ? launch_gated_bf16(p->out_dtype, grid, s, a)
+                    : p->in_dtype == FGE_F16 ? launch_gated_f16(p->out_dtype, grid, s, a)
+                                             : launch_gated_f8(p->out_dtype, grid, s, a));
     if (rc || !pl.needs_finish) return rc;
     return launch_finish(pl, act, norm, p, out, s);
 }

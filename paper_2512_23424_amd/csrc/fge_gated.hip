@@ -1,4 +1,4 @@
-// Gated tile-kernel instantiations (bf16 and fp16 operands).
+// Gated tile-kernel instantiations (bf16, fp16 and 8-bit operands).
 #include "fge_launch.h"
 namespace fge {
 hipError_t launch_gated_bf16(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
@@ -6,5 +6,8 @@ hipError_t launch_gated_bf16(int out_dtype, dim3 grid, hipStream_t s, const Tile
 }
 hipError_t launch_gated_f16(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
     return launch_gated_any<f16_t>(out_dtype, grid, s, a);
+}
+hipError_t launch_gated_f8(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
+    return launch_gated_any<f8_t>(out_dtype, grid, s, a);
 }
 }  // namespace fge

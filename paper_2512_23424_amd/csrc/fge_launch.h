@@ -132,7 +132,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     return hipGetLastError();
 }
 
-// The gated tile kernel (16-bit operands only): ordinary or cooperative launch.
+// The gated tile kernel (16-bit and 8-bit operands): ordinary or cooperative launch.
 template <typename InT>
 inline hipError_t launch_gated_any(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
     typedef typename NarrowOut<InT>::type NarrowT;
@@ -152,6 +152,7 @@ inline hipError_t launch_gated_any(int out_dtype, dim3 grid, hipStream_t s, cons
 }
 hipError_t launch_gated_bf16(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_gated_f16(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
+hipError_t launch_gated_f8(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 
 // Whether launch_tile_any has a cooperative kernel for this tile and operand type.
 inline bool tile_has_coop(int tile, int in_dtype) {

@@ -112,7 +112,7 @@ void tile_kernel(const TileArgs a) {
     // holds the BN/2 rows of W1 and, below them, the same rows of W2; each wave's column blocks
     // are 32 columns of the first product and the same 32 columns of the second, so the gate is
     // applied register by register before the shared epilogue sees a tile of BN/2 columns.
-    static_assert(!GATED || (sizeof(InT) == 2 && BN / WAVES_N == 64 && !SPLIT), "gated form: two 32-column blocks per wave");
+    static_assert(!GATED || (sizeof(InT) <= 2 && BN / WAVES_N == 64 && !SPLIT), "gated form: two 32-column blocks per wave");
     constexpr int BNO = GATED ? BN / 2 : BN;         // output columns per tile
     constexpr int NT = 64 * WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
