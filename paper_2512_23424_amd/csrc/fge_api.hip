@@ -61,7 +61,8 @@ bool forced_tile_ok(const fge_params *p) {
     const bool f32 = p->in_dtype == FGE_F32;
     switch (t) {
     case TILE_64x64: case TILE_64x512: return true;
-    case TILE_128x128: case TILE_256x256: return !f32;
+    case TILE_128x128: return !f32 || !(p->flags & FGE_FLAG_IEEE_FP32);   // fp32: split product only
+    case TILE_256x256: return !f32;
     case TILE_64x128: return f32;
     case TILE_PANEL:
         return f32 && !(p->flags & FGE_FLAG_IEEE_FP32) && p->K <= 64 && p->N <= 512 &&
@@ -129,8 +130,11 @@ int pick_tile(const Problem &pr, int in_dtype, int /*norm*/, bool ieee_fp32) {
         // bound by the output stream; the kernel for it exists with the split product only
         if (!ieee_fp32 && pr.K <= 64 && pr.N > 256 && pr.N <= 512 && pr.batch == 1 && pr.M >= PANEL_MIN_ROWS)
             return TILE_PANEL;
-        // very large problems: the wide tile halves the operand traffic per flop
-        if (fits(TILE_64x512) && pr.K >= 1024 && count(TILE_64x512) >= 2 * NUM_CU) return TILE_64x512;
+        // large problems: 128x128 tiles (split product only), two per CU - twice the MFMA work
+        // per staged and split operand value of the 64x128 tile
+        if (!ieee_fp32 && fits(TILE_128x128) && count(TILE_128x128) >= 2 * NUM_CU) return TILE_128x128;
+        // fp32 instruction, very large problems: the wide tile halves the operand traffic per flop
+        if (ieee_fp32 && fits(TILE_64x512) && pr.K >= 1024 && count(TILE_64x512) >= 2 * NUM_CU) return TILE_64x512;
         // otherwise 64x128 tiles, two or three of which share a CU so that one's epilogue hides
         // behind another's MFMAs
         // (given at least two per CU; with fewer, 64x64 tiles fill the chip better)

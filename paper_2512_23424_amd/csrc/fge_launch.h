@@ -16,7 +16,7 @@ inline const TileInfo &tile_info(int id) {
     static const TileInfo t[TILE_COUNT] = {
         {64, 64, 256, 2, 0, "64x64_w2x2", "64x64_w2x2_splitbf16"},
         {64, 512, 256, 4, 0, "64x512_w1x4", "64x512_w1x4_splitbf16"},
-        {128, 128, 256, 2, 2, "128x128_w2x2", nullptr},
+        {128, 128, 256, 2, 2, "128x128_w2x2", "128x128_w2x2_splitbf16"},
         {256, 256, 512, 4, 1, "256x256_w2x4", nullptr},
         // persistent narrow-K kernel, fp32 operands, always the split product
         {64, 512, 512, 8, 0, "panel64x512_w1x8_splitbf16", "panel64x512_w1x8_splitbf16"},
@@ -67,7 +67,7 @@ inline int resident_workgroups(const void *kernel, int threads) {
 // Which tiles exist for which operand type (tile selection on the host must agree):
 //   bf16, fp16, fp8: 64x64, 64x512, 128x128 (+ cooperative), 256x256 (+ cooperative)
 //   fp32: 64x64, 64x512, 64x128 (+ cooperative) - once with the fp32 matrix instruction and once
-//         with the split-bf16 product (SPLIT)
+//         with the split-bf16 product (SPLIT); 128x128 (+ cooperative) with the split product only
 // The 16-bit output type that goes with an operand type (the other output type is fp32).
 template <typename InT> struct NarrowOut { typedef bf16_t type; };
 template <> struct NarrowOut<f16_t> { typedef f16_t type; };
@@ -104,7 +104,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     case TILE_64x64:   FGE_LAUNCH(64, 64, 2, 2); break;
     case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4); break;
     case TILE_128x128:
-        if constexpr (BF) {
+        if constexpr (BF || SPLIT) {
             if (a.coop) FGE_LAUNCH_COOP(128, 128, 2, 2);
             else        FGE_LAUNCH(128, 128, 2, 2);
             break;
@@ -157,7 +157,8 @@ hipError_t launch_gated_f8(int out_dtype, dim3 grid, hipStream_t s, const TileAr
 // Whether launch_tile_any has a cooperative kernel for this tile and operand type.
 inline bool tile_has_coop(int tile, int in_dtype) {
     if (tile == TILE_GATED) return true;
-    return in_dtype != FGE_F32 ? (tile == TILE_128x128 || tile == TILE_256x256) : tile == TILE_64x128;
+    return in_dtype != FGE_F32 ? (tile == TILE_128x128 || tile == TILE_256x256)
+                               : (tile == TILE_64x128 || tile == TILE_128x128);
 }
 
 }  // namespace fge

@@ -123,7 +123,7 @@ void tile_kernel(const TileArgs a) {
     constexpr int A_LD = BM * 8 / NT, B_LD = BN * 8 / NT;
     constexpr int RSTEP = NT / 8;                    // rows between a thread's successive chunks
     constexpr bool F8 = sizeof(InT) == 1;            // 64 k per matrix instruction
-    constexpr int FR = SPLIT || F8 ? 2 : 1;          // 16-byte chunks per fragment per k-step
+    constexpr int FR = SPLIT || F8 ? 2 : 1;          // 16-byte chunks per fragment per k-step (split: high and low part)
     constexpr int KS = 4 / FR;                       // k-steps per staged tile
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 16 == 0, "load plan");
@@ -257,8 +257,90 @@ void tile_kernel(const TileArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    if constexpr (SPLIT) {
+    // ---------------- mainloop, split product
+    // Every operand value feeds WAVES_N (X) or WAVES_M (W) waves, so the split into bf16 parts is
+    // done once per workgroup on the way into LDS instead of once per wave on the way out: thread
+    // (row, kg) = (tid / 4, tid % 4) fetches the 8 values k = 8kg .. 8kg+7 of its panel rows into
+    // registers while the previous K tile is multiplied, splits them and parks the high and the
+    // low parts as 16-byte chunks 2kg and 2kg+1 of the 128-byte panel row (same swizzle as the
+    // other kernels' panels).  One barrier per K tile; values past K are zero.
+    constexpr int A_IT = BM * 4 / NT, B_IT = BN * 4 / NT, NI = A_IT + B_IT;
+    static_assert((BM * 4) % NT == 0 && (BN * 4) % NT == 0 && (NT / 4) % 16 == 0, "split staging plan");
+    const int it_row = tid >> 2, it_kg = tid & 3;
+    const float *gS[NI];
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i)
+        gS[i] = X + (int64_t)min(m0 + it_row + i * (NT / 4), a.M - 1) * a.ldx + it_kg * 8;
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i)
+        gS[A_IT + i] = W + (int64_t)min(n0 + it_row + i * (NT / 4), a.N - 1) * a.ldw + it_kg * 8;
+    u32x4 sreg[NI][2];
+    auto stage_load = [&](int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const bool kok = k0 + it_kg * 8 + 4 * c < a.K;        // K is a multiple of 4: chunks are whole
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                sreg[i][c] = u32x4{0u, 0u, 0u, 0u};
+                if (kok) sreg[i][c] = *reinterpret_cast<const u32x4 *>(gS[i] + k0 + 4 * c);
+            }
+        }
+    };
+    const int st_off = it_row * ROWB, st_hi = ((2 * it_kg) ^ swz(it_row)) << 4, st_lo = ((2 * it_kg + 1) ^ swz(it_row)) << 4;
+    auto stage_store = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            u32x4 hi, lo;
+            split_bf16x8(sreg[i][0], sreg[i][1], hi, lo);
+            unsigned char *row = smem + buf * STAGE + st_off +
+                                 (i < A_IT ? i * (NT / 4) : BM + (i - A_IT) * (NT / 4)) * ROWB;
+            *reinterpret_cast<u32x4 *>(row + st_hi) = hi;
+            *reinterpret_cast<u32x4 *>(row + st_lo) = lo;
+        }
+    };
+    // fragment (k-step t of the tile's two): lanes 0-31 take k-group 2t, lanes 32-63 k-group 2t+1
+    int fq[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) fq[t][c] = ((2 * (2 * t + h) + c) ^ swz(l32)) << 4;
+    constexpr int NM = MB * NB, NR = MB + NB;
+    u32x4 fh[2][NR], fl[2][NR];                       // [register set][A fragments, then B fragments]
+    auto read_split = [&](int buf, int t) __attribute__((always_inline)) {
+        const unsigned char *sA = smem + buf * STAGE + fa_row * ROWB;
+        const unsigned char *sB = smem + buf * STAGE + BM * ROWB + fb_row * ROWB;
+#pragma unroll
+        for (int q = 0; q < NR; ++q) {
+            const unsigned char *r = q < MB ? sA + q * 32 * ROWB : sB + (q - MB) * 32 * ROWB;
+            fh[t & 1][q] = *reinterpret_cast<const u32x4 *>(r + fq[t][0]);
+            fl[t & 1][q] = *reinterpret_cast<const u32x4 *>(r + fq[t][1]);
+        }
+    };
+    const int KT = (a.K + BK - 1) / BK;
+    stage_load(0);
+    stage_store(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < KT) stage_load((kt + 1) * BK);
+        read_split(buf, 0);
+        static_for<0, 2>([&]<int t>() __attribute__((always_inline)) {
+            if constexpr (t == 0) read_split(buf, 1);
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {            // small terms first
+                floatx16 &c = acc[m / NB][m % NB];
+                Mma<bf16_t>::run(fl[t][m / NB], fh[t][MB + m % NB], c);
+                Mma<bf16_t>::run(fh[t][m / NB], fl[t][MB + m % NB], c);
+                Mma<bf16_t>::run(fh[t][m / NB], fh[t][MB + m % NB], c);
+            }
+        });
+        if (kt + 1 < KT) stage_store(buf ^ 1);
+        __syncthreads();                              // tile kt+1 is parked; reads of tile kt are over
+    }
+    } else {
     // ---------------- mainloop
-    // Per staged tile: KS k-steps of NM MFMAs (3 NM with split operands).  Fragments of the next k-step are read from LDS
+    // Per staged tile: KS k-steps of NM MFMAs.  Fragments of the next k-step are read from LDS
     // behind the first MFMAs of the current one (two register sets).  The single barrier of an
     // iteration sits before the last k-step, and that k-step already prefetches the next tile's
     // first fragments, so no LDS or barrier latency is exposed.  sched_barrier pins this order:
@@ -293,19 +375,9 @@ void tile_kernel(const TileArgs a) {
     // wave's in-order issue, and with it its MFMAs, on the address unit
     auto kstep = [&]<int DMA_PART>(int t, bool do_read, int rbuf, bool do_dma, int dbuf, int dk0) __attribute__((always_inline)) {
         constexpr int HALF = NS / 2;
-        u32x4 hi[SPLIT ? NR : 1], lo[SPLIT ? NR : 1];
-        if constexpr (SPLIT) {
-#pragma unroll
-            for (int q = 0; q < NR; ++q) split_bf16x8(fr[t & 1][q][0], fr[t & 1][q][1], hi[q], lo[q]);
-        }
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
-            if constexpr (SPLIT) {                    // small terms first
-                floatx16 &c = acc[m / NB][m % NB];
-                Mma<bf16_t>::run(lo[m / NB], hi[MB + m % NB], c);
-                Mma<bf16_t>::run(hi[m / NB], lo[MB + m % NB], c);
-                Mma<bf16_t>::run(hi[m / NB], hi[MB + m % NB], c);
-            } else if constexpr (F8) {
+            if constexpr (F8) {
                 Mma<InT>::run(fa1[m / NB], fr[t & 1][MB + m % NB], acc[m / NB][m % NB]);
             } else {
                 Mma<InT>::run(fr[t & 1][m / NB][0], fr[t & 1][MB + m % NB][0], acc[m / NB][m % NB]);
@@ -372,6 +444,7 @@ void tile_kernel(const TileArgs a) {
     }
     compute_last(kt & 1);
     if constexpr (WAVES_M * WAVES_N > 1) __syncthreads();
+    }
 
     // ---------------- epilogue.  The store patches live in the panel memory, free once the
     // mainloop's last fragment reads are behind the barrier above.  The 64-row tiles are the

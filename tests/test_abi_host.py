@@ -111,9 +111,12 @@ def test_status_strings_and_tile_names():
     assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512, flags=B.FLAG_IEEE_FP32)) == "64x128_w2x2"
     assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512)) == "panel64x512_w1x8_splitbf16"
     assert B.fge_tile_name(True, 5, 4, _params(M=1000, N=512, ldo=512)) == "64x64_w2x2_splitbf16"     # few tiles
-    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=256, ldo=256)) == "64x128_w2x2_splitbf16"  # row too narrow for it
+    assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=256, ldo=256)) == "128x128_w2x2_splitbf16"  # row too narrow for it
+    assert B.fge_tile_name(True, 5, 4, _params(M=16384, N=256, ldo=256)) == "64x128_w2x2_splitbf16"    # fewer than two 128x128 tiles per CU
     huge = _params(M=4096, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096)
-    assert B.fge_tile_name(True, 2, 2, huge) == "64x512_w1x4_splitbf16"
+    assert B.fge_tile_name(True, 2, 2, huge) == "128x128_w2x2_splitbf16"
+    huge.flags = B.FLAG_IEEE_FP32
+    assert B.fge_tile_name(True, 2, 2, huge) == "64x512_w1x4"
     big = _params(M=8192, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, in_dtype=1, out_dtype=1)
     assert B.fge_tile_name(True, 4, 3, big) == "256x256_w2x4"
     assert B.fge_fused_needs_finish(4, 3, big) is False      # the tiles finish their rows themselves
@@ -135,8 +138,9 @@ def test_forced_tile_configurations():
     assert B.fge_tile_name(True, 2, 2, _params(**f32, flags=tile(0))) == "64x64_w2x2_splitbf16"
     assert B.fge_tile_name(True, 2, 2, _params(**f32, flags=tile(1))) == "64x512_w1x4_splitbf16"
     assert B.fge_tile_name(True, 2, 2, _params(**f32, flags=tile(5) | B.FLAG_IEEE_FP32)) == "64x128_w2x2"
-    for t in (2, 3):                                           # 128x128, 256x256: 16-bit operands only
-        assert _call(_params(**f32, flags=tile(t))) == 4
+    assert B.fge_tile_name(True, 2, 2, _params(**f32, flags=tile(2))) == "128x128_w2x2_splitbf16"
+    assert _call(_params(**f32, flags=tile(2) | B.FLAG_IEEE_FP32)) == 4   # 128x128 with fp32 operands: split product only
+    assert _call(_params(**f32, flags=tile(3))) == 4           # 256x256: 16-bit and 8-bit operands only
     assert _call(_params(**f32, flags=tile(4))) == 4           # narrow-K kernel needs K <= 64, N <= 512
     assert _call(_params(**f32, flags=tile(6))) == 4 and _call(_params(**f32, flags=tile(14))) == 4
     b16 = dict(f32, in_dtype=1, out_dtype=1)

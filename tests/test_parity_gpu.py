@@ -110,7 +110,8 @@ def test_narrow_k_persistent_kernel(norm, shape):
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
 @pytest.mark.parametrize("case", [(I.BF16, 4100, 136, 4000, "256x256_w2x4"), (I.BF16, 2050, 200, 2040, "128x128_w2x2"),
                                   (I.F16, 4100, 136, 4000, "256x256_w2x4"), (I.F16, 2050, 200, 2040, "128x128_w2x2"),
-                                  (I.F32, 2060, 100, 2040, "64x128_w2x2_splitbf16")])
+                                  (I.F32, 2060, 100, 2040, "64x128_w2x2_splitbf16"),
+                                  (I.F32, 4100, 100, 2040, "128x128_w2x2_splitbf16")])
 def test_split_rows_one_kernel_and_two_pass(norm, case):
     """Rows split over column tiles, large enough for the one-kernel form (the tiles of a row
     block exchange statistics and finish their rows themselves): ragged M / N / K, a partial
