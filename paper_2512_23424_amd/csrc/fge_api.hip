@@ -130,9 +130,10 @@ int pick_tile(const Problem &pr, int in_dtype, int /*norm*/, bool ieee_fp32) {
         // bound by the output stream; the kernel for it exists with the split product only
         if (!ieee_fp32 && pr.K <= 64 && pr.N > 256 && pr.N <= 512 && pr.batch == 1 && pr.M >= PANEL_MIN_ROWS)
             return TILE_PANEL;
-        // large problems: 128x128 tiles (split product only), two per CU - twice the MFMA work
-        // per staged and split operand value of the 64x128 tile
-        if (!ieee_fp32 && fits(TILE_128x128) && count(TILE_128x128) >= 2 * NUM_CU) return TILE_128x128;
+        // 128x128 tiles (split product only) once there is one for every CU: a third less operand
+        // traffic from the L2s than 64x128 tiles - fp32 operands make the staging, not the MFMAs,
+        // the bound of these kernels
+        if (!ieee_fp32 && fits(TILE_128x128) && count(TILE_128x128) >= NUM_CU) return TILE_128x128;
         // fp32 instruction, very large problems: the wide tile halves the operand traffic per flop
         if (ieee_fp32 && fits(TILE_64x512) && pr.K >= 1024 && count(TILE_64x512) >= 2 * NUM_CU) return TILE_64x512;
         // otherwise 64x128 tiles, two or three of which share a CU so that one's epilogue hides

@@ -276,13 +276,14 @@ void tile_kernel(const TileArgs a) {
     for (int i = 0; i < B_IT; ++i)
         gS[A_IT + i] = W + (int64_t)min(n0 + it_row + i * (NT / 4), a.N - 1) * a.ldw + it_kg * 8;
     u32x4 sreg[NI][2];
-    auto stage_load = [&](int k0) __attribute__((always_inline)) {
+    // GUARD: the tile may reach past K (K is a multiple of 4: chunks are whole)
+    auto stage_load = [&]<bool GUARD>(int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            const bool kok = k0 + it_kg * 8 + 4 * c < a.K;        // K is a multiple of 4: chunks are whole
+            const bool kok = !GUARD || k0 + it_kg * 8 + 4 * c < a.K;
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
-                sreg[i][c] = u32x4{0u, 0u, 0u, 0u};
+                if constexpr (GUARD) sreg[i][c] = u32x4{0u, 0u, 0u, 0u};
                 if (kok) sreg[i][c] = *reinterpret_cast<const u32x4 *>(gS[i] + k0 + 4 * c);
             }
         }
@@ -317,16 +318,19 @@ void tile_kernel(const TileArgs a) {
             fl[t & 1][q] = *reinterpret_cast<const u32x4 *>(r + fq[t][1]);
         }
     };
-    const int KT = (a.K + BK - 1) / BK;
-    stage_load(0);
-    stage_store(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) stage_load((kt + 1) * BK);
+    // One K tile: both k-steps' fragments, the MFMAs of k-step 0, then - STORE - the split and
+    // parking of the next tile spread between the MFMAs of k-step 1 (a wave issues in order; left
+    // in one piece, the vector-ALU work of the split would run after the last MFMA instead of
+    // under them).
+    constexpr int ST_VALU = 26 * NI;                  // vector-ALU instructions of one stage_store, about
+    auto compute = [&]<bool STORE>(int buf) __attribute__((always_inline)) {
         read_split(buf, 0);
+        read_split(buf, 1);
         static_for<0, 2>([&]<int t>() __attribute__((always_inline)) {
-            if constexpr (t == 0) read_split(buf, 1);
+            if constexpr (t == 1) {
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (STORE) stage_store(buf ^ 1);
+            }
 #pragma unroll
             for (int m = 0; m < NM; ++m) {            // small terms first
                 floatx16 &c = acc[m / NB][m % NB];
@@ -334,10 +338,42 @@ void tile_kernel(const TileArgs a) {
                 Mma<bf16_t>::run(fh[t][m / NB], fl[t][MB + m % NB], c);
                 Mma<bf16_t>::run(fh[t][m / NB], fh[t][MB + m % NB], c);
             }
+            if constexpr (t == 1 && STORE) {
+#pragma unroll
+                for (int g = 0; g < 3 * NM; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                              // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, (ST_VALU + 3 * NM - 1) / (3 * NM), 0);   // its share of the split
+                }
+                __builtin_amdgcn_sched_group_barrier(0x200, 2 * NI, 0);                             // the parked chunks
+                __builtin_amdgcn_sched_barrier(0);
+            }
         });
-        if (kt + 1 < KT) stage_store(buf ^ 1);
+    };
+    // At the top of iteration kt the staging registers hold tile kt+1 (fetched during iteration
+    // kt-1, so a whole iteration hides the latency); it is parked during iteration kt, and tile
+    // kt+2 is fetched into the same registers right behind.
+    const int KT = (a.K + BK - 1) / BK, KF = a.K / BK;    // tiles; tiles that lie inside K
+    stage_load.template operator()<true>(0);
+    stage_store(0);
+    if (KT > 1) stage_load.template operator()<true>(BK);
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 2 < KF; ++kt) {                       // tile kt+2 lies inside K
+        compute.template operator()<true>(kt & 1);
+        stage_load.template operator()<false>((kt + 2) * BK);
         __syncthreads();                              // tile kt+1 is parked; reads of tile kt are over
     }
+    for (; kt + 2 < KT; ++kt) {                       // tile kt+2 is the partial one
+        compute.template operator()<true>(kt & 1);
+        stage_load.template operator()<true>((kt + 2) * BK);
+        __syncthreads();
+    }
+    for (; kt + 1 < KT; ++kt) {                       // nothing left to fetch
+        compute.template operator()<true>(kt & 1);
+        __syncthreads();
+    }
+    compute.template operator()<false>(kt & 1);
+    __syncthreads();                                  // the epilogue reuses the panel memory
     } else {
     // ---------------- mainloop
     // Per staged tile: KS k-steps of NM MFMAs.  Fragments of the next k-step are read from LDS

@@ -112,7 +112,7 @@ def test_status_strings_and_tile_names():
     assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=512, ldo=512)) == "panel64x512_w1x8_splitbf16"
     assert B.fge_tile_name(True, 5, 4, _params(M=1000, N=512, ldo=512)) == "64x64_w2x2_splitbf16"     # few tiles
     assert B.fge_tile_name(True, 5, 4, _params(M=262144, N=256, ldo=256)) == "128x128_w2x2_splitbf16"  # row too narrow for it
-    assert B.fge_tile_name(True, 5, 4, _params(M=16384, N=256, ldo=256)) == "64x128_w2x2_splitbf16"    # fewer than two 128x128 tiles per CU
+    assert B.fge_tile_name(True, 5, 4, _params(M=8192, N=256, ldo=256)) == "64x64_w2x2_splitbf16"      # fewer 128x128 tiles than CUs
     huge = _params(M=4096, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096)
     assert B.fge_tile_name(True, 2, 2, huge) == "128x128_w2x2_splitbf16"
     huge.flags = B.FLAG_IEEE_FP32

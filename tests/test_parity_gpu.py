@@ -110,14 +110,15 @@ def test_narrow_k_persistent_kernel(norm, shape):
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
 @pytest.mark.parametrize("case", [(I.BF16, 4100, 136, 4000, "256x256_w2x4"), (I.BF16, 2050, 200, 2040, "128x128_w2x2"),
                                   (I.F16, 4100, 136, 4000, "256x256_w2x4"), (I.F16, 2050, 200, 2040, "128x128_w2x2"),
-                                  (I.F32, 2060, 100, 2040, "64x128_w2x2_splitbf16"),
-                                  (I.F32, 4100, 100, 2040, "128x128_w2x2_splitbf16")])
+                                  (I.F32, 2060, 100, 2040, "64x128_w2x2_splitbf16"),      # tile asked for by flag
+                                  (I.F32, 2060, 100, 2040, "128x128_w2x2_splitbf16")])
 def test_split_rows_one_kernel_and_two_pass(norm, case):
     """Rows split over column tiles, large enough for the one-kernel form (the tiles of a row
     block exchange statistics and finish their rows themselves): ragged M / N / K, a partial
     last round of the persistent grid, checked against the oracle; the two-pass form of the same
     call must agree with the oracle as well."""
     dt, M, K, N, tile = case
+    force = (5 + 1) << 8 if tile.startswith("64x128") else 0     # FGE_FLAG_TILE(64x128): no longer chosen by itself
     w = I.Workload(name=f"split{norm}", M=M, K=K, N=N, in_dtype=dt, out_dtype=dt, act=I.ACT_SILU,
                    norm=norm, alpha=0.5, post_scale=1.5, eps=1e-5,
                    dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1),
@@ -125,13 +126,13 @@ def test_split_rows_one_kernel_and_two_pass(norm, case):
                          "beta": ("normal", 0.0, 0.1)})
     t = I.generate(w)
     d = {k: H.to_device(v) for k, v in t.items()}
-    p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(dt), device="cuda"))
+    p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(dt), device="cuda"), flags=force)
     assert B.fge_tile_name(True, w.act, norm, p) == tile
     assert not B.fge_fused_needs_finish(w.act, norm, p)
-    p.flags = B.FLAG_TWO_PASS
+    p.flags = force | B.FLAG_TWO_PASS
     assert B.fge_fused_needs_finish(w.act, norm, p)
     ref, raux = H.oracle_chain(w, t)
-    for flags in (0, B.FLAG_TWO_PASS):
+    for flags in (force, force | B.FLAG_TWO_PASS):
         got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
         H.check(w, got, gaux, ref, raux, f"split flags={flags}")
     # three launches in a row on one workspace: the marks an earlier launch left behind must
@@ -139,7 +140,7 @@ def test_split_rows_one_kernel_and_two_pass(norm, case):
     aux = torch.zeros(M, device="cuda")
     outs = [torch.full((M, N), float("nan"), dtype=H.tdtype(dt), device="cuda") for _ in range(3)]
     p = B.make_params(d["X"], d["W"], outs[0], alpha=w.alpha, post_scale=w.post_scale, eps=w.eps,
-                      gamma=d["gamma"], beta=d["beta"], aux_out=aux)
+                      gamma=d["gamma"], beta=d["beta"], aux_out=aux, flags=force)
     ws = torch.empty(B.fge_workspace_bytes(True, w.act, norm, p), dtype=torch.uint8, device="cuda")
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
     off = B.fge_fault_word_offset(w.act, norm, p)
@@ -150,9 +151,9 @@ def test_split_rows_one_kernel_and_two_pass(norm, case):
     torch.cuda.synchronize()
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     assert int(ws[off:off + 4].view(torch.int32)[0]) == 0        # no wait ran out
-    p.flags = B.FLAG_TWO_PASS
+    p.flags = force | B.FLAG_TWO_PASS
     assert B.fge_fault_word_offset(w.act, norm, p) is None
-    assert np.array_equal(H.to_host_f64(outs[0]), H.run_gpu(w, t, "fused", dev=d)[0])
+    assert np.array_equal(H.to_host_f64(outs[0]), H.run_gpu(w, t, "fused", dev=d, flags=force)[0])
 
 
 @pytest.mark.parametrize("shape", [(300, 1024, 1024), (1030, 520, 2040), (77, 136, 328), (5000, 40, 328)])
