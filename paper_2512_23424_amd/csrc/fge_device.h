@@ -153,17 +153,19 @@ template <int ACT> __device__ __forceinline__ float activate(float y, float lo, 
     } else if constexpr (ACT == FGE_ACT_GELU_ERF) {
         // 0.5 y (1 + erf(y/sqrt2)) = y * Phi(y).  erfc(|x|) by the rational approximation 7.1.26
         // of Abramowitz & Stegun (|error| <= 1.5e-7 on erf):  erfc(|x|) = poly(t) exp(-x^2),
-        // t = 1/(1 + p|x|).  Phi(y) = 0.5 erfc(|x|) for y < 0 and 1 - 0.5 erfc(|x|) otherwise,
-        // x = y/sqrt2, so the negative tail is formed without cancellation.
-        const float x = 0.7071067811865476f * fabsf(y);
-        const float t = fast_rcp(1.0f + 0.3275911f * x);
-        float q = 1.061405429f;
-        q = q * t - 1.453152027f;
-        q = q * t + 1.421413741f;
-        q = q * t - 0.284496736f;
-        q = q * t + 0.254829592f;
-        const float half_erfc = 0.5f * q * t * fast_exp(-x * x);
-        return y * (y < 0.0f ? half_erfc : 1.0f - half_erfc);
+        // t = 1/(1 + p|x|), x = y/sqrt2.  With h = 0.5 erfc(|x|):  Phi(y) = h for y < 0 and
+        // 1 - h otherwise, so  y Phi(y) = max(y, 0) - |y| h  in both cases, the negative tail
+        // without cancellation.  The constants carry the scalings: u = y sqrt(0.5 log2 e), so that
+        // exp(-x^2) = exp2(-u^2) and p|x| = P|u|; the polynomial's coefficients are halved.
+        const float u = 0.8493218002880191f * y;                          // sqrt(0.5 * log2(e)) * y
+        const float t = fast_rcp(fmaf(0.2727374809f, fabsf(u), 1.0f));    // P = p / sqrt(log2(e))
+        float q = 0.5307027145f;
+        q = q * t - 0.7265760135f;
+        q = q * t + 0.7107068705f;
+        q = q * t - 0.142248368f;
+        q = q * t + 0.127414796f;
+        const float h = q * t * __builtin_amdgcn_exp2f(-u * u);
+        return fmaf(-fabsf(y), h, fmaxf(y, 0.0f));
     } else if constexpr (ACT == FGE_ACT_SILU) {
         return y * fast_rcp(1.0f + fast_exp(-y));
     } else if constexpr (ACT == FGE_ACT_CLAMP) {
