@@ -30,7 +30,7 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3, "f8": 5000.0}      # dense MFMA peaks of MI355X
 PEAK_HBM_GBS = 8000.0
 # which roof binds each workload's dominant kernel
-BOUND = {"cfg1": "mfma", "cfg2": "mfma", "cfg3": "mfma", "cfg4": "mfma", "cfg5": "hbm"}
+BOUND = {"cfg1": "mfma", "cfg2": "mfma", "cfg3": "mfma", "cfg4": "mfma", "cfg5": "hbm", "cfg3_f8": "mfma"}
 
 
 def log(*a):
@@ -205,7 +205,12 @@ def main() -> int:
             return None
         if a.dtype == np.uint16:
             return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        if a.dtype == np.uint8:
+            return torch.from_numpy(a).cuda().view(torch.float8_e4m3fn)
         return torch.from_numpy(a).cuda()
+
+    def dtname(w):
+        return {I.BF16: "bf16", I.F8E4M3: "f8"}.get(w.in_dtype, "f32")
 
     class Case:
         """Device-resident inputs (two rotating X / out sets so consecutive steps do not find
@@ -299,14 +304,14 @@ def main() -> int:
                             post_scale=w.post_scale, act=w.act, clamp_lo=w.clamp_lo,
                             clamp_hi=w.clamp_hi, norm=w.norm, eps=w.eps)
         err = C.max_rel_err(got, ref)
-        tol = 2e-2 if w.in_dtype == I.BF16 else 1e-4
+        tol = 2e-2 if w.in_dtype in (I.BF16, I.F8E4M3) else 1e-4
         if not (err <= tol):
             raise SystemExit(f"bench.py: {w.name} fused result off the oracle: {err:.3e} > {tol}")
         return err
 
     def report(case, t_fused, t_unfused, t_kernel):
         w = case.w
-        dt = "bf16" if w.in_dtype == I.BF16 else "f32"
+        dt = dtname(w)
         tf = w.flops / (t_fused * 1e-3) / 1e12
         gbs = w.algorithmic_bytes / (t_fused * 1e-3) / 1e9
         r = {"tile": case.tile, "kernels_fused": 2 if case.two_pass else 1,
@@ -325,7 +330,7 @@ def main() -> int:
         return r
 
     # ------------------------------------------------------------------ headline workload
-    w = I.WORKLOADS[args.workload]
+    w = I.WORKLOADS[args.workload] if args.workload in I.WORKLOADS else I.EXTRA_WORKLOADS[args.workload]
     log(f"[bench] generating {w.name} ...")
     case = Case(w)
     err = parity(case)
@@ -354,7 +359,7 @@ def main() -> int:
     head = report(case, t_fused, t_unfused, t_kernel_gaps)
     log(f"[bench] {w.name}: {json.dumps(head)}")
 
-    dt = "bf16" if w.in_dtype == I.BF16 else "f32"
+    dt = dtname(w)
     if BOUND[w.name] == "hbm":
         achieved = w.algorithmic_bytes / (t_kernel * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -427,7 +432,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": head["ms_fused"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": f"{w.name}: M={w.rows} K={w.K} N={w.N}, "
-                               f"{'bf16 in/out' if dt == 'bf16' else 'fp32'}, fp32 accumulate, "
+                               f"{'bf16 in/out' if dt == 'bf16' else 'E4M3 in, bf16 out' if dt == 'f8' else 'fp32'}, fp32 accumulate, "
                                f"act={w.act} rowop={w.norm} (codes of include/fge.h)",
                    "tile": head["tile"], "speedup_vs_unfused": head.get("speedup_vs_unfused")},
         "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated, "fp8_operands": f8,
