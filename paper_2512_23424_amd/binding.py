@@ -12,6 +12,8 @@ from typing import Optional
 import torch
 
 from . import inputs as _codes   # only the integer codes of activations / row ops / dtypes
+from .inputs import (ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_GELU_ERF, ACT_SILU, ACT_CLAMP,        # noqa: F401
+                     NORM_NONE, NORM_SOFTMAX, NORM_LAYERNORM, NORM_RMSNORM, NORM_LOGSUMEXP)      # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfge.so")
