@@ -48,7 +48,7 @@ struct PanelShape {
 template <typename OutT, bool FULL, bool STREAM>
 __global__ __launch_bounds__(PanelShape::THREADS)
 void panel_kernel(const TileArgs a) {
-    constexpr int BM = PanelShape::BM, BN = PanelShape::BN, WAVES_N = PanelShape::WAVES_N;
+    constexpr int BM = PanelShape::BM, WAVES_N = PanelShape::WAVES_N;
     constexpr int MB = PanelShape::MB, NB = PanelShape::NB, NT = PanelShape::THREADS;
     constexpr int WTN = NB * 32;
     constexpr int SROWB = 128;                        // LDS bytes per row of a bf16 image: 64 values

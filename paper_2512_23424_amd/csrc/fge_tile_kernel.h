@@ -102,7 +102,8 @@ template <> struct Mma<float> {
 // operand split in two bf16 terms, x = xh + xl (bf16 rounding of the value and of the rest):
 //     x*w ~= xl*wh + xh*wl + xh*wh        (fp32 accumulate, the xl*wl term is dropped)
 // Relative error per product <= about 2^-16.5, against 2^-24 of the fp32 instruction, at less
-// than a fifth of its matrix-pipe time (3 x 8 passes per 16 k instead of 8 x 16 passes).
+// than a fifth of its matrix-pipe time (3 x 8 passes per 16 k instead of 8 x 16 passes).  The
+// split product has a mainloop of its own (operands are split on their way into LDS).
 template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N, bool COOP = false, bool FULL = false,
           bool SPLIT = false, bool GATED = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN <= 64 * 128 ? 2 : 1))
@@ -123,8 +124,8 @@ void tile_kernel(const TileArgs a) {
     constexpr int A_LD = BM * 8 / NT, B_LD = BN * 8 / NT;
     constexpr int RSTEP = NT / 8;                    // rows between a thread's successive chunks
     constexpr bool F8 = sizeof(InT) == 1;            // 64 k per matrix instruction
-    constexpr int FR = SPLIT || F8 ? 2 : 1;          // 16-byte chunks per fragment per k-step (split: high and low part)
-    constexpr int KS = 4 / FR;                       // k-steps per staged tile
+    constexpr int FR = F8 ? 2 : 1;                   // 16-byte chunks per fragment per k-step
+    constexpr int KS = 4 / FR;                       // k-steps per staged tile (the split product has its own loop)
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 16 == 0, "load plan");
     constexpr int STAGE = (BM + BN) * ROWB;
