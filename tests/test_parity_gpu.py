@@ -429,3 +429,22 @@ def test_configuration_search_visits_valid_configurations(dt):
     for r in table:
         got, _ = H.run_gpu(w, t, "fused", dev=d, flags=r["flags"])
         H.check(w, got, None, ref, None, f"config {r['label']} {r['kernel']}")
+
+
+def test_island_search_over_the_library_configurations():
+    """The island search (the paper's Section 3.5 loop) driving the real Verifier: every candidate
+    it admits is one the library accepts and whose result passed, a refused configuration is
+    never admitted, and its winner is not slower than 1.3x the fastest configuration of the full
+    visit (timings of a few microseconds are noisy)."""
+    from paper_2512_23424_amd import tune as T
+    w = I.scaled(WL["cfg2"], M=2048, K=512, N=1024)
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    out = torch.empty(w.M, w.N, device="cuda")
+    kw = dict(eps=w.eps, gamma=d["gamma"], beta=d["beta"])
+    best, ms, seen = T.evolve_library(d["X"], d["W"], d["b"], w.act, w.norm, out, steps=10, warmup=3, **kw)
+    assert best is not None and seen[best]["accepted"] and ms == seen[best]["ms"]
+    assert all(r["accepted"] for r in seen.values())
+    assert ("256x256", 0, 0) not in seen and ("256x256", 0, B.FLAG_IEEE_FP32) not in seen   # refused, not timed
+    table = T.tune(d["X"], d["W"], d["b"], w.act, w.norm, out, steps=10, warmup=3, **kw)
+    assert ms <= 1.3 * table[0]["ms"], (best, ms, table[0])
