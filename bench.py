@@ -120,6 +120,28 @@ def gated_ffn(torch, B, I, timed, log):
     return r
 
 
+def row_ops(torch, B, I, timed, log):
+    """The standalone row operations (fge_row_op: one kernel, one read and one write of the
+    matrix) on large matrices, against the HBM roofline; two rotating buffer sets."""
+    res = []
+    for M, N, dt, norm, name in ((65536, 4096, torch.bfloat16, I.NORM_RMSNORM, "rmsnorm bf16"),
+                                 (65536, 8192, torch.bfloat16, I.NORM_SOFTMAX, "softmax bf16"),
+                                 (65536, 4096, torch.float32, I.NORM_LAYERNORM, "layernorm fp32"),
+                                 (262144, 512, torch.float32, I.NORM_LOGSUMEXP, "logsumexp fp32")):
+        A = [torch.randn(M, N, device="cuda").to(dt) for _ in range(2)]
+        out = [torch.empty(M, N, device="cuda", dtype=dt) for _ in range(2)]
+        g, be, aux = torch.ones(N, device="cuda"), torch.zeros(N, device="cuda"), torch.empty(M, device="cuda")
+        ps = [B.make_params(None, None, out[i], eps=1e-6, gamma=g, beta=be, aux_out=aux) for i in range(2)]
+        ms = timed(lambda i: B.fge_row_op(A[i], norm, ps[i], out[i]), 20, 4)
+        nbytes = 2 * M * N * A[0].element_size()
+        res.append({"op": name, "rows": M, "cols": N, "ms": round(ms, 5), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                    "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)})
+        del A, out
+        torch.cuda.empty_cache()
+    log(f"[bench] row operations: {json.dumps(res)}")
+    return res
+
+
 def fp8_operands(torch, B, I, timed, log):
     """cfg3's chain and shape with 8-bit E4M3 operands (bf16 out): fused against the unfused
     sequence of the same library, parity of sampled rows against the oracle on the same bytes."""
@@ -424,6 +446,7 @@ def main() -> int:
     if not args.no_others:
         gated = gated_ffn(torch, B, I, timed, log)
     f8 = None if args.no_others else fp8_operands(torch, B, I, timed, log)
+    rows = None if args.no_others else row_ops(torch, B, I, timed, log)
     geo = math.exp(sum(math.log(s) for s in sp) / len(sp)) if sp else None
 
     line = {
@@ -435,7 +458,7 @@ def main() -> int:
                                f"{'bf16 in/out' if dt == 'bf16' else 'E4M3 in, bf16 out' if dt == 'f8' else 'fp32'}, fp32 accumulate, "
                                f"act={w.act} rowop={w.norm} (codes of include/fge.h)",
                    "tile": head["tile"], "speedup_vs_unfused": head.get("speedup_vs_unfused")},
-        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated, "fp8_operands": f8,
+        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated, "fp8_operands": f8, "row_ops": rows,
         "speedup_geomean": None if geo is None else round(geo, 3),
         "paper_context": "paper reports 1.46x geomean over PyTorch eager (Triton, Ascend 910B, "
                          "KernelBench L1); no number for this chain",

@@ -50,10 +50,16 @@ __global__ __launch_bounds__(256) void act_kernel(const RowArgs a) {
     });
 }
 
-// K3: out = rowop(A).  The row lives in registers: lane l holds chunks l, l+64, ... (CH of them).
+// K3: out = rowop(A).  The row lives in registers as loaded - lane l holds the 16-byte chunks l,
+// l+64, ... (CH of them) - and is unpacked to fp32 pass by pass, so a 16-bit row costs half the
+// registers of its fp32 image (a row of 8192 bf16 values: 64 registers per lane instead of 128,
+// which is the difference between two and four rows in flight per SIMD).  The price: a 16-bit
+// softmax forms its exponentials twice (for the sum and for the result); an fp32 row keeps
+// them in place.
 template <typename T, int CH>
 __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
     constexpr int CW = Store<T>::CW;
+    constexpr bool PACKED = sizeof(T) == 2;
     const int lane = threadIdx.x & 63;
     const int64_t rowg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (rowg >= (int64_t)a.batch * a.M) return;           // wave-uniform
@@ -62,24 +68,27 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
     T *out = reinterpret_cast<T *>(a.out) + off;
     const int cpr = a.N / CW;
 
-    float v[CH][CW];
+    uint4 raw[CH];                                        // chunks past the row hold zeros
     bool ok[CH];
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
         const int q = lane + 64 * i;
         ok[i] = q < cpr;
-        if (ok[i]) {
-            Store<T>::unpack(*reinterpret_cast<const uint4 *>(in + (int64_t)q * CW), v[i]);
-        } else {
-#pragma unroll
-            for (int e = 0; e < CW; ++e) v[i][e] = 0.0f;
-        }
+        raw[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (ok[i]) raw[i] = *reinterpret_cast<const uint4 *>(in + (int64_t)q * CW);
     }
     const float inv_n = 1.0f / (float)a.N;
-    auto store_row = [&]() __attribute__((always_inline)) {
+    // Called between the passes over a 16-bit row: the compiler must not keep the fp32 image of
+    // one pass for the next (it would, as a common subexpression), that is what costs registers.
+    auto forget_unpacked = [&]() __attribute__((always_inline)) {
+        if constexpr (PACKED) {
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
-            if (ok[i]) *reinterpret_cast<uint4 *>(out + (int64_t)(lane + 64 * i) * CW) = Store<T>::pack(v[i]);
+            for (int i = 0; i < CH; ++i)
+                asm volatile("" : "+v"(raw[i].x), "+v"(raw[i].y), "+v"(raw[i].z), "+v"(raw[i].w));
+        }
+    };
+    auto put = [&](int i, const float (&v)[CW]) __attribute__((always_inline)) {
+        *reinterpret_cast<uint4 *>(out + (int64_t)(lane + 64 * i) * CW) = Store<T>::pack(v);
     };
 
     if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
@@ -87,92 +96,113 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
 #pragma unroll
         for (int i = 0; i < CH; ++i)
             if (ok[i]) {
+                float v[CW];
+                Store<T>::unpack(raw[i], v);
 #pragma unroll
-                for (int e = 0; e < CW; ++e) m = fmaxf(m, v[i][e]);
+                for (int e = 0; e < CW; ++e) m = max_nc(m, v[e]);
             }
         m = allreduce64<OpMax>(m);
+        const float c = -m * LOG2E;                       // exp(v - m) = exp2(v*log2(e) + c)
+        forget_unpacked();
         float s = 0.0f;
-        if (a.norm == FGE_NORM_SOFTMAX) {
 #pragma unroll
-            for (int i = 0; i < CH; ++i)
+        for (int i = 0; i < CH; ++i)
+            if (ok[i]) {
+                float v[CW];
+                Store<T>::unpack(raw[i], v);
 #pragma unroll
                 for (int e = 0; e < CW; ++e) {
-                    v[i][e] = ok[i] ? fast_exp(v[i][e] - m) : 0.0f;
-                    s += v[i][e];
+                    v[e] = exp_rel(v[e], c);
+                    s += v[e];
                 }
-            s = allreduce64<OpSum>(s);
+                if constexpr (!PACKED) {
+                    if (a.norm == FGE_NORM_SOFTMAX) raw[i] = Store<T>::pack(v);
+                }
+            }
+        s = allreduce64<OpSum>(s);
+        if (a.norm == FGE_NORM_SOFTMAX) {
             const float inv = fast_rcp(s);
+            forget_unpacked();
 #pragma unroll
             for (int i = 0; i < CH; ++i)
+                if (ok[i]) {
+                    float v[CW];
+                    Store<T>::unpack(raw[i], v);
 #pragma unroll
-                for (int e = 0; e < CW; ++e) v[i][e] *= inv;
-            store_row();
+                    for (int e = 0; e < CW; ++e) v[e] = (PACKED ? exp_rel(v[e], c) : v[e]) * inv;
+                    put(i, v);
+                }
         } else {
-#pragma unroll
-            for (int i = 0; i < CH; ++i)
-#pragma unroll
-                for (int e = 0; e < CW; ++e) s += ok[i] ? fast_exp(v[i][e] - m) : 0.0f;
-            s = allreduce64<OpSum>(s);
             if (lane == 0) a.aux[rowg] = m + __logf(s);
-            if (a.in != a.out) store_row();
+            if (a.in != a.out) {
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    if (ok[i]) *reinterpret_cast<uint4 *>(out + (int64_t)(lane + 64 * i) * CW) = raw[i];
+            }
         }
         return;
     }
 
-    // gamma / beta for this lane's chunks are read when needed (fp32, 16 bytes at a time)
-    auto affine = [&](int i, float scale, float shift) __attribute__((always_inline)) {
+    // gamma / beta of a chunk are read when it is written (fp32, 16 bytes at a time)
+    auto affine_put = [&](int i, float scale, float shift, bool with_beta) __attribute__((always_inline)) {
+        float v[CW];
+        Store<T>::unpack(raw[i], v);
         const int col = (lane + 64 * i) * CW;
 #pragma unroll
         for (int e4 = 0; e4 < CW; e4 += 4) {
             float4 g = make_float4(1.f, 1.f, 1.f, 1.f), b = make_float4(0.f, 0.f, 0.f, 0.f);
             if (a.gamma) g = *reinterpret_cast<const float4 *>(a.gamma + col + e4);
-            if (a.beta) b = *reinterpret_cast<const float4 *>(a.beta + col + e4);
-            v[i][e4 + 0] = (v[i][e4 + 0] - shift) * scale * g.x + b.x;
-            v[i][e4 + 1] = (v[i][e4 + 1] - shift) * scale * g.y + b.y;
-            v[i][e4 + 2] = (v[i][e4 + 2] - shift) * scale * g.z + b.z;
-            v[i][e4 + 3] = (v[i][e4 + 3] - shift) * scale * g.w + b.w;
+            if (with_beta && a.beta) b = *reinterpret_cast<const float4 *>(a.beta + col + e4);
+            v[e4 + 0] = (v[e4 + 0] - shift) * scale * g.x + b.x;
+            v[e4 + 1] = (v[e4 + 1] - shift) * scale * g.y + b.y;
+            v[e4 + 2] = (v[e4 + 2] - shift) * scale * g.z + b.z;
+            v[e4 + 3] = (v[e4 + 3] - shift) * scale * g.w + b.w;
         }
+        put(i, v);
     };
     if (a.norm == FGE_NORM_LAYERNORM) {
         float s = 0.0f;
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
+        for (int i = 0; i < CH; ++i) {
+            float v[CW];
+            Store<T>::unpack(raw[i], v);                              // masked chunks hold zeros
 #pragma unroll
-            for (int e = 0; e < CW; ++e) s += v[i][e];            // masked chunks hold zeros
+            for (int e = 0; e < CW; ++e) s += v[e];
+        }
         const float mean = allreduce64<OpSum>(s) * inv_n;
+        forget_unpacked();
         float q2 = 0.0f;
 #pragma unroll
         for (int i = 0; i < CH; ++i)
+            if (ok[i]) {
+                float v[CW];
+                Store<T>::unpack(raw[i], v);
 #pragma unroll
-            for (int e = 0; e < CW; ++e) {
-                const float d = v[i][e] - mean;
-                q2 += ok[i] ? d * d : 0.0f;
+                for (int e = 0; e < CW; ++e) {
+                    const float d = v[e] - mean;
+                    q2 += d * d;
+                }
             }
         const float rstd = rsqrtf(allreduce64<OpSum>(q2) * inv_n + a.eps);
+        forget_unpacked();
 #pragma unroll
         for (int i = 0; i < CH; ++i)
-            if (ok[i]) affine(i, rstd, mean);
-    } else {  // FGE_NORM_RMSNORM (beta is not part of it)
+            if (ok[i]) affine_put(i, rstd, mean, true);
+    } else {                                              // FGE_NORM_RMSNORM (beta is not part of it)
         float q2 = 0.0f;
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
-#pragma unroll
-            for (int e = 0; e < CW; ++e) q2 += v[i][e] * v[i][e];
-        const float rr = rsqrtf(allreduce64<OpSum>(q2) * inv_n + a.eps);
-#pragma unroll
         for (int i = 0; i < CH; ++i) {
-            if (!ok[i]) continue;
-            const int col = (lane + 64 * i) * CW;
+            float v[CW];
+            Store<T>::unpack(raw[i], v);
 #pragma unroll
-            for (int e4 = 0; e4 < CW; e4 += 4) {
-                float4 g = make_float4(1.f, 1.f, 1.f, 1.f);
-                if (a.gamma) g = *reinterpret_cast<const float4 *>(a.gamma + col + e4);
-                v[i][e4 + 0] *= rr * g.x; v[i][e4 + 1] *= rr * g.y;
-                v[i][e4 + 2] *= rr * g.z; v[i][e4 + 3] *= rr * g.w;
-            }
+            for (int e = 0; e < CW; ++e) q2 += v[e] * v[e];
         }
+        const float rr = rsqrtf(allreduce64<OpSum>(q2) * inv_n + a.eps);
+        forget_unpacked();
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            if (ok[i]) affine_put(i, rr, 0.0f, false);
     }
-    store_row();
 }
 
 // Second pass of the fused path for rows split over several column strips.  The tile kernel
