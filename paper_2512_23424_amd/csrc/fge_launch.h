@@ -87,12 +87,18 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     // cooperative kernel of a tile.  All workgroups of the grid must be resident at once; a
     // launch that the device cannot hold that way is refused instead of being left to run into
     // its wait limit.
-#define FGE_LAUNCH_COOP1(BM, BN, WM, WN, OT)                                                    \
+#define FGE_LAUNCH_COOP2(BM, BN, WM, WN, OT, FULL)                                              \
     do {                                                                                        \
-        auto kern = tile_kernel<InT, OT, BM, BN, WM, WN, true, false, SPLIT>;                   \
+        auto kern = tile_kernel<InT, OT, BM, BN, WM, WN, true, FULL, SPLIT>;                    \
         static const int resident = resident_workgroups(reinterpret_cast<const void *>(kern), 64 * WM * WN); \
         if ((int)grid.x > resident) return hipErrorCooperativeLaunchTooLarge;                   \
         hipLaunchKernelGGL(kern, grid, dim3(64 * WM * WN), 0, s, a);                            \
+    } while (0)
+    /* guard-free epilogue where every tile lies inside the matrix (256x256 tiles only) */      \
+#define FGE_LAUNCH_COOP1(BM, BN, WM, WN, OT)                                                    \
+    do {                                                                                        \
+        if (BM == 256 && a.M % BM == 0 && a.N % BN == 0) FGE_LAUNCH_COOP2(BM, BN, WM, WN, OT, (BM == 256)); \
+        else                                             FGE_LAUNCH_COOP2(BM, BN, WM, WN, OT, false); \
     } while (0)
 #define FGE_LAUNCH_COOP(BM, BN, WM, WN)                                                         \
     do {                                                                                        \
@@ -129,6 +135,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
 #undef FGE_LAUNCH
 #undef FGE_LAUNCH_COOP
 #undef FGE_LAUNCH_COOP1
+#undef FGE_LAUNCH_COOP2
     return hipGetLastError();
 }
 

@@ -448,3 +448,21 @@ def test_island_search_over_the_library_configurations():
     assert ("256x256", 0, 0) not in seen and ("256x256", 0, B.FLAG_IEEE_FP32) not in seen   # refused, not timed
     table = T.tune(d["X"], d["W"], d["b"], w.act, w.norm, out, steps=10, warmup=3, **kw)
     assert ms <= 1.3 * table[0]["ms"], (best, ms, table[0])
+
+
+@pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
+def test_cooperative_tiles_that_all_lie_inside_the_matrix(norm):
+    """M and N multiples of 256: the one-kernel form runs its guard-free epilogue.  Every element
+    against the oracle, every row op; the two-pass form (guarded epilogue) must agree too."""
+    w = I.Workload(name=f"inside{norm}", M=4096, K=72, N=4096, in_dtype=I.BF16, out_dtype=I.BF16, act=I.ACT_GELU_ERF,
+                   norm=norm, alpha=0.5, post_scale=1.5, eps=1e-5,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1), "b": ("uniform", -0.5, 0.5),
+                         "gamma": ("normal", 1.0, 0.1), "beta": ("normal", 0.0, 0.1)})
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    p = B.make_params(d["X"], d["W"], torch.empty(w.M, w.N, dtype=torch.bfloat16, device="cuda"))
+    assert B.fge_tile_name(True, w.act, norm, p) == "256x256_w2x4" and not B.fge_fused_needs_finish(w.act, norm, p)
+    ref, raux = H.oracle_chain(w, t)
+    for flags in (0, B.FLAG_TWO_PASS):
+        got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
+        H.check(w, got, gaux, ref, raux, f"inside flags={flags}")
