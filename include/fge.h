@@ -94,7 +94,11 @@ typedef enum {
  *   kernel of a large problem finishes its rows itself: the column tiles of a row block run at
  *   the same time, exchange their row statistics through the workspace and wait for each other
  *   (a bounded wait).  That form assumes the launch has the device to itself; set this flag when
- *   several launches may overlap on the device (other streams, other processes).
+ *   several launches may overlap on the device (other streams, other processes).  Before such a
+ *   launch the library asks the runtime whether the device holds the whole grid at once; if it
+ *   does not, fused_gemm_epilogue and fused_gated_gemm_epilogue take the two-pass form by
+ *   themselves, while fge_fused_tiles - whose caller decides about the second pass from
+ *   fge_fused_needs_finish - returns FGE_ERR_HIP.
  *   FGE_FLAG_IEEE_FP32 : multiply fp32 operands with the fp32 matrix instruction.  Without it
  *   fp32 operands are multiplied on the bf16 matrix instruction after a split of each operand
  *   into two bf16 terms, x = xh + xl:  x*w ~= xl*wh + xh*wl + xh*wh with fp32 accumulation.
@@ -109,9 +113,9 @@ typedef enum {
 enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_TILE_MASK = 0xF00 };
 #define FGE_FLAG_TILE(t) ((((int)(t)) + 1) << 8)
 
-/* Tile configurations (rows x columns of one workgroup's output tile).  16-bit operands: 64x64,
- * 64x512, 128x128, 256x256; fp32 operands: 64x64, 64x512, 64x128 and the persistent narrow-K
- * kernel. */
+/* Tile configurations (rows x columns of one workgroup's output tile).  16-bit and 8-bit
+ * operands: 64x64, 64x512, 128x128, 256x256; fp32 operands: 64x64, 64x512, 64x128, 128x128 (split
+ * product only) and the persistent narrow-K kernel. */
 typedef enum {
     FGE_TILE_64x64 = 0, FGE_TILE_64x512 = 1, FGE_TILE_128x128 = 2, FGE_TILE_256x256 = 3,
     FGE_TILE_NARROW_K = 4, FGE_TILE_64x128 = 5

@@ -301,8 +301,11 @@ template <typename T> int launch_rownorm(const RowArgs &r, hipStream_t s) {
     return hip_status(hipGetLastError());
 }
 
+// fall_back: if the device cannot hold the cooperative grid (the launcher refuses it before
+// anything runs), take the two-pass form instead - only for callers that run the second pass
+// from the plan returned here.
 int do_fused_tiles(const void *X, const void *W, const float *b, int act, int norm,
-                   const fge_params *p, void *out, hipStream_t s, Plan *plan_out) {
+                   const fge_params *p, void *out, hipStream_t s, Plan *plan_out, bool fall_back = false) {
     int rc = check_common(p, act, norm, true);
     if (rc) return rc;
     if (!X || !W || !out) return FGE_ERR_NULL;
@@ -330,7 +333,13 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
         if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
         if (!p->workspace || p->workspace_bytes < fused_workspace(p, norm)) return FGE_ERR_WORKSPACE;
     }
-    return launch_tiles(tile_args(X, W, b, act, norm, p, pl, out), p, pl, s);
+    rc = launch_tiles(tile_args(X, W, b, act, norm, p, pl, out), p, pl, s);
+    if (rc == FGE_ERR_HIP && fall_back && pl.coop && fge_last_hip_error() == (int)hipErrorCooperativeLaunchTooLarge) {
+        const Plan p2 = make_plan(p, norm, true);
+        if (plan_out) *plan_out = p2;
+        rc = launch_tiles(tile_args(X, W, b, act, norm, p, p2, out), p, p2, s);
+    }
+    return rc;
 }
 
 int launch_finish(const Plan &pl, int act, int norm, const fge_params *p, void *out, hipStream_t s);
@@ -441,9 +450,9 @@ int fge_fused_needs_finish(int act, int norm, const fge_params *p) {
 int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
                         const fge_params *p, void *out, void *stream) {
     Plan pl{};
-    int rc = do_fused_tiles(X, W, b, act, norm, p, out, (hipStream_t)stream, &pl);
+    int rc = do_fused_tiles(X, W, b, act, norm, p, out, (hipStream_t)stream, &pl, true);
     if (rc || !pl.needs_finish) return rc;
-    return do_fused_finish(act, norm, p, out, (hipStream_t)stream);
+    return launch_finish(pl, act, norm, p, out, (hipStream_t)stream);    // with the plan the tiles ran under
 }
 
 int fge_gemm_bias(const void *X, const void *W, const float *b, const fge_params *p, void *Y, void *stream) {
@@ -513,18 +522,26 @@ int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, con
         return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
     hipStream_t s = (hipStream_t)stream;
-    const Plan pl = make_plan(p, norm, capturing(s), TILE_GATED);
+    Plan pl = make_plan(p, norm, capturing(s), TILE_GATED);
     if (pl.split) {
         if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
         if (!p->workspace || p->workspace_bytes < gated_workspace(p, norm)) return FGE_ERR_WORKSPACE;
     }
-    TileArgs a = tile_args(X, W1, b1, act, norm, p, pl, out);
-    a.W2 = W2; a.b2 = b2;
-    const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
-                    a.coop ? 1u : (unsigned)pl.pr.batch);
-    rc = hip_status(p->in_dtype == FGE_BF16  ? launch_gated_bf16(p->out_dtype, grid, s, a)
-                    : p->in_dtype == FGE_F16 ? launch_gated_f16(p->out_dtype, grid, s, a)
-                                             : launch_gated_f8(p->out_dtype, grid, s, a));
+    for (int attempt = 0;; ++attempt) {
+        TileArgs a = tile_args(X, W1, b1, act, norm, p, pl, out);
+        a.W2 = W2; a.b2 = b2;
+        const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
+                        a.coop ? 1u : (unsigned)pl.pr.batch);
+        rc = hip_status(p->in_dtype == FGE_BF16  ? launch_gated_bf16(p->out_dtype, grid, s, a)
+                        : p->in_dtype == FGE_F16 ? launch_gated_f16(p->out_dtype, grid, s, a)
+                                                 : launch_gated_f8(p->out_dtype, grid, s, a));
+        // a cooperative grid the device cannot hold is refused before anything runs: two-pass form
+        if (attempt == 0 && rc == FGE_ERR_HIP && pl.coop && g_last_hip == (int)hipErrorCooperativeLaunchTooLarge) {
+            pl = make_plan(p, norm, true, TILE_GATED);
+            continue;
+        }
+        break;
+    }
     if (rc || !pl.needs_finish) return rc;
     return launch_finish(pl, act, norm, p, out, s);
 }
