@@ -206,7 +206,7 @@ def main() -> int:
         print(kernel_sources_digest())
         return 0
     if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU; the path shards over rows without any exchange, "
+        log("bench.py: the library runs on ONE GPU; the path shards over rows without any exchange, "
             "but no multi-GPU launch is provided.  Use --gpus 1.")
         return 2
 
