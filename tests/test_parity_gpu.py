@@ -466,3 +466,22 @@ def test_cooperative_tiles_that_all_lie_inside_the_matrix(norm):
     for flags in (0, B.FLAG_TWO_PASS):
         got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
         H.check(w, got, gaux, ref, raux, f"inside flags={flags}")
+
+
+@pytest.mark.parametrize("dt", [I.F32, I.BF16, I.F16, I.F8E4M3])
+def test_every_k_tail_exact_integers(dt):
+    """K below, at and just past the staged K tile (32 fp32 / 64 16-bit / 128 8-bit values) and
+    its multiples, with integer operands: every phase of the mainloops' prologue, steady state and
+    tail must give the exact sums, on a small and on a multi-tile problem."""
+    unit = {I.F32: 4, I.BF16: 8, I.F16: 8, I.F8E4M3: 16}[dt]            # K granularity of the fast kernels
+    tile_k = 128 // {I.F32: 4, I.BF16: 2, I.F16: 2, I.F8E4M3: 1}[dt]
+    ks = sorted({unit, tile_k - unit, tile_k, tile_k + unit, 2 * tile_k - unit, 2 * tile_k, 2 * tile_k + unit,
+                 3 * tile_k, 3 * tile_k + unit, 4 * tile_k + unit, 5 * tile_k})
+    for K in ks:
+        for M, N in ((70, 72), (300, 400)):
+            w = I.Workload(name="ktail", M=M, K=K, N=N, in_dtype=dt, out_dtype=I.F32,
+                           dist={"X": ("int", -2, 2), "W": ("int", -2, 2), "b": ("int", -3, 3)})
+            t = I.generate(w)
+            ref, _ = H.oracle_chain(w, t)
+            got, _ = H.run_gpu(w, t, "fused")
+            assert np.array_equal(got, ref), f"dt={dt} K={K} M={M} N={N}: {int((got != ref).sum())} mismatches"
