@@ -10,13 +10,15 @@
 // accumulator register the 32 lanes with equal lane/32 hold 32 neighbouring columns of one
 // output row.
 //
-// LDS panel layout (both operands): row-major, 128 bytes of K per row (64 bf16 / 32 fp32),
+// LDS panel layout (both operands): row-major, 128 bytes of K per row (128 E4M3 / 64 16-bit /
+// 32 fp32 values; with the split product the 32 values' bf16 high and low parts, 8 + 8 chunks),
 // the eight 16-byte chunks of a row stored at chunk ^ ((row >> 1) & 7): the 16-byte fragment
 // reads of 16 neighbouring rows then touch each of the 64 LDS banks exactly once (measured:
 // zero bank-conflict cycles; the 8-row variant chunk ^ (row & 7) conflicts two-way).
 // Full K tiles are copied global -> LDS directly (no staging registers): a wave's load
 // instruction fills 1024 contiguous LDS bytes, lane l at base + 16*l, so each lane fetches
-// the global chunk that belongs at its LDS position.
+// the global chunk that belongs at its LDS position.  The split product of fp32 operands stages
+// through registers instead, since the operands are split into bf16 parts on the way in.
 #pragma once
 #include "fge_epilogue.h"
 
