@@ -11,7 +11,8 @@
 // output row.
 //
 // LDS panel layout (both operands): row-major, 128 bytes of K per row (128 E4M3 / 64 16-bit /
-// 32 fp32 values; with the split product the 32 values' bf16 high and low parts, 8 + 8 chunks),
+// 32 fp32 values; with the split product the bf16 high and low parts of 32 values in
+// alternating chunks),
 // the eight 16-byte chunks of a row stored at chunk ^ ((row >> 1) & 7): the 16-byte fragment
 // reads of 16 neighbouring rows then touch each of the 64 LDS banks exactly once (measured:
 // zero bank-conflict cycles; the 8-row variant chunk ^ (row & 7) conflicts two-way).
