@@ -108,8 +108,8 @@ def gated_ffn(torch, B, I, timed, log):
     err = C.max_rel_err(got, ref)
     if not (err <= 2e-2):
         raise SystemExit(f"bench.py: gated result off the oracle: {err:.3e}")
-    tf_ = timed(fused, 30, 10)
-    tu_ = timed(unfused, 15, 3)
+    tf_ = timed(fused, 50, 10)
+    tu_ = timed(unfused, 25, 5)
     flops = 4.0 * w.M * w.N * w.K
     r = {"workload": "SiLU-and-Mul + RMSNorm, bf16, M=8192 K=4096 N=4096 (two products)",
          "tile": B.fge_gated_tile_name(w.act, w.norm, ps[0][0]), "ms_fused": round(tf_, 5),
@@ -178,8 +178,8 @@ def fp8_operands(torch, B, I, timed, log):
     err = C.max_rel_err(got, ref)
     if not (err <= 2e-2):
         raise SystemExit(f"bench.py: 8-bit result off the oracle: {err:.3e}")
-    tf_ = timed(fused, 30, 10)
-    tu_ = timed(unfused, 15, 3)
+    tf_ = timed(fused, 50, 10)
+    tu_ = timed(unfused, 25, 5)
     r = {"workload": "cfg3's chain, E4M3 operands, bf16 out, M=8192 K=4096 N=4096",
          "tile": B.fge_tile_name(True, w.act, w.norm, ps[0][0]), "ms_fused": round(tf_, 5),
          "ms_unfused": round(tu_, 5), "tflops": round(w.flops / (tf_ * 1e-3) / 1e12, 2),
@@ -431,10 +431,10 @@ def main() -> int:
             log(f"[bench] generating {name} ...")
             c = Case(wl)
             e = parity(c)
-            steps = 1000 if name == "cfg1" else 30
+            steps = 1000 if name == "cfg1" else 50
             tf_ = timed(c.fused, steps, 10)
             tk_ = kernel_time(c, min(steps, 50))
-            tu_ = timed(c.unfused, steps if name == "cfg1" else 15, 3)
+            tu_ = timed(c.unfused, steps if name == "cfg1" else 25, 5)
             per[name] = report(c, tf_, tu_, tk_)
             per[name]["parity_err"] = float(f"{e:.3e}")
             log(f"[bench] {name}: {json.dumps(per[name])}")
