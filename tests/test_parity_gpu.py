@@ -411,6 +411,55 @@ def test_workload_full_size_sampled_rows(name):
             assert np.abs(ms - 1.0).max() < 2e-2
 
 
+# ---- outputs with more than 2^31 elements (and more than 4 GiB): every offset in the kernels is
+#      64-bit.  The rows around and past the 2^31-th element are checked against the oracle; the
+#      rest by properties evaluated on the device (nothing this large is downloaded).
+@pytest.mark.parametrize("name,kw", [("cfg5", dict(M=4198400, K=16)),              # narrow-K kernel, fp32, 8.6 GB
+                                     ("cfg4", dict(M=65600, K=64)),                # 16 strided problems, bf16, 4.3 GB
+                                     ("cfg3", dict(M=1049100, K=32, N=2048))])     # whole 16-bit rows, ragged last tile
+def test_outputs_past_two_to_the_31_elements(name, kw):
+    w = I.scaled(WL[name], **kw)
+    assert w.rows * w.N > 2 ** 31
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    edge = 2 ** 31 // w.N                             # first row with elements past 2^31
+    rng = np.random.default_rng(11)
+    rows = np.unique(np.concatenate([[0, edge - 1, edge, edge + 1, w.rows - 1],
+                                     rng.integers(edge, w.rows, 24), rng.integers(0, edge, 8)]))
+    ref, raux = H.oracle_chain(w, dict(t, X=np.ascontiguousarray(t["X"][rows])))
+    idx = torch.from_numpy(rows).cuda()
+    X = d["X"].view(w.batch, w.M, w.K) if w.batch > 1 else d["X"]
+    for path in ("fused", "unfused"):
+        out = torch.full((w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N), float("nan"),
+                         dtype=H.tdtype(w.out_dtype), device="cuda")
+        aux = torch.full((w.rows,), float("nan"), device="cuda") if w.norm == I.NORM_LOGSUMEXP else None
+        p = B.make_params(X, d["W"], out, alpha=w.alpha, post_scale=w.post_scale, clamp_lo=w.clamp_lo,
+                          clamp_hi=w.clamp_hi, eps=w.eps, gamma=d["gamma"], beta=d["beta"], aux_out=aux)
+        nbytes = B.fge_workspace_bytes(path == "fused", w.act, w.norm, p)
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), nbytes
+        fn = B.fused_gemm_epilogue if path == "fused" else B.unfused_gemm_epilogue
+        fn(X, d["W"], d["b"], w.act, w.norm, p, out)
+        torch.cuda.synchronize()
+        flat = out.view(w.rows, w.N)
+        H.check(w, H.to_host_f64(flat[idx]), None if aux is None else H.to_host_f64(aux[idx]), ref, raux,
+                f"past 2^31 {path}")
+        # every row, on the device
+        if w.norm == I.NORM_SOFTMAX:
+            s = flat.sum(dim=1, dtype=torch.float32)
+            assert float((s - 1.0).abs().max()) < 4e-3
+        elif w.norm == I.NORM_LOGSUMEXP:
+            top = flat.amax(dim=1)
+            assert float(flat.amin()) >= w.clamp_lo and float(top.max()) <= w.clamp_hi
+            assert bool(((aux >= top - 1e-5) & (aux <= top + math.log(w.N) + 1e-5)).all())
+        else:                                         # RMSNorm: mean square of out / gamma is 1
+            ms = torch.zeros(w.rows, device="cuda")
+            for r0 in range(0, w.rows, 1 << 17):      # in slabs, so no fp32 copy of the whole matrix
+                ms[r0:r0 + (1 << 17)] = ((flat[r0:r0 + (1 << 17)].float() / d["gamma"]) ** 2).mean(dim=1)
+            assert float((ms - 1.0).abs().max()) < 2e-2
+        del out, ws, flat
+
+
 @pytest.mark.parametrize("dt", [I.F32, I.BF16])
 def test_configuration_search_visits_valid_configurations(dt):
     """The search tool runs every configuration the library accepts for a problem; each of them
