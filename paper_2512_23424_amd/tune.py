@@ -259,8 +259,14 @@ def _upload(a):
 
 
 def main(argv: List[str]) -> int:
-    names = [a for a in argv[1:] if not a.startswith("--")]
-    name = names[0] if names else "cfg2"
+    import argparse
+    known = sorted(I.WORKLOADS) + sorted(I.EXTRA_WORKLOADS)
+    ap = argparse.ArgumentParser(prog="python -m paper_2512_23424_amd.tune",
+                                 description="Time every configuration the library accepts for a workload.")
+    ap.add_argument("workload", nargs="?", default="cfg2", choices=known)
+    ap.add_argument("--evolve", action="store_true", help="island search instead of the exhaustive visit")
+    args = ap.parse_args(argv[1:])
+    name = args.workload
     w = I.WORKLOADS[name] if name in I.WORKLOADS else I.EXTRA_WORKLOADS[name]
     t = {k: _upload(v) for k, v in I.generate(w).items()}
     X = t["X"].view(w.batch, w.M, w.K) if w.batch > 1 else t["X"]
@@ -269,7 +275,7 @@ def main(argv: List[str]) -> int:
     aux = torch.empty(w.rows, device="cuda") if w.norm == I.NORM_LOGSUMEXP else None
     kw = dict(alpha=w.alpha, post_scale=w.post_scale, clamp_lo=w.clamp_lo, clamp_hi=w.clamp_hi, eps=w.eps,
               gamma=t["gamma"], beta=t["beta"], aux_out=aux)
-    if "--evolve" in argv:
+    if args.evolve:
         best, ms, seen = evolve_library(X, t["W"], t["b"], w.act, w.norm, out, **kw)
         print(f"{name}: {len(seen)} configurations evaluated by the island search")
         for c, r in sorted(seen.items(), key=lambda e: e[1]["ms"]):
