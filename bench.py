@@ -298,6 +298,25 @@ def main() -> int:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps          # ms per step
 
+    def graphed(fn, calls=100, replays=10):
+        """ms per step with the launches recorded once into a HIP graph and replayed: what a
+        launch-bound step costs once the host is out of the loop (kernels only, no memsets)."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for i in range(calls):
+                fn(i & 1)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(replays):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (calls * replays)
+
     def kernel_time(case, steps):
         """Average duration of the fused tile kernel: events recorded on the launch stream
         (torch's current stream, the one the library is given) around each launch."""
@@ -437,6 +456,10 @@ def main() -> int:
             tu_ = timed(c.unfused, steps if name == "cfg1" else 25, 5)
             per[name] = report(c, tf_, tu_, tk_)
             per[name]["parity_err"] = float(f"{e:.3e}")
+            if name == "cfg1":                      # launch bound: the same steps replayed from a graph
+                gf, gu = graphed(c.fused), graphed(c.unfused)
+                per[name].update(ms_fused_graph=round(gf, 5), ms_unfused_graph=round(gu, 5),
+                                 speedup_vs_unfused_graph=round(gu / gf, 3))
             log(f"[bench] {name}: {json.dumps(per[name])}")
             del c
             torch.cuda.empty_cache()
