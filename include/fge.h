@@ -208,7 +208,7 @@ const char *fge_status_string(int status);
 /* hipError_t (as int) recorded by the calling thread's last FGE_ERR_HIP, else 0. */
 int fge_last_hip_error(void);
 /* Name of the tile configuration the fused path picks for these arguments (static string,
- * e.g. "256x256x64_w2x4"); NULL on invalid arguments.  For reports and tests. */
+ * e.g. "256x256_w2x4"); NULL on invalid arguments.  For reports and tests. */
 const char *fge_tile_name(int fused, int act, int norm, const fge_params *p);
 
 #ifdef __cplusplus

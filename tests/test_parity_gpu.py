@@ -380,6 +380,64 @@ def test_stage_entry_points_compose_to_the_paths():
     assert np.array_equal(H.to_host_f64(o2), unf)
 
 
+# ---- the standalone elementwise and row-operation kernels against the oracle's own functions:
+#      every row op x storage type x width (one chunk per lane up to the widest row, an odd width
+#      for the element-granular kernel), rows with a stride, several problems, in place
+@pytest.mark.parametrize("dt", [I.F32, I.BF16, I.F16])
+@pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
+def test_standalone_row_operations(dt, norm):
+    from oracle import compare as C
+    from oracle import oracle as O
+    for (batch, M, N, pad) in [(1, 37, 8, 0), (1, 130, 520, 8), (2, 45, 4096, 0), (1, 9, 8192, 16), (1, 33, 77, 0)]:
+        a = I.draw(5, "X", (batch * M, N), ("normal", 0.3, 1.5), dt)
+        g = I.draw(5, "gamma", (N,), ("normal", 1.0, 0.1))
+        be = I.draw(5, "beta", (N,), ("normal", 0.0, 0.1))
+        ref, raux = O.rowop(I.as_f64(a), norm, 1e-5, I.as_f64(g), I.as_f64(be))
+        buf_in = torch.zeros(batch, M, N + pad, dtype=H.tdtype(dt), device="cuda")
+        buf_in[:, :, :N] = H.to_device(a).view(batch, M, N)
+        A = buf_in[:, :, :N] if batch > 1 else buf_in[0, :, :N]
+        for in_place in (False, True):
+            buf_out = buf_in.clone() if in_place else torch.full_like(buf_in, float("nan"))
+            out = buf_out[:, :, :N] if batch > 1 else buf_out[0, :, :N]
+            src = out if in_place else A
+            aux = torch.full((batch * M,), float("nan"), device="cuda")
+            p = B.make_params(None, None, out, eps=1e-5, gamma=H.to_device(g), beta=H.to_device(be), aux_out=aux)
+            n = B.fge_workspace_bytes(False, I.ACT_NONE, norm, p)
+            ws = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
+            p.workspace, p.workspace_bytes = ws.data_ptr(), n
+            B.fge_row_op(src, norm, p, out)
+            torch.cuda.synchronize()
+            got = H.to_host_f64(out).reshape(batch * M, N)
+            err = C.max_rel_err(got, ref)
+            label = f"row op {norm} dt {dt} {batch}x{M}x{N} pad {pad} in_place {in_place}: {err:.2e}"
+            print(label, flush=True)
+            assert np.isfinite(got).all() and err <= {I.F32: 1e-5, I.BF16: 8e-3, I.F16: 1e-3}[dt], label
+            if norm == I.NORM_LOGSUMEXP:
+                assert C.max_rel_err_vec(H.to_host_f64(aux), raux) <= 1e-5, label
+            if pad:                                    # the padding columns are never written
+                tail = buf_out[:, :, N:]
+                assert bool(torch.isnan(tail).all()) if not in_place else bool((tail == 0).all())
+
+
+@pytest.mark.parametrize("dt", [I.F32, I.BF16, I.F16])
+def test_standalone_activations(dt):
+    from oracle import compare as C
+    from oracle import oracle as O
+    for (M, N) in [(50, 1032), (7, 33)]:
+        y = I.draw(6, "X", (M, N), ("normal", 0.0, 2.0), dt)
+        Y = H.to_device(y)
+        for act in range(6):
+            A = torch.full((M, N), float("nan"), dtype=H.tdtype(dt), device="cuda")
+            p = B.make_params(None, None, A, clamp_lo=-1.25, clamp_hi=0.75)
+            B.fge_activation(Y, act, p, A)
+            torch.cuda.synchronize()
+            ref = O.act(I.as_f64(y), act, -1.25, 0.75)
+            got = H.to_host_f64(A)
+            tol = {I.F32: 1e-5, I.BF16: 2.0 ** -8, I.F16: 2.0 ** -10}[dt]   # fp32 arithmetic, one rounding of the result
+            bad = np.abs(got - ref) > tol * np.maximum(np.abs(ref), 1e-2) + 1e-6
+            assert not bad.any(), f"act {act} dt {dt} {M}x{N}: {int(bad.sum())} off, first {np.argwhere(bad)[:3].tolist()}"
+
+
 # ---- the full-size workloads, in the launch configuration the benchmark times; the oracle
 #      evaluates sampled complete rows (rows are independent, so those rows are checked exactly)
 @pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
