@@ -105,12 +105,19 @@ typedef enum {
  *   Relative error per product <= about 2^-16.5 (a few 1e-5 on the final result, inside the
  *   1e-4 the fp32 path is held to, and exact for operands that bf16 holds exactly) at less than a
  *   fifth of the matrix-pipe time.  bf16 operands are not affected.
+ *   FGE_FLAG_NO_SPLIT_K : never cut K into slices.  Without it fused_gemm_epilogue runs a problem
+ *   with few tiles and a long K (64x64 tiles, no more of them than compute units, K >= 2048; see
+ *   fge_fused_k_slices) as partial products over 2 to 16 slices of K - one launch, fp32, into the
+ *   workspace - which a second kernel adds in slice order (the result does not depend on the
+ *   schedule) before scale, bias and activation; a row operation then runs over that fp32
+ *   result.  Taken only when the workspace has the room fge_workspace_bytes reports; with a
+ *   smaller workspace (or none, where none is needed otherwise) the problem runs unsliced.
  *   FGE_FLAG_TILE(t) : run the tile kernels with tile configuration t (an fge_tile) instead of
  *   the library's own choice - for tuning and tests.  A configuration without kernels for the
  *   operand type (or the narrow-K kernel outside K <= 64, N <= 512, fp32) yields
  *   FGE_ERR_UNSUPPORTED.  Ignored by the gated form and by shapes that take the element-granular
  *   kernels. */
-enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_TILE_MASK = 0xF00 };
+enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_NO_SPLIT_K = 4, FGE_FLAG_TILE_MASK = 0xF00 };
 #define FGE_FLAG_TILE(t) ((((int)(t)) + 1) << 8)
 
 /* Tile configurations (rows x columns of one workgroup's output tile).  16-bit and 8-bit
@@ -194,6 +201,10 @@ int fge_fused_tiles(const void *X, const void *W, const float *b, int act, int n
 int fge_fused_finish(int act, int norm, const fge_params *p, void *out, void *stream);
 /* 1 if fge_fused_finish has work to do for these arguments, 0 if not, negative on bad args. */
 int fge_fused_needs_finish(int act, int norm, const fge_params *p);
+/* Slices of K that fused_gemm_epilogue cuts these arguments into when the workspace has the
+ * room (1: none; see FGE_FLAG_NO_SPLIT_K), negative on bad args.  The stage entry points
+ * fge_fused_tiles / fge_fused_finish never slice. */
+int fge_fused_k_slices(int act, int norm, const fge_params *p);
 
 /* Unfused K1: Y (rows x N, out_dtype, row stride ldo) = post_scale * (alpha * X.W^T + b). */
 int fge_gemm_bias(const void *X, const void *W, const float *b, const fge_params *p,

@@ -22,6 +22,7 @@ ACT = {"none": 0, "relu": 1, "gelu_tanh": 2, "gelu_erf": 3, "silu": 4, "clamp": 
 NORM = {"none": 0, "softmax": 1, "layernorm": 2, "rmsnorm": 3, "logsumexp": 4}
 FLAG_TWO_PASS = 1
 FLAG_IEEE_FP32 = 2
+FLAG_NO_SPLIT_K = 4
 STATUS_OK = 0
 
 
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.fge_fused_finish.restype = ci
         L.fge_fused_needs_finish.argtypes = [ci, ci, pp]
         L.fge_fused_needs_finish.restype = ci
+        L.fge_fused_k_slices.argtypes = [ci, ci, pp]
+        L.fge_fused_k_slices.restype = ci
         L.fge_gemm_bias.argtypes = [vp, vp, vp, pp, vp, vp]
         L.fge_gemm_bias.restype = ci
         L.fge_activation.argtypes = [vp, ci, pp, vp, vp]
@@ -193,6 +196,13 @@ def fge_fused_tiles(X, W, b, act, norm, p: FgeParams, out, stream=None) -> None:
 def fge_fused_finish(act, norm, p: FgeParams, out, stream=None) -> None:
     _check(lib().fge_fused_finish(_code(ACT, act), _code(NORM, norm), ctypes.byref(p), _ptr(out),
                                   _stream(stream)), "fge_fused_finish")
+
+
+def fge_fused_k_slices(act, norm, p: FgeParams) -> int:
+    rc = lib().fge_fused_k_slices(_code(ACT, act), _code(NORM, norm), ctypes.byref(p))
+    if rc < 0:
+        raise FgeError(-rc, "fge_fused_k_slices")
+    return rc
 
 
 def fge_fused_needs_finish(act, norm, p: FgeParams) -> bool:

@@ -76,7 +76,7 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
     if (p == nullptr) return FGE_ERR_NULL;
     if (act < FGE_ACT_NONE || act > FGE_ACT_CLAMP) return FGE_ERR_BAD_ENUM;
     if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
-    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32 | FGE_FLAG_TILE_MASK)) return FGE_ERR_BAD_ENUM;
+    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32 | FGE_FLAG_NO_SPLIT_K | FGE_FLAG_TILE_MASK)) return FGE_ERR_BAD_ENUM;
     if (!forced_tile_ok(p)) return FGE_ERR_UNSUPPORTED;
     if (p->in_dtype < FGE_F32 || p->in_dtype > FGE_F8E4M3 || p->out_dtype < FGE_F32 || p->out_dtype > FGE_F8E4M3)
         return FGE_ERR_BAD_ENUM;
@@ -197,11 +197,52 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
     return pl;
 }
 
+// K-split (one-call fused entry point only): a problem with so few tiles that most CUs would
+// idle while each workgroup walks a long K alone is cut into S slices of K.  One launch of the
+// tile kernel computes the S partial products (slice z of X and W starts z*K/S elements into
+// every row; fp32, into the workspace), a second kernel adds the slices in slice order and
+// applies scale, bias and activation, and a row operation runs over that fp32 result (a third
+// kernel, one wave per row: a wave that also added the slices of its row would walk them one
+// memory round trip after the other - measured 37 us for that against 8 us for the two kernels).
+// Chosen when it pays (measured at M <= 256, N = K = 4096, 16-bit operands: 39 us as one
+// launch): 64x64 tiles (the choice for small problems; with 256 tiles of 128x128 the slices
+// gained nothing), no more of them than CUs, K >= 2048, slices of at least 512 that are whole
+// staged K tiles, at most two workgroups per CU and 32 MB of partial sums.
+struct KSplit {
+    int slices;                  // 1: none
+    size_t ws_part, ws_mid;      // bytes of the partial products / of the fp32 rows a row op reads
+    size_t bytes() const { return ws_part + ws_mid; }
+};
+
+KSplit k_split(const fge_params *p, int norm, const Plan &pl) {
+    KSplit ks{1, 0, 0};
+    if (pl.generic || pl.tile != TILE_64x64 || pl.pr.batch != 1 || (p->flags & FGE_FLAG_NO_SPLIT_K)) return ks;
+    const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+    if (tiles > NUM_CU || pl.pr.K < 2048) return ks;
+    const size_t one = round256((size_t)pl.pr.M * pl.pr.N * sizeof(float));
+    int S = 1;
+    for (int c = 2; c <= 16; c *= 2)
+        if (tiles * c <= 2 * NUM_CU && pl.pr.K % (c * 128) == 0 && pl.pr.K / c >= 512 && one * c <= ((size_t)32 << 20)) S = c;
+    if (S == 1) return ks;
+    ks.slices = S;
+    ks.ws_part = one * S;
+    ks.ws_mid = norm == FGE_NORM_NONE ? 0 : one;
+    return ks;
+}
+
 // Workspace of the fused path: enough for either form of split rows, since a launch on a
-// stream under graph capture takes the two-pass form whatever the flags say.
+// stream under graph capture takes the two-pass form whatever the flags say - and for the
+// K-split where the one-call entry point would take it.
 size_t fused_workspace(const fge_params *p, int norm) {
     const Plan p1 = make_plan(p, norm, false), p2 = make_plan(p, norm, true);
     if (p1.generic) return p1.ws_generic;
+    const size_t a = p1.ws_stats + p1.ws_marks, b = p2.ws_stats + p2.ws_marks, c = k_split(p, norm, p1).bytes();
+    return a > b ? (a > c ? a : c) : (b > c ? b : c);
+}
+
+// What the tile kernels need of it (the K-split is optional: without the room it is not taken).
+size_t split_rows_workspace(const fge_params *p, int norm) {
+    const Plan p1 = make_plan(p, norm, false), p2 = make_plan(p, norm, true);
     const size_t a = p1.ws_stats + p1.ws_marks, b = p2.ws_stats + p2.ws_marks;
     return a > b ? a : b;
 }
@@ -291,26 +332,63 @@ RowArgs row_args(const void *in, void *out, int act, int norm, const fge_params 
     return r;
 }
 
-template <typename T> int launch_rownorm(const RowArgs &r, hipStream_t s) {
+// SLICES: T = float, the row is formed from the partial products of a K-split (see RowArgs)
+template <typename T, typename OutT = T, bool SLICES = false> int launch_rownorm(const RowArgs &r, hipStream_t s) {
     const int cpr = r.N / Store<T>::CW;
     const int ch = (cpr + 63) / 64;
     const int64_t rows = (int64_t)r.batch * r.M;
     const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
-    if (ch <= 1)       hipLaunchKernelGGL((rownorm_kernel<T, 1>), grid, block, 0, s, r);
-    else if (ch <= 2)  hipLaunchKernelGGL((rownorm_kernel<T, 2>), grid, block, 0, s, r);
-    else if (ch <= 4)  hipLaunchKernelGGL((rownorm_kernel<T, 4>), grid, block, 0, s, r);
-    else if (ch <= 8)  hipLaunchKernelGGL((rownorm_kernel<T, 8>), grid, block, 0, s, r);
-    else if (ch <= 16) hipLaunchKernelGGL((rownorm_kernel<T, 16>), grid, block, 0, s, r);
-    else if (ch <= 32) hipLaunchKernelGGL((rownorm_kernel<T, 32>), grid, block, 0, s, r);
+    if (ch <= 1)       hipLaunchKernelGGL((rownorm_kernel<T, 1, OutT, SLICES>), grid, block, 0, s, r);
+    else if (ch <= 2)  hipLaunchKernelGGL((rownorm_kernel<T, 2, OutT, SLICES>), grid, block, 0, s, r);
+    else if (ch <= 4)  hipLaunchKernelGGL((rownorm_kernel<T, 4, OutT, SLICES>), grid, block, 0, s, r);
+    else if (ch <= 8)  hipLaunchKernelGGL((rownorm_kernel<T, 8, OutT, SLICES>), grid, block, 0, s, r);
+    else if (ch <= 16) hipLaunchKernelGGL((rownorm_kernel<T, 16, OutT, SLICES>), grid, block, 0, s, r);
+    else if (ch <= 32) hipLaunchKernelGGL((rownorm_kernel<T, 32, OutT, SLICES>), grid, block, 0, s, r);
     else return FGE_ERR_UNSUPPORTED;
     return hip_status(hipGetLastError());
 }
 
-// fall_back: if the device cannot hold the cooperative grid (the launcher refuses it before
-// anything runs), take the two-pass form instead - only for callers that run the second pass
-// from the plan returned here.
+// The K-split of k_split(): partial products, their sum with scale / bias / activation, row op.
+int run_k_split(const void *X, const void *W, const float *b, int act, int norm, const fge_params *p,
+                const Plan &pl, const KSplit &ks, void *out, hipStream_t s) {
+    const int S = ks.slices, Kc = pl.pr.K / S;
+    char *part = static_cast<char *>(p->workspace);
+    const int64_t slice = (int64_t)(ks.ws_part / S / sizeof(float));     // elements between slices
+    fge_params q = *p;                         // the S partial products as S problems of one launch
+    q.M = pl.pr.M; q.batch = S; q.K = Kc; q.ldx = pl.pr.ldx; q.batch_stride_x = Kc;
+    q.out_dtype = FGE_F32; q.ldo = pl.pr.N; q.batch_stride_o = slice;
+    q.alpha = q.post_scale = 1.0f;
+    q.flags = p->flags & FGE_FLAG_IEEE_FP32;
+    const Plan pq = make_plan(&q, FGE_NORM_NONE, false, pl.tile);
+    if (pq.generic || pq.pr.batch != S) return FGE_ERR_UNSUPPORTED;    // (k_split() admits no such shape)
+    TileArgs a = tile_args(X, W, nullptr, FGE_ACT_NONE, FGE_NORM_NONE, &q, pq, part);
+    a.bsw = Kc;                                // slice z of W starts z*Kc into every row, like X's
+    int rc = launch_tiles(a, &q, pq, s);
+    if (rc) return rc;
+    GenArgs g = gen_args(p);
+    g.X = part; g.K = S; g.bsx = slice; g.M = pl.pr.M; g.batch = 1; g.b = b; g.act = act;
+    if (norm == FGE_NORM_NONE) {
+        g.dst = out; g.ldd = pl.pr.ldo;
+        return hip_status(launch_splitk_sum(p->out_dtype, s, g));
+    }
+    void *mid = part + ks.ws_part;             // act(post*(alpha*sum + b)) in fp32, dense rows
+    g.dst = mid; g.ldd = pl.pr.N;
+    if ((rc = hip_status(launch_splitk_sum(FGE_F32, s, g)))) return rc;
+    // the row operation on the row in a wave's registers (vectorisable() keeps N <= 8192), read
+    // as one fp32 "slice" that needs no further scale, bias or activation
+    RowArgs r = row_args(mid, out, FGE_ACT_NONE, norm, p, pl);
+    r.b = nullptr; r.scale = 1.0f; r.post = 0.0f; r.slices = 1; r.slice_stride = 0;
+    return p->out_dtype == FGE_BF16  ? launch_rownorm<float, bf16_t, true>(r, s)
+           : p->out_dtype == FGE_F16 ? launch_rownorm<float, f16_t, true>(r, s)
+                                     : launch_rownorm<float, float, true>(r, s);
+}
+
+// one_call (the caller runs a second pass, if any, from the plan returned here - not the stage
+// entry points, whose callers decide from fge_fused_needs_finish): if the device cannot hold the
+// cooperative grid (the launcher refuses it before anything runs), take the two-pass form
+// instead; and take the K-split where it pays and the workspace has the room.
 int do_fused_tiles(const void *X, const void *W, const float *b, int act, int norm,
-                   const fge_params *p, void *out, hipStream_t s, Plan *plan_out, bool fall_back = false) {
+                   const fge_params *p, void *out, hipStream_t s, Plan *plan_out, bool one_call = false) {
     int rc = check_common(p, act, norm, true);
     if (rc) return rc;
     if (!X || !W || !out) return FGE_ERR_NULL;
@@ -334,12 +412,19 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
         r.X = p->workspace; r.ldx = p->N; r.bsx = (int64_t)p->M * p->N; r.dst = out; r.norm = norm;
         return hip_status(launch_generic_row(FGE_F32, p->out_dtype, s, r));
     }
+    if (one_call) {
+        const KSplit ks = k_split(p, norm, pl);
+        if (ks.slices > 1 && p->workspace && p->workspace_bytes >= ks.bytes()) {
+            if (plan_out) plan_out->needs_finish = false;
+            return run_k_split(X, W, b, act, norm, p, pl, ks, out, s);
+        }
+    }
     if (pl.split) {
         if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
-        if (!p->workspace || p->workspace_bytes < fused_workspace(p, norm)) return FGE_ERR_WORKSPACE;
+        if (!p->workspace || p->workspace_bytes < split_rows_workspace(p, norm)) return FGE_ERR_WORKSPACE;
     }
     rc = launch_tiles(tile_args(X, W, b, act, norm, p, pl, out), p, pl, s);
-    if (rc == FGE_ERR_HIP && fall_back && pl.coop && fge_last_hip_error() == (int)hipErrorCooperativeLaunchTooLarge) {
+    if (rc == FGE_ERR_HIP && one_call && pl.coop && fge_last_hip_error() == (int)hipErrorCooperativeLaunchTooLarge) {
         const Plan p2 = make_plan(p, norm, true);
         if (plan_out) *plan_out = p2;
         rc = launch_tiles(tile_args(X, W, b, act, norm, p, p2, out), p, p2, s);
@@ -358,7 +443,7 @@ int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream
     const Plan pl = make_plan(p, norm, capturing(s));
     if (!pl.needs_finish) return FGE_OK;
     if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
-    if (!p->workspace || p->workspace_bytes < fused_workspace(p, norm)) return FGE_ERR_WORKSPACE;
+    if (!p->workspace || p->workspace_bytes < split_rows_workspace(p, norm)) return FGE_ERR_WORKSPACE;
     return launch_finish(pl, act, norm, p, out, s);
 }
 
@@ -450,6 +535,12 @@ int fge_fused_needs_finish(int act, int norm, const fge_params *p) {
     const int rc = check_common(p, act, norm, true);
     if (rc) return -rc;
     return make_plan(p, norm).needs_finish ? 1 : 0;
+}
+
+int fge_fused_k_slices(int act, int norm, const fge_params *p) {
+    const int rc = check_common(p, act, norm, true);
+    if (rc) return -rc;
+    return k_split(p, norm, make_plan(p, norm)).slices;
 }
 
 int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,

@@ -34,6 +34,7 @@ struct TileArgs {
                                 // second pass, or [batch*M][tiles_n] tile pairs (cooperative form)
     int M, N, K;
     int64_t ldx, ldw, ldo, bsx, bso;
+    int64_t bsw;                // offset of problem z in W (0: W is shared; a K-split gives each slice its own k range)
     float alpha, post, lo, hi, eps;
     int act, norm;
     int tiles_m, tiles_n, group_m, batch;

@@ -6,6 +6,7 @@
 //   generic_gemm_kernel : dst = act(post*(alpha*X.W^T + b))   32x32 tile, LDS staged, fp32 FMA
 //   generic_act_kernel  : dst = act(src) [* second operand]   elementwise
 //   generic_row_kernel  : out = rowop(src)                    one wave per row, passes over src
+//   splitk_sum_kernel   : dst = act(post*(alpha*sum_s P_s + b))  the slices of a K-split product, summed in slice order
 #include "fge_launch.h"
 
 namespace fge {
@@ -128,7 +129,47 @@ __global__ __launch_bounds__(256) void generic_row_kernel(const GenArgs a) {
     }
 }
 
+// K-split product: X holds `K` dense fp32 slices of M x N partial sums, `bsx` elements apart; four
+// neighbouring columns per thread (N is a multiple of 4).  The slices are added in slice order,
+// so the result does not depend on how the launch was scheduled.
+template <typename DstT>
+__global__ __launch_bounds__(256) void splitk_sum_kernel(const GenArgs a) {
+    const int n4 = a.N >> 2;
+    const int64_t total = (int64_t)a.M * n4;
+    const float *P = reinterpret_cast<const float *>(a.X);
+    const float scale = a.post * a.alpha;
+    dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) {
+        for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+            const int64_t row = idx / n4;
+            const int col = (int)(idx - row * n4) << 2;
+            const float *q = P + row * a.N + col;
+            floatx4 acc = *reinterpret_cast<const floatx4 *>(q);
+            for (int sl = 1; sl < a.K; ++sl) {
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(q + sl * a.bsx);
+                acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+            }
+            DstT *d = reinterpret_cast<DstT *>(a.dst) + row * a.ldd + col;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float bias = a.b != nullptr ? a.post * a.b[col + e] : 0.0f;
+                Store<DstT>::put(d + e, activate<ACT>(scale * acc[e] + bias, a.lo, a.hi));
+            }
+        }
+    });
+}
+
 }  // namespace
+
+hipError_t launch_splitk_sum(int dst_dtype, hipStream_t s, const GenArgs &a) {
+    const int64_t total = (int64_t)a.M * (a.N >> 2);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;                           // grid-stride beyond that
+    const dim3 grid((unsigned)blocks), block(256);
+    if (dst_dtype == FGE_BF16)     hipLaunchKernelGGL((splitk_sum_kernel<bf16_t>), grid, block, 0, s, a);
+    else if (dst_dtype == FGE_F16) hipLaunchKernelGGL((splitk_sum_kernel<f16_t>), grid, block, 0, s, a);
+    else                           hipLaunchKernelGGL((splitk_sum_kernel<float>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_generic_gemm(int in_dtype, int dst_dtype, hipStream_t s, const GenArgs &a) {
     const dim3 grid((unsigned)((a.N + 31) / 32), (unsigned)((a.M + 31) / 32), (unsigned)a.batch), block(256);

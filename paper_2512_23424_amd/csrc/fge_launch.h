@@ -54,6 +54,8 @@ struct GenArgs {
 hipError_t launch_generic_gemm(int in_dtype, int dst_dtype, hipStream_t s, const GenArgs &a);
 hipError_t launch_generic_act(int dtype, hipStream_t s, const GenArgs &a);
 hipError_t launch_generic_row(int src_dtype, int out_dtype, hipStream_t s, const GenArgs &a);
+// X: a.K dense fp32 slices of M x N, a.bsx elements apart; dst = act(post*(alpha*sum + b))
+hipError_t launch_splitk_sum(int dst_dtype, hipStream_t s, const GenArgs &a);
 
 // Workgroups of `kernel` the current device holds at the same time (0 if the query fails).
 inline int resident_workgroups(const void *kernel, int threads) {

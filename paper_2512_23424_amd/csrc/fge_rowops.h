@@ -2,6 +2,8 @@
 // the light second pass of the fused path that merges per-strip row statistics.
 // One 64-lane wavefront owns one row; data moves in 16-byte chunks per lane.
 #pragma once
+#include <type_traits>
+
 #include "fge_device.h"
 
 namespace fge {
@@ -18,6 +20,13 @@ struct RowArgs {
     float lo, hi, eps;
     int act, norm;
     int tiles_n, bn;            // finish only: column strips per row and their width
+    // row op over a K-split product (rownorm_kernel<float, CH, OutT, true>): `in` holds `slices`
+    // dense fp32 M x N partial products, `slice_stride` elements apart; the row is
+    // act(scale * sum of the slices + post * b) before the row operation
+    const float *b;
+    float scale, post;
+    int slices;
+    int64_t slice_stride;
 };
 
 // K2: A = act(Y) (times a second operand in the gated sequence), elementwise, 16 bytes per lane
@@ -56,16 +65,20 @@ __global__ __launch_bounds__(256) void act_kernel(const RowArgs a) {
 // which is the difference between two and four rows in flight per SIMD).  The price: a 16-bit
 // softmax forms its exponentials twice (for the sum and for the result); an fp32 row keeps
 // them in place.
-template <typename T, int CH>
+// SLICES (T = float): the row is first formed from the partial products of a K-split GEMM - the
+// slices are added in slice order, then scale, bias and activation - and the result is stored
+// as OutT; everything else is the same kernel.
+template <typename T, int CH, typename OutT = T, bool SLICES = false>
 __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
+    static_assert(SLICES ? std::is_same_v<T, float> : std::is_same_v<T, OutT>, "slices are fp32; otherwise in and out share a type");
     constexpr int CW = Store<T>::CW;
     constexpr bool PACKED = sizeof(T) == 2;
     const int lane = threadIdx.x & 63;
     const int64_t rowg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (rowg >= (int64_t)a.batch * a.M) return;           // wave-uniform
     const int64_t off = (rowg / a.M) * a.bso + (rowg % a.M) * a.ldo;
-    const T *in = reinterpret_cast<const T *>(a.in) + off;
-    T *out = reinterpret_cast<T *>(a.out) + off;
+    const T *in = reinterpret_cast<const T *>(a.in) + (SLICES ? rowg * a.N : off);
+    OutT *out = reinterpret_cast<OutT *>(a.out) + off;
     const int cpr = a.N / CW;
 
     uint4 raw[CH];                                        // chunks past the row hold zeros
@@ -76,6 +89,29 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
         ok[i] = q < cpr;
         raw[i] = make_uint4(0u, 0u, 0u, 0u);
         if (ok[i]) raw[i] = *reinterpret_cast<const uint4 *>(in + (int64_t)q * CW);
+    }
+    if constexpr (SLICES) {
+        for (int sl = 1; sl < a.slices; ++sl) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i)
+                if (ok[i]) {
+                    const floatx4 v = *reinterpret_cast<const floatx4 *>(in + sl * a.slice_stride + (int64_t)(lane + 64 * i) * CW);
+                    raw[i].x = as_u32(as_f32(raw[i].x) + v[0]); raw[i].y = as_u32(as_f32(raw[i].y) + v[1]);
+                    raw[i].z = as_u32(as_f32(raw[i].z) + v[2]); raw[i].w = as_u32(as_f32(raw[i].w) + v[3]);
+                }
+        }
+        dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i)
+                if (ok[i]) {
+                    floatx4 bb = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (a.b != nullptr) bb = *reinterpret_cast<const floatx4 *>(a.b + (lane + 64 * i) * CW);
+                    raw[i].x = as_u32(activate<ACT>(fmaf(a.scale, as_f32(raw[i].x), a.post * bb[0]), a.lo, a.hi));
+                    raw[i].y = as_u32(activate<ACT>(fmaf(a.scale, as_f32(raw[i].y), a.post * bb[1]), a.lo, a.hi));
+                    raw[i].z = as_u32(activate<ACT>(fmaf(a.scale, as_f32(raw[i].z), a.post * bb[2]), a.lo, a.hi));
+                    raw[i].w = as_u32(activate<ACT>(fmaf(a.scale, as_f32(raw[i].w), a.post * bb[3]), a.lo, a.hi));
+                }
+        });
     }
     const float inv_n = 1.0f / (float)a.N;
     // Called between the passes over a 16-bit row: the compiler must not keep the fp32 image of
@@ -88,7 +124,13 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
         }
     };
     auto put = [&](int i, const float (&v)[CW]) __attribute__((always_inline)) {
-        *reinterpret_cast<uint4 *>(out + (int64_t)(lane + 64 * i) * CW) = Store<T>::pack(v);
+        if constexpr (sizeof(OutT) == sizeof(T)) {
+            *reinterpret_cast<uint4 *>(out + (int64_t)(lane + 64 * i) * CW) = Store<OutT>::pack(v);
+        } else {                                          // four fp32 values to a 16-bit type: 8 bytes
+            const float f[8] = {v[0], v[1], v[2], v[3], 0.0f, 0.0f, 0.0f, 0.0f};
+            const uint4 u = Store<OutT>::pack(f);
+            *reinterpret_cast<uint2 *>(out + (int64_t)(lane + 64 * i) * CW) = make_uint2(u.x, u.y);
+        }
     };
 
     if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
@@ -134,10 +176,18 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
                 }
         } else {
             if (lane == 0) a.aux[rowg] = m + __logf(s);
-            if (a.in != a.out) {
+            if (SLICES || a.in != a.out) {
 #pragma unroll
                 for (int i = 0; i < CH; ++i)
-                    if (ok[i]) *reinterpret_cast<uint4 *>(out + (int64_t)(lane + 64 * i) * CW) = raw[i];
+                    if (ok[i]) {
+                        if constexpr (SLICES) {
+                            float v[CW];
+                            Store<T>::unpack(raw[i], v);
+                            put(i, v);
+                        } else {
+                            *reinterpret_cast<uint4 *>(out + (int64_t)(lane + 64 * i) * CW) = raw[i];
+                        }
+                    }
             }
         }
         return;

@@ -183,7 +183,7 @@ void tile_kernel(const TileArgs a) {
     const int m0 = tm * BM, n0 = tn * BNO;
 
     const InT *X = reinterpret_cast<const InT *>(a.X) + (int64_t)z * a.bsx;
-    const InT *W = reinterpret_cast<const InT *>(a.W);
+    const InT *W = reinterpret_cast<const InT *>(a.W) + (int64_t)z * a.bsw;
     OutT *out = reinterpret_cast<OutT *>(a.out) + (int64_t)z * a.bso;
 
     // ---------------- global -> LDS staging plan

@@ -3,7 +3,8 @@
 The paper's optimisation loop (its evolutionary search, Section 3.5) proposes kernel variants,
 has the Verifier accept or reject each one, times the accepted ones and keeps the fastest.  The
 configuration space of this library is small and discrete - tile configuration x how split rows
-are finished x (fp32 operands) which matrix instruction multiplies - so the search here visits
+are finished x (fp32 operands) which matrix instruction multiplies x whether a long K is cut
+into slices - so the search here visits
 all of it instead of evolving a population: every configuration the library accepts for the
 problem is run, checked against the automatic configuration's result (the Verifier's element
 rule with the tolerance of the storage type), timed, and the table is returned fastest first.
@@ -22,8 +23,8 @@ of its neighbour; the answer is the fastest member of any island.  Here it reach
 configuration as the full visit with fewer kernel runs only when the space grows; it is kept
 as the search driver for larger configuration spaces and is tested on synthetic ones.
 
-The search only uses the public entry points; FGE_FLAG_TILE and FGE_FLAG_TWO_PASS select the
-configuration.  It is a tool around the library, not part of a call's hot path."""
+The search only uses the public entry points; FGE_FLAG_TILE, FGE_FLAG_TWO_PASS, FGE_FLAG_IEEE_FP32
+and FGE_FLAG_NO_SPLIT_K select the configuration.  It is a tool around the library, not part of a call's hot path."""
 from __future__ import annotations
 
 import random
@@ -51,19 +52,25 @@ def candidates(make_params: Callable[[int], B.FgeParams], act, norm) -> List[Dic
     for tname, tid in [("auto", None)] + list(TILES.items()):
         for two_pass in (0, B.FLAG_TWO_PASS):
             for ex in extra:
-                flags = (0 if tid is None else flag_tile(tid)) | two_pass | ex
-                p = make_params(flags)
-                try:
-                    kernel = B.fge_tile_name(True, act, norm, p)
-                    finish = B.fge_fused_needs_finish(act, norm, p)
-                except B.FgeError:
-                    continue
-                key = (kernel, finish)
-                if key in seen:
-                    continue
-                seen.add(key)
-                out.append({"label": f"{tname}{'+two_pass' if finish else ''}{'+ieee' if ex else ''}",
-                            "flags": flags, "kernel": kernel, "kernels": 2 if finish else 1, "auto": tid is None})
+                for whole_k in (0, B.FLAG_NO_SPLIT_K):
+                    flags = (0 if tid is None else flag_tile(tid)) | two_pass | ex | whole_k
+                    p = make_params(flags)
+                    try:
+                        kernel = B.fge_tile_name(True, act, norm, p)
+                        slices = B.fge_fused_k_slices(act, norm, p)
+                        finish = slices == 1 and B.fge_fused_needs_finish(act, norm, p)
+                    except B.FgeError:
+                        continue
+                    if slices > 1:                      # partial products, their sum, (row op)
+                        kernel += f" k/{slices}"
+                    key = (kernel, finish)
+                    if key in seen:
+                        continue
+                    seen.add(key)
+                    out.append({"label": f"{tname}{'+two_pass' if finish else ''}{'+ieee' if ex else ''}"
+                                         f"{'+whole_k' if whole_k else ''}",
+                                "flags": flags, "kernel": kernel, "auto": tid is None and not whole_k,
+                                "kernels": (2 if norm == I.NORM_NONE else 3) if slices > 1 else 2 if finish else 1})
     return out
 
 
@@ -202,7 +209,8 @@ def evolve_library(X, W, b, act, norm, out: torch.Tensor, *, steps: int = 20, wa
     configuration's result (element rule, tolerance of the storage type) and times it; a
     configuration the library refuses is invalid."""
     base = B.make_params(X, W, out, flags=0, **params)
-    genes = [[None] + list(TILES), [0, B.FLAG_TWO_PASS], [0, B.FLAG_IEEE_FP32] if base.in_dtype == I.F32 else [0]]
+    genes = [[None] + list(TILES), [0, B.FLAG_TWO_PASS], [0, B.FLAG_IEEE_FP32] if base.in_dtype == I.F32 else [0],
+             [0, B.FLAG_NO_SPLIT_K]]
     ref: List[Optional[torch.Tensor]] = [None]
     seen: Dict[Config, Dict] = {}
 
@@ -213,8 +221,10 @@ def evolve_library(X, W, b, act, norm, out: torch.Tensor, *, steps: int = 20, wa
         return p, ws
 
     def evaluate(c: Config):
-        tname, two_pass, ieee = c
-        flags = (0 if tname is None else flag_tile(TILES[tname])) | two_pass | ieee
+        if c in seen:                               # another island has run it already
+            return seen[c]["accepted"], seen[c]["ms"]
+        tname, two_pass, ieee, whole_k = c
+        flags = (0 if tname is None else flag_tile(TILES[tname])) | two_pass | ieee | whole_k
         try:
             p, ws = run(flags)
             kernel = B.fge_tile_name(True, act, norm, p)

@@ -22,7 +22,7 @@ def test_library_exports_every_declared_function():
     assert {"fused_gemm_epilogue", "unfused_gemm_epilogue", "fge_workspace_bytes", "fge_fused_tiles",
             "fge_fused_finish", "fge_gemm_bias", "fge_activation", "fge_row_op",
             "fge_status_string", "fge_last_hip_error", "fge_tile_name",
-            "fge_fused_needs_finish"} <= set(names)
+            "fge_fused_needs_finish", "fge_fused_k_slices"} <= set(names)
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -87,7 +87,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert 4096 * 8 * 8 + 64 * 8 * 4 + 256 < need == 4096 * (8 * 2) * 8
     p.flags = B.FLAG_TWO_PASS
     assert B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p)) == 4096 * (8 * 2) * 8
-    p.flags = 4
+    p.flags = 8
     assert _call(p, act=2, norm=2) == 2        # unknown flag bit
     p.flags = 0
     assert _call(p, act=2, norm=2) == 6
@@ -152,3 +152,28 @@ def test_forced_tile_configurations():
     # a forced tile changes the split-row bookkeeping accordingly
     p = _params(**b16, flags=tile(0))
     assert B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p)) == 512 * (16 * 2) * 8
+
+
+def test_k_split_planning():
+    """Few tiles and a long K: the one-call fused entry point cuts K into slices, and the workspace
+    query asks for the partial products (plus the fp32 rows a row op reads)."""
+    def prm(M, N, K, dt=1, **kw):
+        return _params(M=M, N=N, K=K, ldx=K, ldw=K, ldo=N, in_dtype=dt, out_dtype=dt, **kw)
+    p = prm(64, 4096, 4096)                       # 64 tiles of 64x64: 8 slices fill 512 workgroup slots
+    assert B.fge_fused_k_slices(4, 3, p) == 8
+    one = 64 * 4096 * 4
+    assert B.lib().fge_workspace_bytes(1, 4, 3, ctypes.byref(p)) == 9 * one      # 8 partial products + the fp32 rows the row op reads
+    assert B.lib().fge_workspace_bytes(1, 4, 0, ctypes.byref(p)) == 8 * one
+    assert B.fge_fused_needs_finish(4, 3, p) is True                             # the stage entry points never slice
+    p.flags = B.FLAG_NO_SPLIT_K
+    assert B.fge_fused_k_slices(4, 3, p) == 1
+    assert B.lib().fge_workspace_bytes(1, 4, 0, ctypes.byref(p)) == 0
+    assert B.fge_fused_k_slices(4, 3, prm(256, 1024, 8192)) == 8                 # 64 tiles; 16 slices would pass two per CU
+    assert B.fge_fused_k_slices(4, 3, prm(16, 1024, 8192)) == 16                 # 16 tiles, slices of 512
+    assert B.fge_fused_k_slices(4, 3, prm(64, 4096, 1024)) == 1                  # K too short to pay
+    assert B.fge_fused_k_slices(4, 3, prm(64, 4096, 4096 + 64)) == 1             # slices would not be whole K tiles
+    assert B.fge_fused_k_slices(4, 3, prm(1024, 4096, 4096)) == 1                # enough tiles as it is
+    assert B.fge_fused_k_slices(4, 3, prm(64, 4096, 4096, dt=0)) == 8            # fp32 operands too
+    assert B.fge_fused_k_slices(4, 3, prm(61, 4090, 4096, dt=0)) == 1            # odd extents: element-granular kernels
+    with pytest.raises(B.FgeError):
+        B.fge_fused_k_slices(1, 1, _params(M=0))
