@@ -189,6 +189,44 @@ def fp8_operands(torch, B, I, timed, log):
     return r
 
 
+def few_rows(torch, B, I, timed, log):
+    """A decode-like problem (16 rows, K = N = 4096, bf16, cfg3's chain): bound by reading W once.
+    The fused call cuts K into slices; timed against the same call without the slices and
+    against the unfused sequence, checked against the oracle on every row."""
+    from oracle import compare as C
+    from oracle import oracle as O
+    w = I.scaled(I.WORKLOADS["cfg3"], M=16, K=4096, N=4096)
+    t = I.generate(w)
+    W = [torch.from_numpy(t["W"].view(np.int16)).cuda().view(torch.bfloat16) for _ in range(2)]
+    X = torch.from_numpy(t["X"].view(np.int16)).cuda().view(torch.bfloat16)
+    gamma = torch.from_numpy(t["gamma"]).cuda()
+    out = torch.empty(w.M, w.N, dtype=torch.bfloat16, device="cuda")
+    ps = {}
+    for name, flags in (("sliced", 0), ("whole", B.FLAG_NO_SPLIT_K)):
+        p = B.make_params(X, W[0], out, eps=w.eps, gamma=gamma, flags=flags)
+        n = max(B.fge_workspace_bytes(True, w.act, w.norm, p), B.fge_workspace_bytes(False, w.act, w.norm, p), 16)
+        ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), n
+        ps[name] = (p, ws)
+    out.fill_(float("nan"))
+    B.fused_gemm_epilogue(X, W[0], None, w.act, w.norm, ps["sliced"][0], out)
+    torch.cuda.synchronize()
+    ref, _ = O.chain(I.as_f64(t["X"]), I.as_f64(t["W"]), None, I.as_f64(t["gamma"]), None, act=w.act, norm=w.norm, eps=w.eps)
+    err = C.max_rel_err(out.to(torch.float64).cpu().numpy(), ref)
+    if not (err <= 2e-2):
+        raise SystemExit(f"bench.py: few-rows result off the oracle: {err:.3e}")
+    ts = timed(lambda i: B.fused_gemm_epilogue(X, W[i], None, w.act, w.norm, ps["sliced"][0], out), 200, 20)
+    tw = timed(lambda i: B.fused_gemm_epilogue(X, W[i], None, w.act, w.norm, ps["whole"][0], out), 200, 20)
+    tu = timed(lambda i: B.unfused_gemm_epilogue(X, W[i], None, w.act, w.norm, ps["whole"][0], out), 200, 20)
+    r = {"workload": "cfg3's chain, bf16, M=16 K=4096 N=4096", "k_slices": B.fge_fused_k_slices(w.act, w.norm, ps["sliced"][0]),
+         "ms_fused": round(ts, 5), "ms_fused_whole_k": round(tw, 5), "ms_unfused": round(tu, 5),
+         "gbs": round(w.algorithmic_bytes / (ts * 1e-3) / 1e9, 1),
+         "frac_hbm": round(w.algorithmic_bytes / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+         "speedup_vs_unfused": round(tu / ts, 3), "parity_err": float(f"{err:.3e}")}
+    log(f"[bench] few rows: {json.dumps(r)}")
+    return r
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -470,6 +508,7 @@ def main() -> int:
         gated = gated_ffn(torch, B, I, timed, log)
     f8 = None if args.no_others else fp8_operands(torch, B, I, timed, log)
     rows = None if args.no_others else row_ops(torch, B, I, timed, log)
+    few = None if args.no_others else few_rows(torch, B, I, timed, log)
     geo = math.exp(sum(math.log(s) for s in sp) / len(sp)) if sp else None
 
     line = {
@@ -481,7 +520,7 @@ def main() -> int:
                                f"{'bf16 in/out' if dt == 'bf16' else 'E4M3 in, bf16 out' if dt == 'f8' else 'fp32'}, fp32 accumulate, "
                                f"act={w.act} rowop={w.norm} (codes of include/fge.h)",
                    "tile": head["tile"], "speedup_vs_unfused": head.get("speedup_vs_unfused")},
-        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated, "fp8_operands": f8, "row_ops": rows,
+        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated, "fp8_operands": f8, "row_ops": rows, "few_rows": few,
         "speedup_geomean": None if geo is None else round(geo, 3),
         "paper_context": "paper reports 1.46x geomean over PyTorch eager (Triton, Ascend 910B, "
                          "KernelBench L1); no number for this chain",

@@ -316,15 +316,17 @@ def test_graph_capture_and_replay():
     nodes, and on a capturing stream split rows take the two-pass form (a replay repeats the
     recorded arguments, so arrival marks could not tell one replay from the next).  Every
     replay - with eager work and synchronisations between them - reproduces the eager result."""
-    for (dt, M, K, N) in [(I.BF16, 4100, 136, 4000), (I.F32, 2060, 100, 2040), (I.F32, 5000, 40, 328)]:
+    for (dt, M, K, N) in [(I.BF16, 4100, 136, 4000), (I.F32, 2060, 100, 2040), (I.F32, 5000, 40, 328),
+                          (I.BF16, 24, 4096, 1024)]:          # the last one runs as a K-split (three kernels)
         w = I.Workload(name="graph", M=M, K=K, N=N, in_dtype=dt, out_dtype=dt, act=I.ACT_SILU,
                        norm=I.NORM_RMSNORM, eps=1e-5,
-                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1), "gamma": ("normal", 1.0, 0.1)})
+                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1 if K < 1024 else 0.02), "gamma": ("normal", 1.0, 0.1)})
         t = I.generate(w)
         d = {k: H.to_device(v) for k, v in t.items()}
         eager = torch.empty(M, N, dtype=H.tdtype(dt), device="cuda")
         out = torch.empty_like(eager)
         p = B.make_params(d["X"], d["W"], out, eps=w.eps, gamma=d["gamma"])
+        assert (B.fge_fused_k_slices(w.act, w.norm, p) > 1) == (K >= 2048)
         ws = torch.empty(max(B.fge_workspace_bytes(True, w.act, w.norm, p), 16), dtype=torch.uint8, device="cuda")
         p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
         B.fused_gemm_epilogue(d["X"], d["W"], None, w.act, w.norm, p, eager)
