@@ -106,7 +106,8 @@ typedef enum {
  *   1e-4 the fp32 path is held to, and exact for operands that bf16 holds exactly) at less than a
  *   fifth of the matrix-pipe time.  bf16 operands are not affected.
  *   FGE_FLAG_NO_SPLIT_K : never cut K into slices.  Without it fused_gemm_epilogue runs a problem
- *   with few tiles and a long K (64x64 tiles, no more of them than compute units, K >= 2048; see
+ *   with few tiles and a long K (64x64 tiles, no more of them than compute units, K >= 2048 to
+ *   8192 depending on operand type and tile count; see
  *   fge_fused_k_slices) as partial products over 2 to 16 slices of K - one launch, fp32, into the
  *   workspace - which a second kernel adds in slice order (the result does not depend on the
  *   schedule) before scale, bias and activation; a row operation then runs over that fp32

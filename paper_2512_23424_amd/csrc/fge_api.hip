@@ -204,9 +204,10 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
 // applies scale, bias and activation, and a row operation runs over that fp32 result (a third
 // kernel, one wave per row: a wave that also added the slices of its row would walk them one
 // memory round trip after the other - measured 37 us for that against 8 us for the two kernels).
-// Chosen when it pays (measured at M <= 256, N = K = 4096, 16-bit operands: 39 us as one
-// launch): 64x64 tiles (the choice for small problems; with 256 tiles of 128x128 the slices
-// gained nothing), no more of them than CUs, K >= 2048, slices of at least 512 that are whole
+// Chosen when it pays (measured: 16 x 8192 x 4096, 16-bit operands, 46 us as one launch, 21 us
+// in 8 slices): 64x64 tiles (the choice for small problems; with 256 tiles of 128x128 the slices
+// gained nothing), no more of them than CUs, K >= 2048 (split product) / 4096 / 8192 (more than
+// half the CUs busy as it is), slices of at least 512 that are whole
 // staged K tiles, at most two workgroups per CU and 32 MB of partial sums.
 struct KSplit {
     int slices;                  // 1: none
@@ -218,7 +219,11 @@ KSplit k_split(const fge_params *p, int norm, const Plan &pl) {
     KSplit ks{1, 0, 0};
     if (pl.generic || pl.tile != TILE_64x64 || pl.pr.batch != 1 || (p->flags & FGE_FLAG_NO_SPLIT_K)) return ks;
     const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
-    if (tiles > NUM_CU || pl.pr.K < 2048) return ks;
+    // the 64x64 kernel of the 16- and 8-bit operands and of the fp32 instruction keeps three K tiles
+    // in flight and walks K faster than the split-product kernel: slices pay later there
+    const bool deep = !(p->in_dtype == FGE_F32 && !(p->flags & FGE_FLAG_IEEE_FP32));
+    const int k_min = !deep ? 2048 : tiles * 2 > NUM_CU ? 8192 : 4096;
+    if (tiles > NUM_CU || pl.pr.K < k_min) return ks;
     const size_t one = round256((size_t)pl.pr.M * pl.pr.N * sizeof(float));
     int S = 1;
     for (int c = 2; c <= 16; c *= 2)

@@ -132,8 +132,13 @@ void tile_kernel(const TileArgs a) {
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 16 == 0, "load plan");
     constexpr int STAGE = (BM + BN) * ROWB;
+    // DEEP (the 64x64 tile): a K tile of this size is multiplied in a fraction of the time its
+    // copy takes to arrive, so one tile of lookahead leaves the loop waiting on memory latency.
+    // Four stage buffers keep three copies in flight instead.
+    constexpr bool DEEP = BM == 64 && BN == 64 && !SPLIT && !COOP;
+    constexpr int NST = DEEP ? 4 : 2;
 
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[NST * STAGE];
     __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];
 
     // One pass for an ordinary launch.  A cooperative launch is persistent: every round the
@@ -451,6 +456,35 @@ void tile_kernel(const TileArgs a) {
     };
     const int KF = a.K / BK;                          // full K tiles
     const bool ragged_k = (a.K % BK) != 0;            // plus one partial tile
+    if constexpr (DEEP) {
+        // Tile kt lives in buffer kt % NST; the copies of tiles kt+1 .. kt+NST-1 are in flight
+        // while tile kt is multiplied.  Copies complete in issue order, so "tile kt has landed"
+        // is a wait until only the copies of the later tiles (NS instructions each) are out.
+        // One barrier per tile: behind it tile kt is visible to every wave and every wave is
+        // done with tile kt-1, whose buffer the copy of tile kt+NST-1 may then overwrite.
+        static_assert((NST - 1) * NS <= 16, "copy counter");
+#pragma unroll
+        for (int d = 0; d < NST - 1; ++d)
+            if (d < KF) dma_tile(d, d * BK);
+        for (int kt = 0; kt < KF; ++kt) {
+            const int later = KF - 1 - kt;            // tiles issued after kt (capped by the depth)
+            if (later >= NST - 2)   asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * NS) : "memory");
+            else if (later == 1)    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS) : "memory");
+            else                    lds_dma_wait();
+            __syncthreads();
+            if (kt + NST - 1 < KF) dma_tile((kt + NST - 1) % NST, (kt + NST - 1) * BK);
+            __builtin_amdgcn_sched_barrier(0);
+            read_t0(kt % NST);
+            compute_last(kt % NST);
+        }
+        if (ragged_k) {                               // the partial tile, through registers
+            stage_tail(KF % NST, KF * BK);
+            __syncthreads();
+            read_t0(KF % NST);
+            compute_last(KF % NST);
+        }
+        __syncthreads();
+    } else {
     // Tile kt lives in buffer kt & 1.  Its copy is issued in two halves - behind the MFMAs of
     // the last k-step of tile kt-2 (right after the barrier that ends the reads of that buffer)
     // and of k-step 0 of tile kt-1 - and is awaited just before the barrier of tile kt-1.
@@ -484,6 +518,7 @@ void tile_kernel(const TileArgs a) {
     }
     compute_last(kt & 1);
     if constexpr (WAVES_M * WAVES_N > 1) __syncthreads();
+    }
     }
 
     // ---------------- epilogue.  The store patches live in the panel memory, free once the

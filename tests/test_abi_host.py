@@ -170,7 +170,10 @@ def test_k_split_planning():
     assert B.lib().fge_workspace_bytes(1, 4, 0, ctypes.byref(p)) == 0
     assert B.fge_fused_k_slices(4, 3, prm(256, 1024, 8192)) == 8                 # 64 tiles; 16 slices would pass two per CU
     assert B.fge_fused_k_slices(4, 3, prm(16, 1024, 8192)) == 16                 # 16 tiles, slices of 512
-    assert B.fge_fused_k_slices(4, 3, prm(64, 4096, 1024)) == 1                  # K too short to pay
+    assert B.fge_fused_k_slices(4, 3, prm(64, 4096, 2048)) == 1                  # K too short to pay ...
+    assert B.fge_fused_k_slices(4, 3, prm(64, 4096, 2048, dt=0)) == 4            # ... but not for the split product
+    assert B.fge_fused_k_slices(4, 3, prm(256, 4096, 4096)) == 1                 # 256 tiles: only from K = 8192 on
+    assert B.fge_fused_k_slices(4, 3, prm(256, 4096, 8192)) == 2
     assert B.fge_fused_k_slices(4, 3, prm(64, 4096, 4096 + 64)) == 1             # slices would not be whole K tiles
     assert B.fge_fused_k_slices(4, 3, prm(1024, 4096, 4096)) == 1                # enough tiles as it is
     assert B.fge_fused_k_slices(4, 3, prm(64, 4096, 4096, dt=0)) == 8            # fp32 operands too

@@ -326,7 +326,7 @@ def test_graph_capture_and_replay():
         eager = torch.empty(M, N, dtype=H.tdtype(dt), device="cuda")
         out = torch.empty_like(eager)
         p = B.make_params(d["X"], d["W"], out, eps=w.eps, gamma=d["gamma"])
-        assert (B.fge_fused_k_slices(w.act, w.norm, p) > 1) == (K >= 2048)
+        assert (B.fge_fused_k_slices(w.act, w.norm, p) > 1) == (K >= 4096)
         ws = torch.empty(max(B.fge_workspace_bytes(True, w.act, w.norm, p), 16), dtype=torch.uint8, device="cuda")
         p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
         B.fused_gemm_epilogue(d["X"], d["W"], None, w.act, w.norm, p, eager)
@@ -384,7 +384,7 @@ def test_stage_entry_points_compose_to_the_paths():
 
 # ---- few tiles, long K: the one-call fused entry point cuts K into slices (partial products in
 #      one launch, summed in slice order).  Same gates as everywhere; bit-identical from run to run.
-KSPLIT = [("cfg3", dict(M=16, K=4096, N=4096), 8), ("cfg3", dict(M=1, K=2048, N=1024), 4),
+KSPLIT = [("cfg3", dict(M=16, K=4096, N=4096), 8), ("cfg3", dict(M=1, K=4096, N=1024), 8),
           ("cfg4", dict(M=50, K=4096, N=2048, batch=2), 8), ("cfg2", dict(M=256, K=8192, N=1024), 8),
           ("cfg5", dict(M=100, K=2048, N=520), 4), ("cfg1", dict(M=64, K=8192, N=64), 16)]
 
@@ -401,7 +401,8 @@ def test_k_split_of_problems_with_few_tiles(name, kw, slices):
     for flags in (0, B.FLAG_IEEE_FP32) if w.in_dtype == I.F32 else (0,):
         p = B.make_params(X, d["W"], out, alpha=w.alpha, post_scale=w.post_scale, clamp_lo=w.clamp_lo,
                           clamp_hi=w.clamp_hi, eps=w.eps, gamma=d["gamma"], beta=d["beta"], aux_out=aux, flags=flags)
-        assert B.fge_fused_k_slices(w.act, w.norm, p) == slices
+        # (the fp32 instruction's kernel walks K faster: slices start at K = 4096 there)
+        assert B.fge_fused_k_slices(w.act, w.norm, p) == (1 if flags and w.K < 4096 else slices)
         got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
         H.check(w, got, gaux, ref, raux, f"k-split x{slices} flags {flags}")
         again, _ = H.run_gpu(w, t, "fused", dev=d, flags=flags)
