@@ -181,8 +181,13 @@ size_t fge_fault_word_offset(int act, int norm, const fge_params *p);
  * operands in shapes the fast kernels take; every other case (fp32 operands, odd extents) runs
  * the unfused sequence: two GEMMs into the workspace (fp32 operands always on the fp32 matrix
  * instruction here: the gate multiplies two products and their errors), the gate as an
- * elementwise kernel, the row operation.  fge_gated_workspace_bytes gives the workspace either call needs;
- * fge_gated_tile_name names what the fused call runs ("unfused_sequence" for the fallback). */
+ * elementwise kernel, the row operation.  A small problem with a long K (at most 96 of the gated
+ * kernel's 256 x 128 tiles, K >= 1024) runs as fp32 partial products of both GEMMs instead (K cut
+ * into slices where fused_gemm_epilogue would cut it), one kernel that adds the slices and
+ * applies scale, bias, activation and gate, and the row operation on that fp32 result - when
+ * the workspace has the room, else the tile kernel.  fge_gated_workspace_bytes gives the
+ * workspace either call needs; fge_gated_tile_name names what the fused call runs
+ * ("partial_products_then_gate" for small problems, "unfused_sequence" for the fallback). */
 int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, const float *b1,
                               const float *b2, int act, int norm, const fge_params *p, void *out,
                               void *stream);

@@ -353,32 +353,36 @@ template <typename T, typename OutT = T, bool SLICES = false> int launch_rownorm
     return hip_status(hipGetLastError());
 }
 
-// The K-split of k_split(): partial products, their sum with scale / bias / activation, row op.
-int run_k_split(const void *X, const void *W, const float *b, int act, int norm, const fge_params *p,
-                const Plan &pl, const KSplit &ks, void *out, hipStream_t s) {
-    const int S = ks.slices, Kc = pl.pr.K / S;
-    char *part = static_cast<char *>(p->workspace);
-    const int64_t slice = (int64_t)(ks.ws_part / S / sizeof(float));     // elements between slices
-    fge_params q = *p;                         // the S partial products as S problems of one launch
+// S partial products of X.W^T over S slices of K (S = 1: the whole product), fp32, dense M x N
+// slices `slice` elements apart at `part`: the slices are the problems of one strided-batch launch.
+int launch_partials(const void *X, const void *W, const fge_params *p, const Plan &pl, int S, int64_t slice,
+                    void *part, hipStream_t s) {
+    const int Kc = pl.pr.K / S;
+    fge_params q = *p;
     q.M = pl.pr.M; q.batch = S; q.K = Kc; q.ldx = pl.pr.ldx; q.batch_stride_x = Kc;
     q.out_dtype = FGE_F32; q.ldo = pl.pr.N; q.batch_stride_o = slice;
     q.alpha = q.post_scale = 1.0f;
     q.flags = p->flags & FGE_FLAG_IEEE_FP32;
     const Plan pq = make_plan(&q, FGE_NORM_NONE, false, pl.tile);
-    if (pq.generic || pq.pr.batch != S) return FGE_ERR_UNSUPPORTED;    // (k_split() admits no such shape)
+    if (pq.generic || pq.pr.batch != S) return FGE_ERR_UNSUPPORTED;    // (the callers admit no such shape)
     TileArgs a = tile_args(X, W, nullptr, FGE_ACT_NONE, FGE_NORM_NONE, &q, pq, part);
     a.bsw = Kc;                                // slice z of W starts z*Kc into every row, like X's
-    int rc = launch_tiles(a, &q, pq, s);
-    if (rc) return rc;
+    return launch_tiles(a, &q, pq, s);
+}
+
+// Sum of the slices with scale / bias / activation (and the gate, when a second product's
+// slices are given), then the row op.  `mid`: fp32 rows the row op reads (unused without one).
+int finish_partials(const void *part, const void *part2, const float *b, const float *b2, int act, int norm,
+                    const fge_params *p, const Plan &pl, int S, int64_t slice, void *mid, void *out, hipStream_t s) {
     GenArgs g = gen_args(p);
-    g.X = part; g.K = S; g.bsx = slice; g.M = pl.pr.M; g.batch = 1; g.b = b; g.act = act;
+    g.X = part; g.W = part2; g.K = S; g.bsx = slice; g.M = pl.pr.M; g.batch = 1; g.b = b; g.b2 = b2; g.act = act;
     if (norm == FGE_NORM_NONE) {
         g.dst = out; g.ldd = pl.pr.ldo;
         return hip_status(launch_splitk_sum(p->out_dtype, s, g));
     }
-    void *mid = part + ks.ws_part;             // act(post*(alpha*sum + b)) in fp32, dense rows
-    g.dst = mid; g.ldd = pl.pr.N;
-    if ((rc = hip_status(launch_splitk_sum(FGE_F32, s, g)))) return rc;
+    g.dst = mid; g.ldd = pl.pr.N;              // act(post*(alpha*sum + b)) [* gate] in fp32, dense rows
+    const int rc = hip_status(launch_splitk_sum(FGE_F32, s, g));
+    if (rc) return rc;
     // the row operation on the row in a wave's registers (vectorisable() keeps N <= 8192), read
     // as one fp32 "slice" that needs no further scale, bias or activation
     RowArgs r = row_args(mid, out, FGE_ACT_NONE, norm, p, pl);
@@ -386,6 +390,17 @@ int run_k_split(const void *X, const void *W, const float *b, int act, int norm,
     return p->out_dtype == FGE_BF16  ? launch_rownorm<float, bf16_t, true>(r, s)
            : p->out_dtype == FGE_F16 ? launch_rownorm<float, f16_t, true>(r, s)
                                      : launch_rownorm<float, float, true>(r, s);
+}
+
+// The K-split of k_split(): partial products, their sum with scale / bias / activation, row op.
+int run_k_split(const void *X, const void *W, const float *b, int act, int norm, const fge_params *p,
+                const Plan &pl, const KSplit &ks, void *out, hipStream_t s) {
+    const int S = ks.slices;
+    char *part = static_cast<char *>(p->workspace);
+    const int64_t slice = (int64_t)(ks.ws_part / S / sizeof(float));     // elements between slices
+    const int rc = launch_partials(X, W, p, pl, S, slice, part, s);
+    if (rc) return rc;
+    return finish_partials(part, nullptr, b, nullptr, act, norm, p, pl, S, slice, part + ks.ws_part, out, s);
 }
 
 // one_call (the caller runs a second pass, if any, from the plan returned here - not the stage
@@ -612,6 +627,37 @@ int unfused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, c
     return do_rownorm(A, norm, p, out, s);
 }
 
+// Gated form of a small problem with a long K: the gated tile kernel has 256-row tiles only, and
+// with a handful of them most of the chip idles (16 x 4096 x 4096: 84 us, against 52 us for the
+// unfused sequence).  Such a problem runs like a K-split instead: both products as fp32 partial
+// products (one slice if K is not worth cutting), one kernel that adds the slices and applies
+// scale, bias, activation and the gate in fp32, then the row op.
+struct GatedSmall {
+    bool use;
+    Plan pl;                     // plan of one plain product of this shape
+    KSplit ks;                   // slices of each product; ws_part bytes per product
+    size_t bytes() const { return 2 * ks.ws_part + ks.ws_mid; }
+};
+
+GatedSmall gated_small(const fge_params *p, int norm) {
+    GatedSmall g{false, make_plan(p, norm), {1, 0, 0}};
+    const Plan &pl = g.pl;
+    if (!gated_fast(p, norm) || pl.generic || pl.pr.batch != 1 || pl.tile == TILE_PANEL || pl.pr.K < 1024) return g;
+    const TileInfo &gt = tile_info(TILE_GATED);
+    const int64_t gated_tiles = (int64_t)((pl.pr.M + gt.bm - 1) / gt.bm) * ((pl.pr.N + gt.bn - 1) / gt.bn);
+    // from about 96 of its tiles on the gated kernel is the faster one, and so it is when one plain
+    // product alone has more 64x64 tiles than two per CU (256 x 4096 x 11008: 86 against 117 us)
+    if (gated_tiles * 8 > NUM_CU * 3 || pl.tile != TILE_64x64 || (int64_t)pl.tiles_m * pl.tiles_n > 2 * NUM_CU) return g;
+    g.ks = k_split(p, norm, pl);
+    if (g.ks.slices == 1) {
+        const size_t one = round256((size_t)pl.pr.M * pl.pr.N * sizeof(float));
+        g.ks.ws_part = one;
+        g.ks.ws_mid = norm == FGE_NORM_NONE ? 0 : one;
+    }
+    g.use = true;
+    return g;
+}
+
 int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, const float *b1, const float *b2,
                               int act, int norm, const fge_params *p, void *out, void *stream) {
     int rc = check_common(p, act, norm, true);
@@ -623,6 +669,16 @@ int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, con
         return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
     hipStream_t s = (hipStream_t)stream;
+    const GatedSmall gs = gated_small(p, norm);
+    if (gs.use && p->workspace && p->workspace_bytes >= gs.bytes()) {
+        const int S = gs.ks.slices;
+        char *part = static_cast<char *>(p->workspace);
+        const int64_t slice = (int64_t)(gs.ks.ws_part / S / sizeof(float));
+        if ((rc = launch_partials(X, W1, p, gs.pl, S, slice, part, s))) return rc;
+        if ((rc = launch_partials(X, W2, p, gs.pl, S, slice, part + gs.ks.ws_part, s))) return rc;
+        return finish_partials(part, part + gs.ks.ws_part, b1, b2, act, norm, p, gs.pl, S, slice,
+                               part + 2 * gs.ks.ws_part, out, s);
+    }
     Plan pl = make_plan(p, norm, capturing(s), TILE_GATED);
     if (pl.split) {
         if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
@@ -649,12 +705,16 @@ int fused_gated_gemm_epilogue(const void *X, const void *W1, const void *W2, con
 
 size_t fge_gated_workspace_bytes(int fused, int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return (size_t)-1;
-    return fused && gated_fast(p, norm) ? gated_workspace(p, norm) : 2 * make_plan(p, norm).ws_buf;
+    if (!fused || !gated_fast(p, norm)) return 2 * make_plan(p, norm).ws_buf;
+    const size_t a = gated_workspace(p, norm);
+    const GatedSmall gs = gated_small(p, norm);
+    return gs.use && gs.bytes() > a ? gs.bytes() : a;
 }
 
 const char *fge_gated_tile_name(int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return nullptr;
-    return gated_fast(p, norm) ? tile_info(TILE_GATED).name : "unfused_sequence";
+    if (!gated_fast(p, norm)) return "unfused_sequence";
+    return gated_small(p, norm).use ? "partial_products_then_gate" : tile_info(TILE_GATED).name;
 }
 
 size_t fge_fault_word_offset(int act, int norm, const fge_params *p) {

@@ -137,22 +137,32 @@ __global__ __launch_bounds__(256) void splitk_sum_kernel(const GenArgs a) {
     const int n4 = a.N >> 2;
     const int64_t total = (int64_t)a.M * n4;
     const float *P = reinterpret_cast<const float *>(a.X);
+    const float *P2 = reinterpret_cast<const float *>(a.W);     // gated form: the second product's slices
     const float scale = a.post * a.alpha;
+    auto sum = [&](const float *q) __attribute__((always_inline)) {
+        floatx4 acc = *reinterpret_cast<const floatx4 *>(q);
+        for (int sl = 1; sl < a.K; ++sl) {
+            const floatx4 v = *reinterpret_cast<const floatx4 *>(q + sl * a.bsx);
+            acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+        }
+        return acc;
+    };
     dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) {
         for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
             const int64_t row = idx / n4;
             const int col = (int)(idx - row * n4) << 2;
-            const float *q = P + row * a.N + col;
-            floatx4 acc = *reinterpret_cast<const floatx4 *>(q);
-            for (int sl = 1; sl < a.K; ++sl) {
-                const floatx4 v = *reinterpret_cast<const floatx4 *>(q + sl * a.bsx);
-                acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+            const floatx4 acc = sum(P + row * a.N + col);
+            floatx4 gate = {1.0f, 1.0f, 1.0f, 1.0f};
+            if (P2 != nullptr) {
+                const floatx4 u = sum(P2 + row * a.N + col);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) gate[e] = scale * u[e] + (a.b2 != nullptr ? a.post * a.b2[col + e] : 0.0f);
             }
             DstT *d = reinterpret_cast<DstT *>(a.dst) + row * a.ldd + col;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float bias = a.b != nullptr ? a.post * a.b[col + e] : 0.0f;
-                Store<DstT>::put(d + e, activate<ACT>(scale * acc[e] + bias, a.lo, a.hi));
+                Store<DstT>::put(d + e, activate<ACT>(scale * acc[e] + bias, a.lo, a.hi) * gate[e]);
             }
         }
     });

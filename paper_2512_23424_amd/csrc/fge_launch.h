@@ -44,6 +44,7 @@ hipError_t launch_panel_f32(int out_dtype, dim3 grid, hipStream_t s, const TileA
 struct GenArgs {
     const void *X, *W;
     const float *b, *gamma, *beta;
+    const float *b2;            // slice sum with a gate: bias of the second product
     void *dst;
     float *aux;
     int M, N, K, batch;
@@ -54,7 +55,8 @@ struct GenArgs {
 hipError_t launch_generic_gemm(int in_dtype, int dst_dtype, hipStream_t s, const GenArgs &a);
 hipError_t launch_generic_act(int dtype, hipStream_t s, const GenArgs &a);
 hipError_t launch_generic_row(int src_dtype, int out_dtype, hipStream_t s, const GenArgs &a);
-// X: a.K dense fp32 slices of M x N, a.bsx elements apart; dst = act(post*(alpha*sum + b))
+// X: a.K dense fp32 slices of M x N, a.bsx elements apart; dst = act(post*(alpha*sum + b)),
+// times post*(alpha*sum2 + b2) when W points to the slices of a second product (gated form)
 hipError_t launch_splitk_sum(int dst_dtype, hipStream_t s, const GenArgs &a);
 
 // Workgroups of `kernel` the current device holds at the same time (0 if the query fails).

@@ -180,3 +180,21 @@ def test_k_split_planning():
     assert B.fge_fused_k_slices(4, 3, prm(61, 4090, 4096, dt=0)) == 1            # odd extents: element-granular kernels
     with pytest.raises(B.FgeError):
         B.fge_fused_k_slices(1, 1, _params(M=0))
+
+
+def test_gated_small_problem_planning():
+    """A handful of gated tiles and a long K: fp32 partial products of both GEMMs, then the gate."""
+    def prm(M, N, K):
+        return _params(M=M, N=N, K=K, ldx=K, ldw=K, ldo=N, in_dtype=1, out_dtype=1)
+    L = B.lib()
+    p = prm(16, 4096, 4096)
+    assert L.fge_gated_tile_name(4, 3, ctypes.byref(p)) == b"partial_products_then_gate"
+    one = 16 * 4096 * 4
+    assert L.fge_gated_workspace_bytes(1, 4, 3, ctypes.byref(p)) == (2 * 8 + 1) * one    # 8 slices per product + fp32 rows
+    assert L.fge_gated_workspace_bytes(1, 4, 0, ctypes.byref(p)) == 2 * 8 * one
+    assert L.fge_gated_tile_name(4, 3, ctypes.byref(prm(16, 4096, 512))) == b"gated256x128_w2x4"      # short K
+    assert L.fge_gated_tile_name(4, 3, ctypes.byref(prm(2048, 4096, 4096))) == b"gated256x128_w2x4"   # 256 gated tiles
+    assert L.fge_gated_tile_name(4, 0, ctypes.byref(prm(256, 11008, 4096))) == b"gated256x128_w2x4"   # too many 64x64 tiles
+    q = prm(300, 520, 1152)                                                                           # not worth slicing
+    assert L.fge_gated_tile_name(4, 3, ctypes.byref(q)) == b"partial_products_then_gate"
+    assert L.fge_gated_workspace_bytes(1, 4, 3, ctypes.byref(q)) == 3 * ((300 * 520 * 4 + 255) // 256 * 256)

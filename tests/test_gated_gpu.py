@@ -116,3 +116,37 @@ def test_gated_fp32_keeps_the_fp32_gate():
         err = H.C.max_rel_err(got, ref)
         print(f"gated fp32 {path}: {err:.3e}", flush=True)
         assert err <= 2e-5
+
+
+@pytest.mark.parametrize("dt", [I.BF16, I.F16, I.F8E4M3])
+@pytest.mark.parametrize("norm", NORMS)
+def test_gated_small_problems_with_a_long_k(dt, norm):
+    """A handful of 256-row tiles and a long K: both products run as fp32 partial products (K cut
+    into slices where that pays), then one kernel adds, activates and gates in fp32 and the row
+    op follows - the same gates as the gated tile kernel, which the same call with too small a
+    workspace still takes."""
+    for (M, K, N, act) in [(24, 4096, 1032, I.ACT_SILU), (300, 1152, 520, I.ACT_GELU_ERF)]:
+        if dt == I.F8E4M3:
+            w = I.Workload(name=f"gsmall{norm}", M=M, K=K, N=N, in_dtype=dt, out_dtype=I.BF16, act=act, norm=norm,
+                           alpha=1.0 / K ** 0.5, post_scale=1.5, clamp_lo=-1.0, clamp_hi=2.0, eps=1e-5,
+                           dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 1.0), "b": ("uniform", -0.5, 0.5),
+                                 "gamma": ("normal", 1.0, 0.1), "beta": ("normal", 0.0, 0.1)})
+        else:
+            w = _workload(dt, M, K, N, act, norm)
+            w = I.scaled(w, dist=dict(w.dist, W=("normal", 0.0, 1.0 / K ** 0.5)))
+        _case(w, paths=("fused",), expect="partial_products_then_gate")
+    # without the room for the partial products the gated tile kernel runs the same call
+    t = I.generate_gated(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    out = torch.full((w.M, w.N), float("nan"), dtype=H.tdtype(w.out_dtype), device="cuda")
+    aux = torch.full((w.M,), float("nan"), device="cuda") if norm == I.NORM_LOGSUMEXP else None
+    p = B.make_params(d["X"], d["W"], out, alpha=w.alpha, post_scale=w.post_scale, clamp_lo=w.clamp_lo,
+                      clamp_hi=w.clamp_hi, eps=w.eps, gamma=d["gamma"], beta=d["beta"], aux_out=aux)
+    need = B.fge_gated_workspace_bytes(True, w.act, norm, p)
+    assert need >= 2 * w.M * w.N * 4
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")           # enough for the tile kernel's row statistics
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+    B.fused_gated_gemm_epilogue(d["X"], d["W"], d["W2"], d["b"], d["b2"], w.act, norm, p, out)
+    torch.cuda.synchronize()
+    ref, raux = _oracle(w, t)
+    H.check(w, H.to_host_f64(out), None if aux is None else H.to_host_f64(aux), ref, raux, "gated tile kernel, small workspace")
