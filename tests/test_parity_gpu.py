@@ -412,6 +412,27 @@ def test_k_split_of_problems_with_few_tiles(name, kw, slices):
         H.check(w, whole, waux, ref, raux, "unsliced")
 
 
+def test_k_split_with_row_strides():
+    """X, W and out as views with row strides larger than the rows: the slices start z*K/S elements
+    into every strided row."""
+    w = I.scaled(WL["cfg3"], M=70, K=4096, N=1032, act=I.ACT_GELU_ERF, norm=I.NORM_LAYERNORM)
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    ref, _ = H.oracle_chain(w, t)
+    Xb = torch.zeros(w.M, w.K + 64, dtype=torch.bfloat16, device="cuda"); Xb[:, :w.K] = d["X"]
+    Wb = torch.zeros(w.N, w.K + 128, dtype=torch.bfloat16, device="cuda"); Wb[:, :w.K] = d["W"]
+    ob = torch.full((w.M, w.N + 8), float("nan"), dtype=torch.bfloat16, device="cuda")
+    X, W, out = Xb[:, :w.K], Wb[:, :w.K], ob[:, :w.N]
+    p = B.make_params(X, W, out, eps=w.eps, gamma=d["gamma"], beta=d["beta"])
+    assert (p.ldx, p.ldw, p.ldo) == (w.K + 64, w.K + 128, w.N + 8) and B.fge_fused_k_slices(w.act, w.norm, p) == 8
+    ws = torch.empty(B.fge_workspace_bytes(True, w.act, w.norm, p), dtype=torch.uint8, device="cuda")
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+    B.fused_gemm_epilogue(X, W, d["b"], w.act, w.norm, p, out)
+    torch.cuda.synchronize()
+    H.check(w, H.to_host_f64(out), None, ref, None, "k-split, strided rows")
+    assert bool(torch.isnan(ob[:, w.N:]).all())          # the padding columns are never written
+
+
 @pytest.mark.parametrize("dt", [I.F16, I.F8E4M3])
 @pytest.mark.parametrize("act,norm", [(I.ACT_GELU_TANH, I.NORM_NONE), (I.ACT_RELU, I.NORM_SOFTMAX),
                                       (I.ACT_CLAMP, I.NORM_LOGSUMEXP), (I.ACT_NONE, I.NORM_LAYERNORM)])
