@@ -147,7 +147,10 @@ int pick_tile(const Problem &pr, int in_dtype, int /*norm*/, bool ieee_fp32) {
     if (fits(TILE_256x256) && (count(TILE_256x256) >= NUM_CU ||
                                (2 * count(TILE_256x256) > NUM_CU && count(TILE_128x128) > 2 * NUM_CU)))
         return TILE_256x256;
-    if (fits(TILE_128x128) && count(TILE_128x128) >= NUM_CU) return TILE_128x128;
+    // 128x128 tiles from 5/8 of the CUs on: one round of them (three stage buffers, see tile_args)
+    // then beats the 64x64 tiles' several (640 x 4096 x 4096: 48.5 against 58.3 us; at 512 rows,
+    // 128 tiles, the 64x64 tiles still win with 38 us)
+    if (fits(TILE_128x128) && count(TILE_128x128) * 8 >= NUM_CU * 5) return TILE_128x128;
     return TILE_64x64;
 }
 
@@ -301,6 +304,10 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
     a.act = act; a.norm = norm;
     a.tiles_m = pl.tiles_m; a.tiles_n = pl.tiles_n; a.batch = pl.pr.batch;
     a.group_m = pl.tiles_m < 8 ? pl.tiles_m : 8;
+    // 16- and 8-bit 128x128 tiles, no more of them than CUs: no second workgroup shares a CU, so
+    // the variant with three stage buffers hides the copy latency instead
+    a.deep = pl.tile == TILE_128x128 && p->in_dtype != FGE_F32 &&
+             (int64_t)pl.tiles_m * pl.tiles_n * pl.pr.batch <= NUM_CU;
     a.coop = 0;
     if (pl.coop && norm != FGE_NORM_NONE) {
         char *base = static_cast<char *>(p->workspace) + pl.ws_stats;

@@ -109,12 +109,32 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
         if (out_dtype != FGE_F32)  FGE_LAUNCH_COOP1(BM, BN, WM, WN, NarrowT);                   \
         else                       FGE_LAUNCH_COOP1(BM, BN, WM, WN, float);                     \
     } while (0)
+    // 128x128 tiles with three stage buffers (one workgroup per CU), ordinary and cooperative launch
+#define FGE_LAUNCH_DEEP128(OT)                                                                  \
+    do {                                                                                        \
+        if (a.coop) {                                                                           \
+            auto kern = tile_kernel<InT, OT, 128, 128, 2, 2, true, false, false, false, 3>;     \
+            static const int resident = resident_workgroups(reinterpret_cast<const void *>(kern), 256); \
+            if ((int)grid.x > resident) return hipErrorCooperativeLaunchTooLarge;               \
+            hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, a);                                 \
+        } else {                                                                                \
+            hipLaunchKernelGGL((tile_kernel<InT, OT, 128, 128, 2, 2, false, false, false, false, 3>), grid, \
+                               dim3(256), 0, s, a);                                             \
+        }                                                                                       \
+    } while (0)
     constexpr bool BF = sizeof(InT) <= 2;
     switch (tile) {
     case TILE_64x64:   FGE_LAUNCH(64, 64, 2, 2); break;
     case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4); break;
     case TILE_128x128:
         if constexpr (BF || SPLIT) {
+            if constexpr (BF && !SPLIT) {
+                if (a.deep) {
+                    if (out_dtype != FGE_F32) FGE_LAUNCH_DEEP128(NarrowT);
+                    else                      FGE_LAUNCH_DEEP128(float);
+                    break;
+                }
+            }
             if (a.coop) FGE_LAUNCH_COOP(128, 128, 2, 2);
             else        FGE_LAUNCH(128, 128, 2, 2);
             break;
@@ -137,6 +157,7 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     default: return hipErrorInvalidValue;
     }
 #undef FGE_LAUNCH
+#undef FGE_LAUNCH_DEEP128
 #undef FGE_LAUNCH_COOP
 #undef FGE_LAUNCH_COOP1
 #undef FGE_LAUNCH_COOP2

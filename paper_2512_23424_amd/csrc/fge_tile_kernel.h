@@ -107,8 +107,9 @@ template <> struct Mma<float> {
 // Relative error per product <= about 2^-16.5, against 2^-24 of the fp32 instruction, at less
 // than a fifth of its matrix-pipe time (3 x 8 passes per 16 k instead of 8 x 16 passes).  The
 // split product has a mainloop of its own (operands are split on their way into LDS).
+// STAGES: 0 for the tile's usual number of stage buffers, else that many (see DEEP below).
 template <typename InT, typename OutT, int BM, int BN, int WAVES_M, int WAVES_N, bool COOP = false, bool FULL = false,
-          bool SPLIT = false, bool GATED = false>
+          bool SPLIT = false, bool GATED = false, int STAGES = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (BM * BN <= 64 * 128 ? 2 : 1))
 void tile_kernel(const TileArgs a) {
     static_assert(!SPLIT || sizeof(InT) == 4, "only fp32 operands are split");
@@ -132,11 +133,14 @@ void tile_kernel(const TileArgs a) {
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 16 == 0, "load plan");
     constexpr int STAGE = (BM + BN) * ROWB;
-    // DEEP (the 64x64 tile): a K tile of this size is multiplied in a fraction of the time its
-    // copy takes to arrive, so one tile of lookahead leaves the loop waiting on memory latency.
-    // Four stage buffers keep three copies in flight instead.
-    constexpr bool DEEP = BM == 64 && BN == 64 && !SPLIT && !COOP;
-    constexpr int NST = DEEP ? 4 : 2;
+    // DEEP: a K tile of a small tile is multiplied in a fraction of the time its copy takes to
+    // arrive, so one tile of lookahead leaves the loop waiting on memory latency.  The 64x64 tile
+    // always runs with four stage buffers (three copies in flight, two workgroups per CU); the
+    // 128x128 tile has a variant with three (STAGES = 3, one workgroup per CU) for launches that
+    // give a CU no second workgroup to hide the latency with.
+    static_assert(STAGES == 0 || (STAGES > 2 && !SPLIT && !GATED), "extra stage buffers: plain 16- and 8-bit tiles");
+    constexpr bool DEEP = STAGES > 2 || (BM == 64 && BN == 64 && !SPLIT && !COOP);
+    constexpr int NST = STAGES > 2 ? STAGES : DEEP ? 4 : 2;
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[NST * STAGE];
     __shared__ __attribute__((aligned(16))) float2 xch[2 * BM * WAVES_N];
@@ -462,15 +466,15 @@ void tile_kernel(const TileArgs a) {
         // is a wait until only the copies of the later tiles (NS instructions each) are out.
         // One barrier per tile: behind it tile kt is visible to every wave and every wave is
         // done with tile kt-1, whose buffer the copy of tile kt+NST-1 may then overwrite.
-        static_assert((NST - 1) * NS <= 16, "copy counter");
+        static_assert(NST <= 4 && (NST - 1) * NS <= 32, "copy counter");
 #pragma unroll
         for (int d = 0; d < NST - 1; ++d)
             if (d < KF) dma_tile(d, d * BK);
         for (int kt = 0; kt < KF; ++kt) {
             const int later = KF - 1 - kt;            // tiles issued after kt (capped by the depth)
-            if (later >= NST - 2)   asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * NS) : "memory");
-            else if (later == 1)    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS) : "memory");
-            else                    lds_dma_wait();
+            if (later >= NST - 2)             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * NS) : "memory");
+            else if (NST > 3 && later == 1)   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS) : "memory");
+            else                              lds_dma_wait();
             __syncthreads();
             if (kt + NST - 1 < KF) dma_tile((kt + NST - 1) % NST, (kt + NST - 1) * BK);
             __builtin_amdgcn_sched_barrier(0);
