@@ -160,7 +160,9 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
                           const fge_params *p, void *out, void *stream);
 
 /* Bytes of workspace the fused (fused != 0) or unfused (fused == 0) path needs for these
- * arguments; 0 is a valid answer.  Returns (size_t)-1 when the arguments are invalid. */
+ * arguments; 0 is a valid answer.  Returns (size_t)-1 when the arguments are invalid.  The fused
+ * figure includes the room for the optional K slices (FGE_FLAG_NO_SPLIT_K); a smaller workspace
+ * that still holds the row statistics of split rows is accepted and runs unsliced. */
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p);
 
 /* Where the one-kernel form of split rows reports a wait that ran out: byte offset into the
