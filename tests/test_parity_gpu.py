@@ -412,6 +412,35 @@ def test_k_split_of_problems_with_few_tiles(name, kw, slices):
         H.check(w, whole, waux, ref, raux, "unsliced")
 
 
+def test_k_split_needs_the_room_and_is_skipped_without_it():
+    """A workspace that holds the row statistics of split rows but not the partial products: the
+    call is accepted and runs unsliced; with no workspace at all where none is needed otherwise
+    (no row op) as well."""
+    w = I.scaled(WL["cfg3"], M=16, K=4096, N=4096)
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    ref, _ = H.oracle_chain(w, t)
+    out = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    p = B.make_params(d["X"], d["W"], out, eps=w.eps, gamma=d["gamma"])
+    assert B.fge_fused_k_slices(w.act, w.norm, p) == 8
+    whole = B.make_params(d["X"], d["W"], out, eps=w.eps, gamma=d["gamma"], flags=B.FLAG_NO_SPLIT_K)
+    small = B.fge_workspace_bytes(True, w.act, w.norm, whole)
+    assert 0 < small < B.fge_workspace_bytes(True, w.act, w.norm, p)
+    ws = torch.empty(small, dtype=torch.uint8, device="cuda")
+    p.workspace, p.workspace_bytes = ws.data_ptr(), small
+    B.fused_gemm_epilogue(d["X"], d["W"], None, w.act, w.norm, p, out)
+    torch.cuda.synchronize()
+    H.check(w, H.to_host_f64(out), None, ref, None, "unsliced for want of room")
+    w0 = I.scaled(w, norm=I.NORM_NONE)
+    ref0, _ = H.oracle_chain(w0, t)
+    out.fill_(float("nan"))
+    p0 = B.make_params(d["X"], d["W"], out)
+    assert B.fge_fused_k_slices(w0.act, w0.norm, p0) == 8 and p0.workspace_bytes == 0
+    B.fused_gemm_epilogue(d["X"], d["W"], None, w0.act, w0.norm, p0, out)
+    torch.cuda.synchronize()
+    H.check(w0, H.to_host_f64(out), None, ref0, None, "no workspace, no row op")
+
+
 def test_k_split_with_row_strides():
     """X, W and out as views with row strides larger than the rows: the slices start z*K/S elements
     into every strided row."""
