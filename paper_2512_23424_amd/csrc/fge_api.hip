@@ -21,7 +21,7 @@ std::atomic<unsigned> g_generation{
 
 constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 CUs
 constexpr int MAX_ROWOP_N = 8192;    // a row must fit the register-resident row kernels
-constexpr int MAX_SPLIT = 1024;      // column strips per row the second pass will merge
+constexpr int MAX_SPLIT = 8192;      // column strips per row the second pass will merge (wider rows: element-granular kernels)
 
 inline size_t esize(int dt) { return dt == FGE_F32 ? 4 : dt == FGE_F8E4M3 ? 1 : 2; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -99,8 +99,9 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
 
 // Whether the vectorised kernels take this problem: every extent and stride they move in
 // 16-byte units must be a multiple of 16 bytes (base pointers are checked separately), and a
-// row operation needs the row to fit a wave's registers.  Everything else goes to the
-// element-granular kernels.
+// row operation on its own (need_in false: the unfused K3, fge_row_op) needs the row to fit a
+// wave's registers - the fused tile kernels split rows of any width over column tiles.
+// Everything else goes to the element-granular kernels.
 bool vectorisable(const fge_params *p, int norm, bool need_in) {
     const size_t is = esize(p->in_dtype), os = esize(p->out_dtype);
     if ((p->N * os) % 16 || (p->ldo * os) % 16) return false;
@@ -109,7 +110,7 @@ bool vectorisable(const fge_params *p, int norm, bool need_in) {
         if ((p->K * is) % 16 || (p->ldx * is) % 16 || (p->ldw * is) % 16) return false;
         if (p->batch > 1 && (p->batch_stride_x * is) % 16) return false;
     }
-    if (norm != FGE_NORM_NONE && p->N > MAX_ROWOP_N) return false;
+    if (norm != FGE_NORM_NONE && !need_in && p->N > MAX_ROWOP_N) return false;
     return true;
 }
 
@@ -191,7 +192,7 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
     pl.ws_buf = round256(extent * esize(p->out_dtype));
     // K2 writes straight into `out` when the row op leaves the activated values in place
     pl.n_bufs = (norm == FGE_NORM_NONE || norm == FGE_NORM_LOGSUMEXP) ? 1 : 2;
-    pl.generic = !vectorisable(p, norm, true);
+    pl.generic = !vectorisable(p, norm, true) || (pl.split && pl.tiles_n * ti.waves_n > MAX_SPLIT);
     if (pl.generic) {                // no tiles, no statistics: GEMM + activation to fp32, then the row op
         pl.split = pl.coop = pl.needs_finish = false;
         pl.ws_stats = pl.ws_marks = 0;
@@ -221,6 +222,7 @@ struct KSplit {
 KSplit k_split(const fge_params *p, int norm, const Plan &pl) {
     KSplit ks{1, 0, 0};
     if (pl.generic || pl.tile != TILE_64x64 || pl.pr.batch != 1 || (p->flags & FGE_FLAG_NO_SPLIT_K)) return ks;
+    if (norm != FGE_NORM_NONE && pl.pr.N > MAX_ROWOP_N) return ks;      // its row kernel holds a row in registers
     const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
     // the 64x64 kernel of the 16- and 8-bit operands and of the fp32 instruction keeps three K tiles
     // in flight and walks K faster than the split-product kernel: slices pay later there
@@ -650,6 +652,7 @@ GatedSmall gated_small(const fge_params *p, int norm) {
     GatedSmall g{false, make_plan(p, norm), {1, 0, 0}};
     const Plan &pl = g.pl;
     if (!gated_fast(p, norm) || pl.generic || pl.pr.batch != 1 || pl.tile == TILE_PANEL || pl.pr.K < 1024) return g;
+    if (norm != FGE_NORM_NONE && pl.pr.N > MAX_ROWOP_N) return g;
     const TileInfo &gt = tile_info(TILE_GATED);
     const int64_t gated_tiles = (int64_t)((pl.pr.M + gt.bm - 1) / gt.bm) * ((pl.pr.N + gt.bn - 1) / gt.bn);
     // from about 96 of its tiles on the gated kernel is the faster one, and so it is when one plain

@@ -67,16 +67,20 @@ def test_argument_errors_are_reported_before_any_launch():
     assert _call(_params(ldo=128)) == 3                       # stride smaller than the row
     assert _call(_params(ldx=32)) == 3
     assert _call(_params(), X=FAKE + 4) == 5                  # misaligned base pointer
-    # extents / strides that are not multiples of 16 bytes, and rows too wide for the register
-    # row kernels, are valid: they take the element-granular kernels, which need a workspace for
+    # extents / strides that are not multiples of 16 bytes are valid: they take the element-granular kernels, which need a workspace for
     # the fp32 intermediate of a row op (so these calls stop at the missing workspace)
-    for q in (_params(N=250, ldo=250), _params(K=62, ldx=64, ldw=64), _params(ldo=258),
-              _params(N=16384, ldo=16384)):
+    for q in (_params(N=250, ldo=250), _params(K=62, ldx=64, ldw=64), _params(ldo=258)):
         assert B.fge_tile_name(True, 1, 1, q) == "generic32x32_scalar"
         assert B.lib().fge_workspace_bytes(1, 1, 1, ctypes.byref(q)) == q.M * q.N * 4
         assert B.fge_fused_needs_finish(1, 1, q) is False
         assert _call(q) == 6
     assert B.lib().fge_workspace_bytes(1, 1, 0, ctypes.byref(_params(N=250, ldo=250))) == 0
+    # the fused tile kernels split rows of any width over column tiles (the row kernels on their
+    # own stop at 8192 columns); only beyond 8192 column strips per row the generic kernels take over
+    wide = _params(N=16384, ldo=16384)
+    assert B.fge_tile_name(True, 1, 1, wide) == "64x64_w2x2_splitbf16" and B.fge_fused_needs_finish(1, 1, wide)
+    assert B.lib().fge_workspace_bytes(1, 1, 1, ctypes.byref(wide)) == 128 * (256 * 2) * 8 and _call(wide) == 6
+    assert B.fge_tile_name(True, 1, 1, _params(N=1 << 21, ldo=1 << 21)) == "generic32x32_scalar"
     assert _call(_params(), norm=4) == 1                      # logsumexp without aux_out
     # split rows need a workspace
     p = _params(M=4096, N=1024, K=1024, ldx=1024, ldw=1024, ldo=1024)

@@ -228,8 +228,9 @@ def test_widest_row_and_smallest_problem(dt, norm):
 @pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (33, 17, 65), (100, 101, 250), (70, 63, 1001),
                                    (40, 72, 9000)])
 def test_any_shape_takes_the_element_granular_kernels(dt, shape):
-    """Extents that are not multiples of 16 bytes (and a row op over more than 8192 columns) are
-    computed by the element-granular kernels: every row op, both paths, against the oracle."""
+    """Extents that are not multiples of 16 bytes (and, in the unfused sequence, a row op over more
+    than 8192 columns) are computed by the element-granular kernels: every row op, both paths,
+    against the oracle."""
     M, K, N = shape
     for norm in NORMS:
         act = I.ACT_GELU_TANH if norm in (I.NORM_NONE, I.NORM_LAYERNORM) else I.ACT_CLAMP
@@ -241,7 +242,7 @@ def test_any_shape_takes_the_element_granular_kernels(dt, shape):
         t = I.generate(w)
         d = {k: H.to_device(v) for k, v in t.items()}
         p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(dt), device="cuda"))
-        if norm != I.NORM_NONE or N != 9000:
+        if N != 9000:          # (9000 columns: the fused path runs on tiles, the unfused K3 on the generic row kernel)
             assert B.fge_tile_name(True, act, norm, p) == "generic32x32_scalar"
         ref, raux = H.oracle_chain(w, t)
         for path in ("fused", "unfused"):
@@ -380,6 +381,36 @@ def test_stage_entry_points_compose_to_the_paths():
     torch.cuda.synchronize()
     unf, _ = H.run_gpu(w, t, "unfused", dev=d)
     assert np.array_equal(H.to_host_f64(o2), unf)
+
+
+# ---- rows wider than the register-resident row kernels hold (8192 columns): the fused tile kernels
+#      split them over column tiles like any other row (one-kernel and two-pass form); the unfused
+#      sequence finishes them with the element-granular row kernel
+@pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
+@pytest.mark.parametrize("case", [(I.BF16, 300, 136, 11008), (I.F32, 130, 72, 9000), (I.BF16, 2100, 64, 32000),
+                                  (I.F8E4M3, 520, 256, 8208)])
+def test_rows_wider_than_8192_columns(norm, case):
+    dt, M, K, N = case
+    w = I.Workload(name=f"wide{norm}", M=M, K=K, N=N, in_dtype=dt, out_dtype=I.BF16 if dt == I.F8E4M3 else dt,
+                   act=I.ACT_SILU, norm=norm, alpha=1.0 / K ** 0.5 if dt == I.F8E4M3 else 1.0, eps=1e-5,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 1.0 if dt == I.F8E4M3 else 1.0 / K ** 0.5),
+                         "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1), "beta": ("normal", 0.0, 0.1)})
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    ref, raux = H.oracle_chain(w, t)
+    for flags in (0, B.FLAG_TWO_PASS):
+        out = torch.empty(M, N, dtype=H.tdtype(w.out_dtype), device="cuda")
+        p = B.make_params(d["X"], d["W"], out, flags=flags)
+        assert B.fge_tile_name(True, w.act, norm, p) != "generic32x32_scalar"
+        got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
+        H.check(w, got, gaux, ref, raux, f"wide rows flags {flags}")
+    if M <= 600:                                       # (the element-granular row kernel is slow)
+        got, gaux = H.run_gpu(w, t, "unfused", dev=d)
+        tol = 8e-2 if w.out_dtype != I.F32 and norm in (I.NORM_SOFTMAX, I.NORM_LOGSUMEXP) else None
+        if tol is None:
+            H.check(w, got, gaux, ref, raux, "wide rows unfused")
+        else:                                          # 16-bit intermediates under a softmax, as elsewhere
+            assert np.isfinite(got).all() and H.C.max_rel_err(got, ref) <= tol
 
 
 # ---- few tiles, long K: the one-call fused entry point cuts K into slices (partial products in
