@@ -177,7 +177,13 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
     // cooperative form: the column tiles of a row block must all be in flight at once, so the
     // grid is a whole number of row blocks that fits the chip
     const int capacity = NUM_CU * ti.coop_per_cu;
-    pl.coop = pl.split && !two_pass && !(p->flags & FGE_FLAG_TWO_PASS) && tile_has_coop(pl.tile, p->in_dtype) && capacity >= pl.tiles_n;
+    // ... and not too many of them: every tile merges the pairs of all tiles of its rows, which
+    // grows with their number (125 column tiles, 2048 x 4096 x 32000: 626 us against 544 us for the
+    // second pass; equal at 64); logsumexp leaves `out` final in the first pass, so its second
+    // pass only writes aux and wins from 32 column tiles on
+    const int coop_max_tiles = norm == FGE_NORM_LOGSUMEXP ? 16 : 64;
+    pl.coop = pl.split && !two_pass && !(p->flags & FGE_FLAG_TWO_PASS) && tile_has_coop(pl.tile, p->in_dtype) &&
+              capacity >= pl.tiles_n && pl.tiles_n <= coop_max_tiles;
     if (pl.coop) {
         const int64_t total = (int64_t)pl.tiles_m * pl.tiles_n * pr.batch;
         const int64_t g = (int64_t)(capacity / pl.tiles_n) * pl.tiles_n;
@@ -479,10 +485,18 @@ int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream
 int launch_finish(const Plan &pl, int act, int norm, const fge_params *p, void *out, hipStream_t s) {
     const RowArgs r = row_args(out, out, act, norm, p, pl);
     const int64_t rows = (int64_t)r.batch * r.M;
-    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
-    if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((finish_kernel<bf16_t>), grid, block, 0, s, r);
-    else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((finish_kernel<f16_t>), grid, block, 0, s, r);
-    else                              hipLaunchKernelGGL((finish_kernel<float>), grid, block, 0, s, r);
+    const dim3 block(256);
+    if (r.N > MAX_ROWOP_N && rows <= INT32_MAX) {        // a wide row is shared by the four waves of a workgroup
+        const dim3 grid((unsigned)rows);
+        if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((finish_kernel<bf16_t, 4>), grid, block, 0, s, r);
+        else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((finish_kernel<f16_t, 4>), grid, block, 0, s, r);
+        else                              hipLaunchKernelGGL((finish_kernel<float, 4>), grid, block, 0, s, r);
+        return hip_status(hipGetLastError());
+    }
+    const dim3 grid((unsigned)((rows + 3) / 4));
+    if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((finish_kernel<bf16_t, 1>), grid, block, 0, s, r);
+    else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((finish_kernel<f16_t, 1>), grid, block, 0, s, r);
+    else                              hipLaunchKernelGGL((finish_kernel<float, 1>), grid, block, 0, s, r);
     return hip_status(hipGetLastError());
 }
 
@@ -532,6 +546,16 @@ int do_rownorm(const void *A, int norm, const fge_params *p, void *out, hipStrea
     if (!aligned16(A) || !aligned16(out)) return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
     if (!vectorisable(p, norm, false)) {
+        if (vectorisable(p, FGE_NORM_NONE, false) && (int64_t)p->M * p->batch <= INT32_MAX) {
+            // only the row's width stands in the way: one workgroup per row, passes over memory
+            const Plan pl = make_plan(p, norm);
+            const RowArgs r = row_args(A, out, FGE_ACT_NONE, norm, p, pl);
+            const dim3 grid((unsigned)((int64_t)r.batch * r.M)), block(256);
+            if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((rownorm_wide_kernel<bf16_t>), grid, block, 0, s, r);
+            else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((rownorm_wide_kernel<f16_t>), grid, block, 0, s, r);
+            else                              hipLaunchKernelGGL((rownorm_wide_kernel<float>), grid, block, 0, s, r);
+            return hip_status(hipGetLastError());
+        }
         GenArgs g = gen_args(p);
         g.X = A; g.ldx = p->ldo; g.bsx = g.bsd; g.dst = out; g.norm = norm;
         return hip_status(launch_generic_row(p->out_dtype, p->out_dtype, s, g));

@@ -255,18 +255,137 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
     }
 }
 
+// K3 for rows wider than rownorm_kernel's registers hold: one workgroup of four waves per row,
+// the row read from memory once per pass (two passes for RMSNorm, three for the others; a row
+// of this width sits in the L2 between the passes), 16 bytes per lane and step.  In place
+// (in == out) is fine: a thread only ever rewrites the chunks it read itself.
+template <typename T>
+__global__ __launch_bounds__(256) void rownorm_wide_kernel(const RowArgs a) {
+    constexpr int CW = Store<T>::CW;
+    __shared__ float red[2][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t rowg = blockIdx.x;
+    const int64_t off = (rowg / a.M) * a.bso + (rowg % a.M) * a.ldo;
+    const T *in = reinterpret_cast<const T *>(a.in) + off;
+    T *out = reinterpret_cast<T *>(a.out) + off;
+    const int cpr = a.N / CW;
+    const float inv_n = 1.0f / (float)a.N;
+    int turn = 0;
+    // reduction over the workgroup: waves first, then the four partial results through LDS
+    // (two alternating slots, so one barrier per reduction is enough)
+    auto block_reduce = [&]<typename Op>(Op, float v) __attribute__((always_inline)) {
+        v = allreduce64<Op>(v);
+        if (lane == 0) red[turn][wave] = v;
+        __syncthreads();
+        const float r = Op::f(Op::f(red[turn][0], red[turn][1]), Op::f(red[turn][2], red[turn][3]));
+        turn ^= 1;
+        return r;
+    };
+    auto load = [&](int q, float (&v)[CW]) __attribute__((always_inline)) {
+        Store<T>::unpack(*reinterpret_cast<const uint4 *>(in + (int64_t)q * CW), v);
+    };
+    auto store = [&](int q, const float (&v)[CW]) __attribute__((always_inline)) {
+        *reinterpret_cast<uint4 *>(out + (int64_t)q * CW) = Store<T>::pack(v);
+    };
+
+    if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
+        float m = OpMax::ident();
+        for (int q = tid; q < cpr; q += 256) {
+            float v[CW];
+            load(q, v);
+#pragma unroll
+            for (int e = 0; e < CW; ++e) m = max_nc(m, v[e]);
+        }
+        m = block_reduce(OpMax{}, m);
+        const float c = -m * LOG2E;
+        float s = 0.0f;
+        for (int q = tid; q < cpr; q += 256) {
+            float v[CW];
+            load(q, v);
+#pragma unroll
+            for (int e = 0; e < CW; ++e) s += exp_rel(v[e], c);
+        }
+        s = block_reduce(OpSum{}, s);
+        if (a.norm == FGE_NORM_LOGSUMEXP) {
+            if (tid == 0) a.aux[rowg] = m + __logf(s);
+            if (a.in != a.out)
+                for (int q = tid; q < cpr; q += 256)
+                    *reinterpret_cast<uint4 *>(out + (int64_t)q * CW) = *reinterpret_cast<const uint4 *>(in + (int64_t)q * CW);
+            return;
+        }
+        const float inv = fast_rcp(s);
+        for (int q = tid; q < cpr; q += 256) {
+            float v[CW];
+            load(q, v);
+#pragma unroll
+            for (int e = 0; e < CW; ++e) v[e] = exp_rel(v[e], c) * inv;
+            store(q, v);
+        }
+        return;
+    }
+    float shift = 0.0f, scale;
+    if (a.norm == FGE_NORM_LAYERNORM) {
+        float sm = 0.0f;
+        for (int q = tid; q < cpr; q += 256) {
+            float v[CW];
+            load(q, v);
+#pragma unroll
+            for (int e = 0; e < CW; ++e) sm += v[e];
+        }
+        shift = block_reduce(OpSum{}, sm) * inv_n;
+        float q2 = 0.0f;
+        for (int q = tid; q < cpr; q += 256) {
+            float v[CW];
+            load(q, v);
+#pragma unroll
+            for (int e = 0; e < CW; ++e) q2 += (v[e] - shift) * (v[e] - shift);
+        }
+        scale = rsqrtf(block_reduce(OpSum{}, q2) * inv_n + a.eps);
+    } else {                                              // FGE_NORM_RMSNORM
+        float q2 = 0.0f;
+        for (int q = tid; q < cpr; q += 256) {
+            float v[CW];
+            load(q, v);
+#pragma unroll
+            for (int e = 0; e < CW; ++e) q2 += v[e] * v[e];
+        }
+        scale = rsqrtf(block_reduce(OpSum{}, q2) * inv_n + a.eps);
+    }
+    const bool use_beta = a.norm == FGE_NORM_LAYERNORM && a.beta != nullptr;
+    for (int q = tid; q < cpr; q += 256) {
+        float v[CW];
+        load(q, v);
+#pragma unroll
+        for (int e4 = 0; e4 < CW; e4 += 4) {
+            float4 g = make_float4(1.f, 1.f, 1.f, 1.f), b = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (a.gamma) g = *reinterpret_cast<const float4 *>(a.gamma + q * CW + e4);
+            if (use_beta) b = *reinterpret_cast<const float4 *>(a.beta + q * CW + e4);
+            v[e4 + 0] = (v[e4 + 0] - shift) * scale * g.x + b.x;
+            v[e4 + 1] = (v[e4 + 1] - shift) * scale * g.y + b.y;
+            v[e4 + 2] = (v[e4 + 2] - shift) * scale * g.z + b.z;
+            v[e4 + 3] = (v[e4 + 3] - shift) * scale * g.w + b.w;
+        }
+        store(q, v);
+    }
+}
+
 // Second pass of the fused path for rows split over several column strips.  The tile kernel
 // left one pair per (row, strip) in the workspace - `tiles_n` strips of `bn` columns per row -
 // and the row itself parked in `out`; this kernel merges the pairs and finishes the row in
-// place.  One wavefront per row.  Merge rules:
+// place.  Merge rules:
 //   softmax / logsumexp: m = max_t m_t, s = sum_t s_t exp(m_t - m); parked e_t * exp(m_t - m)/s
 //   layernorm: mean = sum_t n_t mean_t / N, M2 = sum_t (M2_t + n_t (mean_t - mean)^2)
 //   rmsnorm:   sum of the per-strip sums of squares
-template <typename T>
+// WAVES = 1: one wavefront per row, four rows per workgroup.  WAVES = 4 (wide rows): the four
+// waves of a workgroup share one row - each merges the pairs for itself (they are few), the
+// elements are divided among all 256 threads.
+template <typename T, int WAVES>
 __global__ __launch_bounds__(256) void finish_kernel(const RowArgs a) {
     constexpr int CW = Store<T>::CW;
+    constexpr int TEAM = 64 * WAVES;                      // threads per row
     const int lane = threadIdx.x & 63;
-    const int64_t rowg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int member = WAVES == 1 ? lane : (int)threadIdx.x;
+    const int64_t rowg = WAVES == 1 ? (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6) : (int64_t)blockIdx.x;
     if (rowg >= (int64_t)a.batch * a.M) return;           // wave-uniform
     T *out = reinterpret_cast<T *>(a.out) + (rowg / a.M) * a.bso + (rowg % a.M) * a.ldo;
     const int cpr = a.N / CW;
@@ -282,11 +401,11 @@ __global__ __launch_bounds__(256) void finish_kernel(const RowArgs a) {
         for (int t = lane; t < S; t += 64) s += wr[t].y * fast_exp(wr[t].x - m);
         s = allreduce64<OpSum>(s);
         if (a.norm == FGE_NORM_LOGSUMEXP) {
-            if (lane == 0) a.aux[rowg] = m + __logf(s);
+            if (member == 0) a.aux[rowg] = m + __logf(s);
             return;
         }
         const float inv = fast_rcp(s);
-        for (int q = lane; q < cpr; q += 64) {
+        for (int q = member; q < cpr; q += TEAM) {
             const float f = fast_exp(wr[(q * CW) / SW].x - m) * inv;
             float v[CW];
             Store<T>::unpack(*reinterpret_cast<const uint4 *>(out + (int64_t)q * CW), v);
@@ -314,7 +433,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const RowArgs a) {
         scale = rsqrtf(allreduce64<OpSum>(ss) * inv_n + a.eps);
     }
     const bool use_beta = a.norm == FGE_NORM_LAYERNORM && a.beta != nullptr;
-    for (int q = lane; q < cpr; q += 64) {
+    for (int q = member; q < cpr; q += TEAM) {
         float v[CW];
         Store<T>::unpack(*reinterpret_cast<const uint4 *>(out + (int64_t)q * CW), v);
 #pragma unroll

@@ -385,7 +385,7 @@ def test_stage_entry_points_compose_to_the_paths():
 
 # ---- rows wider than the register-resident row kernels hold (8192 columns): the fused tile kernels
 #      split them over column tiles like any other row (one-kernel and two-pass form); the unfused
-#      sequence finishes them with the element-granular row kernel
+#      sequence finishes them with the workgroup-per-row kernel
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
 @pytest.mark.parametrize("case", [(I.BF16, 300, 136, 11008), (I.F32, 130, 72, 9000), (I.BF16, 2100, 64, 32000),
                                   (I.F8E4M3, 520, 256, 8208)])
@@ -404,7 +404,7 @@ def test_rows_wider_than_8192_columns(norm, case):
         assert B.fge_tile_name(True, w.act, norm, p) != "generic32x32_scalar"
         got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
         H.check(w, got, gaux, ref, raux, f"wide rows flags {flags}")
-    if M <= 600:                                       # (the element-granular row kernel is slow)
+    if True:
         got, gaux = H.run_gpu(w, t, "unfused", dev=d)
         tol = 8e-2 if w.out_dtype != I.F32 and norm in (I.NORM_SOFTMAX, I.NORM_LOGSUMEXP) else None
         if tol is None:
@@ -507,14 +507,16 @@ def test_k_split_other_operand_types(dt, act, norm):
 
 
 # ---- the standalone elementwise and row-operation kernels against the oracle's own functions:
-#      every row op x storage type x width (one chunk per lane up to the widest row, an odd width
-#      for the element-granular kernel), rows with a stride, several problems, in place
+#      every row op x storage type x width (one chunk per lane up to the widest row a wave holds,
+#      wider rows, an odd width for the element-granular kernel), rows with a stride, several problems, in place
 @pytest.mark.parametrize("dt", [I.F32, I.BF16, I.F16])
 @pytest.mark.parametrize("norm", [I.NORM_SOFTMAX, I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
 def test_standalone_row_operations(dt, norm):
     from oracle import compare as C
     from oracle import oracle as O
-    for (batch, M, N, pad) in [(1, 37, 8, 0), (1, 130, 520, 8), (2, 45, 4096, 0), (1, 9, 8192, 16), (1, 33, 77, 0)]:
+    # (past 8192 columns a workgroup per row walks the row in passes instead of a wave holding it)
+    for (batch, M, N, pad) in [(1, 37, 8, 0), (1, 130, 520, 8), (2, 45, 4096, 0), (1, 9, 8192, 16), (1, 33, 77, 0),
+                               (1, 5, 9000, 0), (2, 3, 8200, 8), (1, 3, 32000, 16)]:
         a = I.draw(5, "X", (batch * M, N), ("normal", 0.3, 1.5), dt)
         g = I.draw(5, "gamma", (N,), ("normal", 1.0, 0.1))
         be = I.draw(5, "beta", (N,), ("normal", 0.0, 0.1))
