@@ -127,7 +127,8 @@ def row_ops(torch, B, I, timed, log):
     for M, N, dt, norm, name in ((65536, 4096, torch.bfloat16, I.NORM_RMSNORM, "rmsnorm bf16"),
                                  (65536, 8192, torch.bfloat16, I.NORM_SOFTMAX, "softmax bf16"),
                                  (65536, 4096, torch.float32, I.NORM_LAYERNORM, "layernorm fp32"),
-                                 (262144, 512, torch.float32, I.NORM_LOGSUMEXP, "logsumexp fp32")):
+                                 (262144, 512, torch.float32, I.NORM_LOGSUMEXP, "logsumexp fp32"),
+                                 (8192, 32000, torch.bfloat16, I.NORM_SOFTMAX, "softmax bf16, 32000 columns")):
         A = [torch.randn(M, N, device="cuda").to(dt) for _ in range(2)]
         out = [torch.empty(M, N, device="cuda", dtype=dt) for _ in range(2)]
         g, be, aux = torch.ones(N, device="cuda"), torch.zeros(N, device="cuda"), torch.empty(M, device="cuda")

@@ -551,9 +551,16 @@ int do_rownorm(const void *A, int norm, const fge_params *p, void *out, hipStrea
             const Plan pl = make_plan(p, norm);
             const RowArgs r = row_args(A, out, FGE_ACT_NONE, norm, p, pl);
             const dim3 grid((unsigned)((int64_t)r.batch * r.M)), block(256);
-            if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((rownorm_wide_kernel<bf16_t>), grid, block, 0, s, r);
-            else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((rownorm_wide_kernel<f16_t>), grid, block, 0, s, r);
-            else                              hipLaunchKernelGGL((rownorm_wide_kernel<float>), grid, block, 0, s, r);
+            const size_t row_bytes = (size_t)r.N * esize(p->out_dtype);
+            if (row_bytes <= ((size_t)64 << 10) - 256) {     // the row fits LDS twice per CU: read memory once
+                if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((rownorm_wide_kernel<bf16_t, true>), grid, block, row_bytes, s, r);
+                else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((rownorm_wide_kernel<f16_t, true>), grid, block, row_bytes, s, r);
+                else                              hipLaunchKernelGGL((rownorm_wide_kernel<float, true>), grid, block, row_bytes, s, r);
+            } else {
+                if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((rownorm_wide_kernel<bf16_t, false>), grid, block, 0, s, r);
+                else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((rownorm_wide_kernel<f16_t, false>), grid, block, 0, s, r);
+                else                              hipLaunchKernelGGL((rownorm_wide_kernel<float, false>), grid, block, 0, s, r);
+            }
             return hip_status(hipGetLastError());
         }
         GenArgs g = gen_args(p);

@@ -256,13 +256,17 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const RowArgs a) {
 }
 
 // K3 for rows wider than rownorm_kernel's registers hold: one workgroup of four waves per row,
-// the row read from memory once per pass (two passes for RMSNorm, three for the others; a row
-// of this width sits in the L2 between the passes), 16 bytes per lane and step.  In place
+// the row read once per pass (two passes for RMSNorm, three for the others) - from memory, where
+// a row of this width sits in the L2 between the passes, or from LDS (CACHE) - 16 bytes per lane and step.  In place
 // (in == out) is fine: a thread only ever rewrites the chunks it read itself.
-template <typename T>
+// CACHE: the row (at most 64 KB) is kept in LDS as loaded, each thread parking the chunks it will
+// need again, so memory is read once; two such workgroups fit a CU.
+template <typename T, bool CACHE>
 __global__ __launch_bounds__(256) void rownorm_wide_kernel(const RowArgs a) {
     constexpr int CW = Store<T>::CW;
     __shared__ float red[2][4];
+    extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf_raw[];
+    uint4 *rowbuf = reinterpret_cast<uint4 *>(rowbuf_raw);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t rowg = blockIdx.x;
     const int64_t off = (rowg / a.M) * a.bso + (rowg % a.M) * a.ldo;
@@ -281,8 +285,15 @@ __global__ __launch_bounds__(256) void rownorm_wide_kernel(const RowArgs a) {
         turn ^= 1;
         return r;
     };
+    // first touch of a chunk (from memory; parked in LDS when cached) and later touches
+    auto load_first = [&](int q, float (&v)[CW]) __attribute__((always_inline)) {
+        const uint4 u = *reinterpret_cast<const uint4 *>(in + (int64_t)q * CW);
+        if constexpr (CACHE) rowbuf[q] = u;
+        Store<T>::unpack(u, v);
+    };
     auto load = [&](int q, float (&v)[CW]) __attribute__((always_inline)) {
-        Store<T>::unpack(*reinterpret_cast<const uint4 *>(in + (int64_t)q * CW), v);
+        if constexpr (CACHE) Store<T>::unpack(rowbuf[q], v);
+        else                 Store<T>::unpack(*reinterpret_cast<const uint4 *>(in + (int64_t)q * CW), v);
     };
     auto store = [&](int q, const float (&v)[CW]) __attribute__((always_inline)) {
         *reinterpret_cast<uint4 *>(out + (int64_t)q * CW) = Store<T>::pack(v);
@@ -290,15 +301,17 @@ __global__ __launch_bounds__(256) void rownorm_wide_kernel(const RowArgs a) {
 
     if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
         float m = OpMax::ident();
+#pragma unroll 4
         for (int q = tid; q < cpr; q += 256) {
             float v[CW];
-            load(q, v);
+            load_first(q, v);
 #pragma unroll
             for (int e = 0; e < CW; ++e) m = max_nc(m, v[e]);
         }
         m = block_reduce(OpMax{}, m);
         const float c = -m * LOG2E;
         float s = 0.0f;
+#pragma unroll 4
         for (int q = tid; q < cpr; q += 256) {
             float v[CW];
             load(q, v);
@@ -310,10 +323,12 @@ __global__ __launch_bounds__(256) void rownorm_wide_kernel(const RowArgs a) {
             if (tid == 0) a.aux[rowg] = m + __logf(s);
             if (a.in != a.out)
                 for (int q = tid; q < cpr; q += 256)
-                    *reinterpret_cast<uint4 *>(out + (int64_t)q * CW) = *reinterpret_cast<const uint4 *>(in + (int64_t)q * CW);
+                    *reinterpret_cast<uint4 *>(out + (int64_t)q * CW) =
+                        CACHE ? rowbuf[q] : *reinterpret_cast<const uint4 *>(in + (int64_t)q * CW);
             return;
         }
         const float inv = fast_rcp(s);
+#pragma unroll 4
         for (int q = tid; q < cpr; q += 256) {
             float v[CW];
             load(q, v);
@@ -326,14 +341,16 @@ __global__ __launch_bounds__(256) void rownorm_wide_kernel(const RowArgs a) {
     float shift = 0.0f, scale;
     if (a.norm == FGE_NORM_LAYERNORM) {
         float sm = 0.0f;
+#pragma unroll 4
         for (int q = tid; q < cpr; q += 256) {
             float v[CW];
-            load(q, v);
+            load_first(q, v);
 #pragma unroll
             for (int e = 0; e < CW; ++e) sm += v[e];
         }
         shift = block_reduce(OpSum{}, sm) * inv_n;
         float q2 = 0.0f;
+#pragma unroll 4
         for (int q = tid; q < cpr; q += 256) {
             float v[CW];
             load(q, v);
@@ -343,15 +360,17 @@ __global__ __launch_bounds__(256) void rownorm_wide_kernel(const RowArgs a) {
         scale = rsqrtf(block_reduce(OpSum{}, q2) * inv_n + a.eps);
     } else {                                              // FGE_NORM_RMSNORM
         float q2 = 0.0f;
+#pragma unroll 4
         for (int q = tid; q < cpr; q += 256) {
             float v[CW];
-            load(q, v);
+            load_first(q, v);
 #pragma unroll
             for (int e = 0; e < CW; ++e) q2 += v[e] * v[e];
         }
         scale = rsqrtf(block_reduce(OpSum{}, q2) * inv_n + a.eps);
     }
     const bool use_beta = a.norm == FGE_NORM_LAYERNORM && a.beta != nullptr;
+#pragma unroll 4
     for (int q = tid; q < cpr; q += 256) {
         float v[CW];
         load(q, v);
@@ -405,6 +424,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const RowArgs a) {
             return;
         }
         const float inv = fast_rcp(s);
+#pragma unroll 4
         for (int q = member; q < cpr; q += TEAM) {
             const float f = fast_exp(wr[(q * CW) / SW].x - m) * inv;
             float v[CW];
@@ -433,6 +453,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const RowArgs a) {
         scale = rsqrtf(allreduce64<OpSum>(ss) * inv_n + a.eps);
     }
     const bool use_beta = a.norm == FGE_NORM_LAYERNORM && a.beta != nullptr;
+#pragma unroll 4
     for (int q = member; q < cpr; q += TEAM) {
         float v[CW];
         Store<T>::unpack(*reinterpret_cast<const uint4 *>(out + (int64_t)q * CW), v);
