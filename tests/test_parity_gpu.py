@@ -404,6 +404,16 @@ def test_rows_wider_than_8192_columns(norm, case):
         assert B.fge_tile_name(True, w.act, norm, p) != "generic32x32_scalar"
         got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
         H.check(w, got, gaux, ref, raux, f"wide rows flags {flags}")
+    # the same through the stage entry points
+    out = torch.full((M, N), float("nan"), dtype=H.tdtype(w.out_dtype), device="cuda")
+    aux = torch.full((M,), float("nan"), device="cuda")
+    p = B.make_params(d["X"], d["W"], out, alpha=w.alpha, eps=w.eps, gamma=d["gamma"], beta=d["beta"], aux_out=aux)
+    ws = torch.empty(B.fge_workspace_bytes(True, w.act, norm, p), dtype=torch.uint8, device="cuda")
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+    B.fge_fused_tiles(d["X"], d["W"], d["b"], w.act, norm, p, out)
+    B.fge_fused_finish(w.act, norm, p, out)
+    torch.cuda.synchronize()
+    H.check(w, H.to_host_f64(out), H.to_host_f64(aux) if norm == I.NORM_LOGSUMEXP else None, ref, raux, "wide rows, stages")
     if True:
         got, gaux = H.run_gpu(w, t, "unfused", dev=d)
         tol = 8e-2 if w.out_dtype != I.F32 and norm in (I.NORM_SOFTMAX, I.NORM_LOGSUMEXP) else None
