@@ -263,8 +263,9 @@ def wide_rows(torch, B, I, timed, log):
             err = max(err, C.max_rel_err_vec(aux[idx].to(torch.float64).cpu().numpy(), raux))
         if not (err <= 2e-2):
             raise SystemExit(f"bench.py: wide-rows result off the oracle: {err:.3e}")
-        tf_ = timed(lambda i: B.fused_gemm_epilogue(X, W, b, w.act, w.norm, ps[i][0], out[i]), 20, 4)
-        tu_ = timed(lambda i: B.unfused_gemm_epilogue(X, W, b, w.act, w.norm, ps[i][0], out[i]), 10, 2)
+        # (the device has idled through the oracle's rows: a longer warm-up brings the clocks back)
+        tf_ = timed(lambda i: B.fused_gemm_epilogue(X, W, b, w.act, w.norm, ps[i][0], out[i]), 20, 20)
+        tu_ = timed(lambda i: B.unfused_gemm_epilogue(X, W, b, w.act, w.norm, ps[i][0], out[i]), 20, 20)
         res.append({"workload": f"logits + row {label}, bf16, M=2048 K=4096 N=32000",
                     "tile": B.fge_tile_name(True, w.act, w.norm, ps[0][0]), "ms_fused": round(tf_, 5),
                     "ms_unfused": round(tu_, 5), "tflops": round(w.flops / (tf_ * 1e-3) / 1e12, 2),
