@@ -97,9 +97,11 @@ typedef enum {
  *   (a bounded wait).  That form assumes the launch has the device to itself; set this flag when
  *   several launches may overlap on the device (other streams, other processes).  Before such a
  *   launch the library asks the runtime whether the device holds the whole grid at once; if it
- *   does not, fused_gemm_epilogue and fused_gated_gemm_epilogue take the two-pass form by
- *   themselves, while fge_fused_tiles - whose caller decides about the second pass from
- *   fge_fused_needs_finish - returns FGE_ERR_HIP.
+ *   does not, the two-pass form is taken.  A tile whose wait runs out all the same (its row block's
+ *   other tiles did not arrive within about 2^20 polls) stores NaN for its rows - and NaN in
+ *   aux_out for LOGSUMEXP - and sets the fault word (fge_fault_word_offset): the kernel always
+ *   terminates and never stores values normalised with incomplete statistics.  The stage entry
+ *   points fge_fused_tiles / fge_fused_finish always take the two-pass form.
  *   FGE_FLAG_IEEE_FP32 : multiply fp32 operands with the fp32 matrix instruction.  Without it
  *   fp32 operands are multiplied on the bf16 matrix instruction after a split of each operand
  *   into two bf16 terms, x = xh + xl:  x*w ~= xl*wh + xh*wl + xh*wh with fp32 accumulation.
@@ -118,8 +120,13 @@ typedef enum {
  *   the library's own choice - for tuning and tests.  A configuration without kernels for the
  *   operand type (or the narrow-K kernel outside K <= 64, N <= 512, fp32) yields
  *   FGE_ERR_UNSUPPORTED.  Ignored by the gated form and by shapes that take the element-granular
- *   kernels. */
-enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_NO_SPLIT_K = 4, FGE_FLAG_TILE_MASK = 0xF00 };
+ *   kernels.
+ *   FGE_FLAG_TEST_EXPIRE_WAIT : for tests of the bounded wait only.  In the one-kernel form the
+ *   first column tile of every row block keeps its arrival mark back and every wait gives up
+ *   after one poll, so the waits run out while every workgroup still finishes normally; the
+ *   affected rows must come back as NaN and the fault word set. */
+enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_NO_SPLIT_K = 4, FGE_FLAG_TILE_MASK = 0xF00,
+       FGE_FLAG_TEST_EXPIRE_WAIT = 0x1000 };
 #define FGE_FLAG_TILE(t) ((((int)(t)) + 1) << 8)
 
 /* Tile configurations (rows x columns of one workgroup's output tile).  16-bit and 8-bit
@@ -167,10 +174,10 @@ int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act,
 size_t fge_workspace_bytes(int fused, int act, int norm, const fge_params *p);
 
 /* Where the one-kernel form of split rows reports a wait that ran out: byte offset into the
- * workspace of an int32 that such a launch sets to 1 (it never clears it; the result of that
- * launch is then invalid).  (size_t)-1 when fused_gemm_epilogue does not take that form for
- * these arguments.  A caller that wants the check clears the word before the call and reads it
- * after synchronising. */
+ * workspace of an int32 that such a launch sets to 1 (it never clears it; the rows of the tiles
+ * whose wait ran out are stored as NaN).  (size_t)-1 when fused_gemm_epilogue does not take that
+ * form for these arguments.  A caller that wants the check clears the word before the call and
+ * reads it after synchronising; a caller that does not will still find the NaN rows. */
 size_t fge_fault_word_offset(int act, int norm, const fge_params *p);
 
 /* ---- the gated form (the "SiLU-and-Mul" / "GELU-and-Mul" fused operators of the paper's
@@ -202,13 +209,16 @@ const char *fge_gated_tile_name(int act, int norm, const fge_params *p);
 
 /* ---- the individual stages, callable on their own (the two paths above are built from them) */
 
-/* Fused stage 1: the tile kernel.  When the chosen tile spans N it produces the final out. */
+/* Fused stage 1: the tile kernel, always in the two-pass form.  When the chosen tile spans N it
+ * produces the final out; otherwise the tiles park their values in out and publish per-strip row
+ * statistics to the workspace (split rows, paper Fig. 2: statistics first, normalise second). */
 int fge_fused_tiles(const void *X, const void *W, const float *b, int act, int norm,
                     const fge_params *p, void *out, void *stream);
 /* Fused stage 2: merge per-tile row statistics from the workspace and finish `out` in place.
  * A no-op (FGE_OK, nothing enqueued) when stage 1 already produced the final result. */
 int fge_fused_finish(int act, int norm, const fge_params *p, void *out, void *stream);
-/* 1 if fge_fused_finish has work to do for these arguments, 0 if not, negative on bad args. */
+/* 1 if fge_fused_finish has work to do for these arguments, 0 if not, negative on bad args.
+ * Depends on the arguments only (not on the stream or the device). */
 int fge_fused_needs_finish(int act, int norm, const fge_params *p);
 /* Slices of K that fused_gemm_epilogue cuts these arguments into when the workspace has the
  * room (1: none; see FGE_FLAG_NO_SPLIT_K), negative on bad args.  The stage entry points

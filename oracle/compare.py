@@ -22,7 +22,8 @@ def max_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     if ref.size == 0:
         return 0.0
     den = np.maximum(np.abs(ref), row_floor(ref))
-    return float(np.max(np.abs(got - ref) / den))
+    e = np.abs(got - ref) / den
+    return float("nan") if np.isnan(e).any() else float(np.max(e))     # (callers gate with err <= tol: NaN fails)
 
 
 def max_rel_err_vec(got: np.ndarray, ref: np.ndarray) -> float:
@@ -44,4 +45,4 @@ def verifier_fraction(got: np.ndarray, ref: np.ndarray, tau: float) -> float:
     eps = np.broadcast_to(row_floor(ref), ref.shape)
     big = np.abs(ref) > eps
     e = np.where(big, np.abs(got - ref) / np.where(big, np.abs(ref), 1.0), np.abs(got - ref))
-    return float(np.mean(e > tau))
+    return float(np.mean(~(e <= tau)))          # a NaN error counts as a failure

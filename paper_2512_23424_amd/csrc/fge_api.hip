@@ -19,7 +19,18 @@ thread_local int g_last_hip = 0;
 std::atomic<unsigned> g_generation{
     (unsigned)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
 
-constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 CUs
+// Compute units of the current device, asked once (MI355X: 8 XCDs x 32 = 256, which is also the
+// answer where no device can be asked - the planning functions are callable without one).
+int num_cu() {
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        return cus;
+    }();
+    return n;
+}
+constexpr unsigned WAIT_POLLS = 1u << 20;   // polls after which a tile stops waiting for its row block
 constexpr int MAX_ROWOP_N = 8192;    // a row must fit the register-resident row kernels
 constexpr int MAX_SPLIT = 8192;      // column strips per row the second pass will merge (wider rows: element-granular kernels)
 
@@ -76,7 +87,8 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
     if (p == nullptr) return FGE_ERR_NULL;
     if (act < FGE_ACT_NONE || act > FGE_ACT_CLAMP) return FGE_ERR_BAD_ENUM;
     if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
-    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32 | FGE_FLAG_NO_SPLIT_K | FGE_FLAG_TILE_MASK)) return FGE_ERR_BAD_ENUM;
+    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32 | FGE_FLAG_NO_SPLIT_K | FGE_FLAG_TILE_MASK | FGE_FLAG_TEST_EXPIRE_WAIT))
+        return FGE_ERR_BAD_ENUM;
     if (!forced_tile_ok(p)) return FGE_ERR_UNSUPPORTED;
     if (p->in_dtype < FGE_F32 || p->in_dtype > FGE_F8E4M3 || p->out_dtype < FGE_F32 || p->out_dtype > FGE_F8E4M3)
         return FGE_ERR_BAD_ENUM;
@@ -134,24 +146,24 @@ int pick_tile(const Problem &pr, int in_dtype, int /*norm*/, bool ieee_fp32) {
         // 128x128 tiles (split product only) once there is one for every CU: a third less operand
         // traffic from the L2s than 64x128 tiles - fp32 operands make the staging, not the MFMAs,
         // the bound of these kernels
-        if (!ieee_fp32 && fits(TILE_128x128) && count(TILE_128x128) >= NUM_CU) return TILE_128x128;
+        if (!ieee_fp32 && fits(TILE_128x128) && count(TILE_128x128) >= num_cu()) return TILE_128x128;
         // fp32 instruction, very large problems: the wide tile halves the operand traffic per flop
-        if (ieee_fp32 && fits(TILE_64x512) && pr.K >= 1024 && count(TILE_64x512) >= 2 * NUM_CU) return TILE_64x512;
+        if (ieee_fp32 && fits(TILE_64x512) && pr.K >= 1024 && count(TILE_64x512) >= 2 * num_cu()) return TILE_64x512;
         // otherwise 64x128 tiles, two or three of which share a CU so that one's epilogue hides
         // behind another's MFMAs
         // (given at least two per CU; with fewer, 64x64 tiles fill the chip better)
-        return fits(TILE_64x128) && count(TILE_64x128) >= 2 * NUM_CU ? TILE_64x128 : TILE_64x64;
+        return fits(TILE_64x128) && count(TILE_64x128) >= 2 * num_cu() ? TILE_64x128 : TILE_64x64;
     }
     // 16- and 8-bit operands: 256x256 tiles once every CU has one - and already from half the CUs
     // on when the 128x128 tiles (two workgroups per CU) would need a second round: measured 1.2-1.4
     // times faster there (160 and 192 tiles at K = 512 and 4096), 0.8-0.9 times at 128 tiles
-    if (fits(TILE_256x256) && (count(TILE_256x256) >= NUM_CU ||
-                               (2 * count(TILE_256x256) > NUM_CU && count(TILE_128x128) > 2 * NUM_CU)))
+    if (fits(TILE_256x256) && (count(TILE_256x256) >= num_cu() ||
+                               (2 * count(TILE_256x256) > num_cu() && count(TILE_128x128) > 2 * num_cu())))
         return TILE_256x256;
     // 128x128 tiles from 5/8 of the CUs on: one round of them (three stage buffers, see tile_args)
     // then beats the 64x64 tiles' several (640 x 4096 x 4096: 48.5 against 58.3 us; at 512 rows,
     // 128 tiles, the 64x64 tiles still win with 38 us)
-    if (fits(TILE_128x128) && count(TILE_128x128) * 8 >= NUM_CU * 5) return TILE_128x128;
+    if (fits(TILE_128x128) && count(TILE_128x128) * 8 >= num_cu() * 5) return TILE_128x128;
     return TILE_64x64;
 }
 
@@ -176,7 +188,7 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
     pl.split = norm != FGE_NORM_NONE && pl.tiles_n > 1;
     // cooperative form: the column tiles of a row block must all be in flight at once, so the
     // grid is a whole number of row blocks that fits the chip
-    const int capacity = NUM_CU * ti.coop_per_cu;
+    const int capacity = num_cu() * ti.coop_per_cu;
     // ... and not too many of them: every tile merges the pairs of all tiles of its rows, which
     // grows with their number (125 column tiles, 2048 x 4096 x 32000: 626 us against 544 us for the
     // second pass; equal at 64); logsumexp leaves `out` final in the first pass, so its second
@@ -233,12 +245,12 @@ KSplit k_split(const fge_params *p, int norm, const Plan &pl) {
     // the 64x64 kernel of the 16- and 8-bit operands and of the fp32 instruction keeps three K tiles
     // in flight and walks K faster than the split-product kernel: slices pay later there
     const bool deep = !(p->in_dtype == FGE_F32 && !(p->flags & FGE_FLAG_IEEE_FP32));
-    const int k_min = !deep ? 2048 : tiles * 2 > NUM_CU ? 8192 : 4096;
-    if (tiles > NUM_CU || pl.pr.K < k_min) return ks;
+    const int k_min = !deep ? 2048 : tiles * 2 > num_cu() ? 8192 : 4096;
+    if (tiles > num_cu() || pl.pr.K < k_min) return ks;
     const size_t one = round256((size_t)pl.pr.M * pl.pr.N * sizeof(float));
     int S = 1;
     for (int c = 2; c <= 16; c *= 2)
-        if (tiles * c <= 2 * NUM_CU && pl.pr.K % (c * 128) == 0 && pl.pr.K / c >= 512 && one * c <= ((size_t)32 << 20)) S = c;
+        if (tiles * c <= 2 * num_cu() && pl.pr.K % (c * 128) == 0 && pl.pr.K / c >= 512 && one * c <= ((size_t)32 << 20)) S = c;
     if (S == 1) return ks;
     ks.slices = S;
     ks.ws_part = one * S;
@@ -315,7 +327,7 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
     // 16- and 8-bit 128x128 tiles, no more of them than CUs: no second workgroup shares a CU, so
     // the variant with three stage buffers hides the copy latency instead
     a.deep = pl.tile == TILE_128x128 && p->in_dtype != FGE_F32 &&
-             (int64_t)pl.tiles_m * pl.tiles_n * pl.pr.batch <= NUM_CU;
+             (int64_t)pl.tiles_m * pl.tiles_n * pl.pr.batch <= num_cu();
     a.coop = 0;
     if (pl.coop && norm != FGE_NORM_NONE) {
         char *base = static_cast<char *>(p->workspace) + pl.ws_stats;
@@ -323,13 +335,16 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
         a.gen = g_generation.fetch_add(1) + 1;
         a.arrive = reinterpret_cast<unsigned *>(base);
         a.fault = reinterpret_cast<int *>(base + pl.ws_marks - 256);
+        const bool expire = (p->flags & FGE_FLAG_TEST_EXPIRE_WAIT) != 0;
+        a.spin_limit = expire ? 1u : WAIT_POLLS;
+        a.withhold = expire ? 1 : 0;
     }
     return a;
 }
 
 int launch_tiles(const TileArgs &a, const fge_params *p, const Plan &pl, hipStream_t s) {
     if (pl.tile == TILE_PANEL) {
-        const dim3 pgrid((unsigned)(pl.tiles_m < NUM_CU ? pl.tiles_m : NUM_CU));
+        const dim3 pgrid((unsigned)(pl.tiles_m < num_cu() ? pl.tiles_m : num_cu()));
         return hip_status(launch_panel_f32(p->out_dtype, pgrid, s, a));
     }
     const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
@@ -418,10 +433,13 @@ int run_k_split(const void *X, const void *W, const float *b, int act, int norm,
     return finish_partials(part, nullptr, b, nullptr, act, norm, p, pl, S, slice, part + ks.ws_part, out, s);
 }
 
-// one_call (the caller runs a second pass, if any, from the plan returned here - not the stage
-// entry points, whose callers decide from fge_fused_needs_finish): if the device cannot hold the
-// cooperative grid (the launcher refuses it before anything runs), take the two-pass form
-// instead; and take the K-split where it pays and the workspace has the room.
+// one_call: fused_gemm_epilogue, which runs the second pass, if any, from the plan returned here.
+// It may finish split rows inside the tile kernel (cooperative form; if the device cannot hold
+// that grid the launcher refuses it before anything runs and the two-pass form is taken) and cut
+// K into slices where that pays and the workspace has the room.  The stage entry points
+// (fge_fused_tiles, then fge_fused_finish) are two passes by definition: they always plan the
+// two-pass form, whatever the stream or the device, so both stages and fge_fused_needs_finish
+// agree without knowing about each other.
 int do_fused_tiles(const void *X, const void *W, const float *b, int act, int norm,
                    const fge_params *p, void *out, hipStream_t s, Plan *plan_out, bool one_call = false) {
     int rc = check_common(p, act, norm, true);
@@ -429,7 +447,7 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
     if (!X || !W || !out) return FGE_ERR_NULL;
     if (!aligned16(X) || !aligned16(W) || !aligned16(out) || !aligned16(b)) return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
-    const Plan pl = make_plan(p, norm, capturing(s));
+    const Plan pl = make_plan(p, norm, !one_call || capturing(s));
     if (plan_out) *plan_out = pl;
     if (pl.generic) {
         // GEMM + activation straight into out, or into an fp32 rows x N intermediate that the row
@@ -475,7 +493,7 @@ int do_fused_finish(int act, int norm, const fge_params *p, void *out, hipStream
     if (!out) return FGE_ERR_NULL;
     if (!aligned16(out)) return FGE_ERR_ALIGN;
     if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
-    const Plan pl = make_plan(p, norm, capturing(s));
+    const Plan pl = make_plan(p, norm, true);
     if (!pl.needs_finish) return FGE_OK;
     if (pl.strips > MAX_SPLIT) return FGE_ERR_UNSUPPORTED;
     if (!p->workspace || p->workspace_bytes < split_rows_workspace(p, norm)) return FGE_ERR_WORKSPACE;
@@ -531,7 +549,7 @@ int do_act(const void *Y, int act, const fge_params *p, void *A, hipStream_t s, 
     const int cw = p->out_dtype == FGE_F32 ? 4 : 8;
     const int64_t chunks = (int64_t)r.batch * r.M * (r.N / cw);
     int64_t blocks = (chunks + 255) / 256;
-    if (blocks > NUM_CU * 32) blocks = NUM_CU * 32;      // grid-stride beyond that
+    if (blocks > num_cu() * 32) blocks = num_cu() * 32;      // grid-stride beyond that
     const dim3 grid((unsigned)blocks), block(256);
     if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((act_kernel<bf16_t>), grid, block, 0, s, r);
     else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((act_kernel<f16_t>), grid, block, 0, s, r);
@@ -594,7 +612,7 @@ int fge_fused_finish(int act, int norm, const fge_params *p, void *out, void *st
 int fge_fused_needs_finish(int act, int norm, const fge_params *p) {
     const int rc = check_common(p, act, norm, true);
     if (rc) return -rc;
-    return make_plan(p, norm).needs_finish ? 1 : 0;
+    return make_plan(p, norm, true).needs_finish ? 1 : 0;
 }
 
 int fge_fused_k_slices(int act, int norm, const fge_params *p) {
@@ -688,7 +706,7 @@ GatedSmall gated_small(const fge_params *p, int norm) {
     const int64_t gated_tiles = (int64_t)((pl.pr.M + gt.bm - 1) / gt.bm) * ((pl.pr.N + gt.bn - 1) / gt.bn);
     // from about 96 of its tiles on the gated kernel is the faster one, and so it is when one plain
     // product alone has more 64x64 tiles than two per CU (256 x 4096 x 11008: 86 against 117 us)
-    if (gated_tiles * 8 > NUM_CU * 3 || pl.tile != TILE_64x64 || (int64_t)pl.tiles_m * pl.tiles_n > 2 * NUM_CU) return g;
+    if (gated_tiles * 8 > num_cu() * 3 || pl.tile != TILE_64x64 || (int64_t)pl.tiles_m * pl.tiles_n > 2 * num_cu()) return g;
     g.ks = k_split(p, norm, pl);
     if (g.ks.slices == 1) {
         const size_t one = round256((size_t)pl.pr.M * pl.pr.N * sizeof(float));

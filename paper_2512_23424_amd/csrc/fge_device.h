@@ -29,7 +29,9 @@ __device__ __forceinline__ uint32_t as_u32(float v) { return __builtin_bit_cast(
 // Written in assembly on purpose: for the builtin form the compiler assumes that every later
 // LDS read may alias the copy and drains the vector-memory counter in front of it, which turns
 // a prefetch into a synchronous load.  m0 is not used by any compiler-generated code of these
-// kernels (no other LDS-direct, GWS or indexed-register instruction is emitted).
+// kernels (no other LDS-direct, GWS or indexed-register instruction is emitted).  It cannot be
+// declared as clobbered: the compiler treats m0 as a reserved register and rejects it on the
+// clobber list with a warning that the entry has no effect.
 __device__ __forceinline__ void lds_dma16(const void *g, void *lds_base) {
     typedef __attribute__((address_space(3))) void *lptr_t;
     const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)lds_base);

@@ -44,7 +44,9 @@ struct TileArgs {
     int coop;
     unsigned gen;               // value that marks "arrived" in this launch
     unsigned *arrive;           // [batch * tiles_m][tiles_n] arrival marks
-    int *fault;                 // set to 1 if a wait ran out (result then invalid)
+    int *fault;                 // set to 1 if a wait ran out (the rows of that tile are then stored as NaN)
+    unsigned spin_limit;        // polls after which a wait gives up
+    int withhold;               // tests only: column tile 0 never marks itself as arrived
 };
 
 // OutT: storage type of out.  MB x NB: 32x32 accumulator blocks per wave.  WAVES_N: waves
@@ -455,32 +457,40 @@ struct TileEpilogue {
     }
 
     // step 3.  Only correct when all tiles of the row block are in flight at once (the caller's
-    // persistent grid guarantees it); the wait is bounded all the same, and a wait that runs
-    // out raises the fault flag instead of hanging.
-    __device__ __forceinline__ void arrive_and_wait(int rowblock, int tid) {
+    // persistent grid guarantees it); the wait is bounded all the same.  A wait that runs out
+    // raises the fault word and is reported to the whole workgroup (return value false), which
+    // then stores NaN for its rows instead of values normalised with incomplete statistics: the
+    // kernel still terminates and the result cannot be mistaken for a valid one.
+    __device__ __forceinline__ bool arrive_and_wait(int rowblock, int tid) {
         // the pair stores are device-scope atomics: once the store counter has drained they are
         // visible to the whole device, and the barrier orders every wave's drain before the mark
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        __syncthreads();                                        // (also: the strip pairs in xch are consumed)
         unsigned *marks = a.arrive + (int64_t)rowblock * a.tiles_n;
-        if (tid == 0) __hip_atomic_store(marks + tn, a.gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // (withhold: host-side tests make the waits of a row block run out by keeping back the
+        // mark of its first column tile)
+        if (tid == 0 && !(a.withhold && tn == 0))
+            __hip_atomic_store(marks + tn, a.gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (tid < 64) {
             bool ok = true;
             for (int t = tid; t < a.tiles_n; t += 64) {
-                int spins = 0;
+                unsigned spins = 0;
                 while (__hip_atomic_load(marks + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.gen) {
                     __builtin_amdgcn_s_sleep(8);
-                    if (++spins > (1 << 20)) { ok = false; break; }
+                    if (++spins > a.spin_limit) { ok = false; break; }
                 }
             }
+            const bool all_ok = __all(ok);
             if (!ok) *a.fault = 1;
+            if (tid == 0) xch[0].x = all_ok ? 0.0f : __builtin_nanf("");
         }
         __syncthreads();                                        // pairs are read with device-scope loads
+        return xch[0].x == 0.0f;
     }
 
     // step 4: TPR neighbouring threads per tile row; the result lands in fin[row]:
     // (m, 1/s) softmax, (mean, rstd) LayerNorm, (rstd, -) RMSNorm; logsumexp writes aux.
-    template <int TPR> __device__ __forceinline__ void merge_tiles(int tid, float2 *fin) {
+    template <int TPR> __device__ __forceinline__ void merge_tiles(int tid, float2 *fin, bool waited_ok) {
         const int row = tid / TPR, part = tid % TPR;
         const int grow = m0 + row;
         const float2 *pr = a.ws + (row_base + min(grow, a.M - 1)) * a.tiles_n;
@@ -506,7 +516,7 @@ struct TileEpilogue {
             o0 = allreduce_lanes<OpMax, TPR>(m);
             const float sden = allreduce_lanes<OpSum, TPR>(m == OpMax::ident() ? 0.0f : sum * fast_exp(m - o0));
             if (a.norm == FGE_NORM_SOFTMAX) o1 = fast_rcp(sden);
-            else if (part == 0 && tn == 0 && grow < a.M) a.aux[row_base + grow] = o0 + __logf(sden);
+            else if (part == 0 && tn == 0 && grow < a.M) a.aux[row_base + grow] = waited_ok ? o0 + __logf(sden) : __builtin_nanf("");
         } else if (a.norm == FGE_NORM_LAYERNORM) {
             // two sweeps over the pairs: the mean first, then M2 about it
             const float inv_n = 1.0f / (float)a.N;
@@ -545,6 +555,7 @@ struct TileEpilogue {
             }
             o0 = rsqrtf(allreduce_lanes<OpSum, TPR>(ss) / (float)a.N + a.eps);
         }
+        if (!waited_ok) o0 = o1 = __builtin_nanf("");          // statistics incomplete: the rows become NaN
         if (part == 0) fin[row] = make_float2(o0, o1);
     }
 
@@ -604,9 +615,9 @@ struct TileEpilogue {
             load_affine<FULL_TILE>(gam, bet);
             __syncthreads();
             if (tid < tile_rows) merge_strips(tid);
-            arrive_and_wait(rowblock, tid);
+            const bool waited_ok = arrive_and_wait(rowblock, tid);
             float2 *fin = xch + tile_rows * WAVES_N;
-            merge_tiles<NT / (MB * 32 * (NT / 64 / WAVES_N))>(tid, fin);
+            merge_tiles<NT / (MB * 32 * (NT / 64 / WAVES_N))>(tid, fin, waited_ok);
             if (a.norm == FGE_NORM_LOGSUMEXP) return;
             __syncthreads();
             static_for<0, MB / G>([&]<int g>() __attribute__((always_inline)) {

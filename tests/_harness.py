@@ -44,7 +44,7 @@ def oracle_chain(w: I.Workload, t: Dict[str, Optional[np.ndarray]]):
 
 def run_gpu(w: I.Workload, t: Dict[str, Optional[np.ndarray]], path: str = "fused",
             dev: Optional[Dict[str, torch.Tensor]] = None, batched_call: bool = True,
-            flags: int = 0) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+            flags: int = 0, expect_fault: bool = False) -> Tuple[np.ndarray, Optional[np.ndarray]]:
     """One call of the fused or unfused path on freshly NaN-poisoned outputs."""
     d = dev if dev is not None else {k: to_device(v) for k, v in t.items()}
     X = d["X"]
@@ -62,8 +62,17 @@ def run_gpu(w: I.Workload, t: Dict[str, Optional[np.ndarray]], path: str = "fuse
     ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * 4
     fn = B.fused_gemm_epilogue if path == "fused" else B.unfused_gemm_epilogue
+    # one-kernel form of split rows: clear the word that reports a wait that ran out, check it after
+    off = B.fge_fault_word_offset(w.act, w.norm, p) if path == "fused" else None
+    fault = ws.view(torch.int32)[off // 4: off // 4 + 1] if off is not None and off + 4 <= ws.numel() * 4 else None
+    if fault is not None:
+        fault.zero_()
     fn(X, d["W"], d["b"], w.act, w.norm, p, out)
     torch.cuda.synchronize()
+    if fault is not None and not expect_fault:
+        assert int(fault.item()) == 0, "a tile's wait for its row block ran out"
+    if expect_fault:
+        assert fault is not None and int(fault.item()) == 1, "the fault word was not set"
     o = to_host_f64(out).reshape(rows, w.N)
     return o, None if aux is None else to_host_f64(aux)
 

@@ -123,8 +123,12 @@ def test_status_strings_and_tile_names():
     assert B.fge_tile_name(True, 2, 2, huge) == "64x512_w1x4"
     big = _params(M=8192, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, in_dtype=1, out_dtype=1)
     assert B.fge_tile_name(True, 4, 3, big) == "256x256_w2x4"
-    assert B.fge_fused_needs_finish(4, 3, big) is False      # the tiles finish their rows themselves
+    # the one-call entry point lets the tiles of this problem finish their rows themselves (it has a
+    # fault word); the stage entry points always take two passes, whatever the flags
+    assert B.fge_fault_word_offset(4, 3, big) is not None
+    assert B.fge_fused_needs_finish(4, 3, big) is True
     big.flags = B.FLAG_TWO_PASS
+    assert B.fge_fault_word_offset(4, 3, big) is None
     assert B.fge_fused_needs_finish(4, 3, big) is True
     small = _params(M=300, N=1024, K=256, ldx=256, ldw=256, ldo=1024)
     assert B.fge_fused_needs_finish(2, 2, small) is True     # small problems keep the second pass

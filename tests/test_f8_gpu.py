@@ -28,7 +28,7 @@ def _wl(M, K, N, act, norm, out_dtype, **kw):
 def _tile(w, t=None, flags=0):
     d = {k: H.to_device(v) for k, v in (t or I.generate(w)).items()}
     p = B.make_params(d["X"], d["W"], torch.empty(w.rows, w.N, dtype=H.tdtype(w.out_dtype), device="cuda"), flags=flags)
-    return B.fge_tile_name(True, w.act, w.norm, p), B.fge_fused_needs_finish(w.act, w.norm, p)
+    return B.fge_tile_name(True, w.act, w.norm, p), B.fge_fault_word_offset(w.act, w.norm, p) is None and B.fge_fused_needs_finish(w.act, w.norm, p)
 
 
 @pytest.mark.parametrize("shape", [(64, 64, 64), (96, 128, 160), (200, 80, 328), (300, 1024, 520)])

@@ -88,7 +88,8 @@ def test_gated_fp32_and_odd_extents_take_the_sequence():
 
 def test_gated_exact_integers_and_fp32_result():
     """Small integers: both products are exact, so with no activation the gate's product must
-    match the oracle bit for bit (fp32 result of bf16 operands)."""
+    match the oracle bit for bit (fp32 result of bf16 operands) - on the fused kernel and on the
+    unfused sequence, whose intermediates are fp32 here and therefore exact as well."""
     w = I.Workload(name="gint", M=260, K=72, N=136, in_dtype=I.BF16, out_dtype=I.F32,
                    dist={"X": ("int", -2, 2), "W": ("int", -2, 2), "b": ("int", -3, 3)})
     t = I.generate_gated(w)
@@ -96,8 +97,7 @@ def test_gated_exact_integers_and_fp32_result():
     ref, _ = _oracle(w, t)
     for path in ("fused", "unfused"):
         got, _, _ = _run(w, d, path)
-        if path == "fused":
-            assert np.array_equal(got, ref)
+        assert np.array_equal(got, ref), path
 
 
 def test_gated_fp32_keeps_the_fp32_gate():

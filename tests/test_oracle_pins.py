@@ -377,3 +377,13 @@ def test_metrics_by_hand():
     assert C.verifier_fraction(got, ref, 5e-4) == 0.75
     assert C.verifier_fraction(got, ref, 2e-3) == 0.0
     assert abs(C.max_rel_err_vec(np.array([2.02]), np.array([2.0])) - 0.01) < 1e-12
+
+
+def test_metrics_count_a_missing_value_as_a_failure():
+    """An element that is NaN has no error below any threshold: both gates must fail on it
+    (the pass rule of the paper's Section 3.2.3 counts the elements that do NOT meet tau)."""
+    ref = np.array([[1.0, -1.0, 0.0, 2.0]])
+    got = ref.copy()
+    got[0, 2] = np.nan
+    assert not (C.max_rel_err(got, ref) <= 1e-4)
+    assert C.verifier_fraction(got, ref, 1e-3) == 0.25
