@@ -167,6 +167,28 @@ int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, i
 int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
                           const fge_params *p, void *out, void *stream);
 
+/* ---- for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it): fused_gemm_epilogue with the library's own scratch in
+ * place of the caller's workspace.  p->workspace and p->workspace_bytes are ignored; the row
+ * statistics of split rows (and, when they fit as well, the partial products of the optional K
+ * slices) live in a static device array of FGE_STATIC_SCRATCH_BYTES that is part of the library's
+ * code object: every GPU the library runs on holds one copy until the process ends.  The call
+ * allocates and frees nothing and, like every other entry point, only enqueues kernels (no memset
+ * node; the scratch needs no clearing between calls).  Arguments, results and errors are those of
+ * fused_gemm_epilogue, with two additions: a problem whose split-row statistics (or, for shapes
+ * on the element-granular kernels, whose fp32 intermediate) exceed the array returns
+ * FGE_ERR_WORKSPACE before anything is enqueued - fge_workspace_bytes with FGE_FLAG_NO_SPLIT_K set
+ * tells the size in question; and all calls on one GPU share that GPU's array, so two such calls
+ * that may overlap on a device (different streams, different threads) race - callers serialise
+ * them on one stream.  The device address of the array is asked from the runtime on the first
+ * call on each device; fge_static_scratch_init does the same ahead of time for the current
+ * device (e.g. before a graph capture starts) and reports a failure as FGE_ERR_HIP. */
+enum { FGE_STATIC_SCRATCH_BYTES = 16 << 20 };     /* 16 MiB */
+int fused_gemm_epilogue_static(const void *X, const void *W, const float *b, int act, int norm,
+                               const fge_params *p, void *out, void *stream);
+int fge_static_scratch_init(void);
+size_t fge_static_scratch_bytes(void);
+
 /* Bytes of workspace the fused (fused != 0) or unfused (fused == 0) path needs for these
  * arguments; 0 is a valid answer.  Returns (size_t)-1 when the arguments are invalid.  The fused
  * figure includes the room for the optional K slices (FGE_FLAG_NO_SPLIT_K); a smaller workspace

@@ -62,9 +62,13 @@ def lib() -> ctypes.CDLL:
             _build.build()
         L = ctypes.CDLL(LIB_PATH)
         vp, ci, pp = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(FgeParams)
-        for name in ("fused_gemm_epilogue", "unfused_gemm_epilogue", "fge_fused_tiles"):
+        for name in ("fused_gemm_epilogue", "unfused_gemm_epilogue", "fge_fused_tiles", "fused_gemm_epilogue_static"):
             getattr(L, name).argtypes = [vp, vp, vp, ci, ci, pp, vp, vp]
             getattr(L, name).restype = ci
+        L.fge_static_scratch_init.argtypes = []
+        L.fge_static_scratch_init.restype = ci
+        L.fge_static_scratch_bytes.argtypes = []
+        L.fge_static_scratch_bytes.restype = ctypes.c_size_t
         L.fge_fused_finish.argtypes = [ci, ci, pp, vp, vp]
         L.fge_fused_finish.restype = ci
         L.fge_fused_needs_finish.argtypes = [ci, ci, pp]
@@ -182,6 +186,19 @@ def fge_tile_name(fused: bool, act, norm, p: FgeParams) -> str:
 def fused_gemm_epilogue(X, W, b, act, norm, p: FgeParams, out, stream=None) -> None:
     _check(lib().fused_gemm_epilogue(_ptr(X), _ptr(W), _ptr(b), _code(ACT, act), _code(NORM, norm),
                                      ctypes.byref(p), _ptr(out), _stream(stream)), "fused_gemm_epilogue")
+
+
+def fused_gemm_epilogue_static(X, W, b, act, norm, p: FgeParams, out, stream=None) -> None:
+    _check(lib().fused_gemm_epilogue_static(_ptr(X), _ptr(W), _ptr(b), _code(ACT, act), _code(NORM, norm),
+                                            ctypes.byref(p), _ptr(out), _stream(stream)), "fused_gemm_epilogue_static")
+
+
+def fge_static_scratch_init() -> None:
+    _check(lib().fge_static_scratch_init(), "fge_static_scratch_init")
+
+
+def fge_static_scratch_bytes() -> int:
+    return lib().fge_static_scratch_bytes()
 
 
 def unfused_gemm_epilogue(X, W, b, act, norm, p: FgeParams, out, stream=None) -> None:

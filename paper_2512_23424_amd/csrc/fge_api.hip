@@ -10,6 +10,11 @@
 
 using namespace fge;
 
+// Scratch of the entry point for callers that cannot allocate (fused_gemm_epilogue_static): one
+// array per GPU, part of the code object, held until the process ends.  In host code the name
+// below is only a handle; the device address is asked from the runtime once per device.
+static __device__ __align__(256) unsigned char scratch[FGE_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local int g_last_hip = 0;
@@ -311,6 +316,27 @@ int hip_status(hipError_t e) {
     if (e == hipSuccess) return FGE_OK;
     g_last_hip = (int)e;
     return FGE_ERR_HIP;
+}
+
+// Device address of `scratch` on the current device: every GPU holds its own copy of the array at
+// its own address, so the address is kept per device (asked on the first call there).
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+
+int static_scratch(void **ptr) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_status(e);
+    if (dev < 0 || dev >= MAX_DEVICES) return FGE_ERR_UNSUPPORTED;
+    void *sp = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (sp == nullptr) {
+        e = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_status(e);
+        if (sp == nullptr) return hip_status(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev].store(sp, std::memory_order_release);
+    }
+    *ptr = sp;
+    return FGE_OK;
 }
 
 TileArgs tile_args(const void *X, const void *W, const float *b, int act, int norm,
@@ -629,6 +655,37 @@ int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, i
     return launch_finish(pl, act, norm, p, out, (hipStream_t)stream);    // with the plan the tiles ran under
 }
 
+int fge_static_scratch_init(void) {
+    void *sp = nullptr;
+    return static_scratch(&sp);
+}
+
+size_t fge_static_scratch_bytes(void) { return FGE_STATIC_SCRATCH_BYTES; }
+
+int fused_gemm_epilogue_static(const void *X, const void *W, const float *b, int act, int norm,
+                               const fge_params *p, void *out, void *stream) {
+    // everything that can be refused is refused before the device is touched
+    int rc = check_common(p, act, norm, true);
+    if (rc) return rc;
+    if (!X || !W || !out) return FGE_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(out) || !aligned16(b)) return FGE_ERR_ALIGN;
+    if (norm == FGE_NORM_LOGSUMEXP && !p->aux_out) return FGE_ERR_NULL;
+    const Plan pl = make_plan(p, norm);
+    const size_t need = pl.generic ? pl.ws_generic : split_rows_workspace(p, norm);
+    if (need > FGE_STATIC_SCRATCH_BYTES) return FGE_ERR_WORKSPACE;
+    fge_params q = *p;
+    q.workspace = nullptr;
+    q.workspace_bytes = 0;
+    // (the K slices are optional: taken when their partial products fit the array as well)
+    if (need > 0 || k_split(p, norm, pl).slices > 1) {
+        void *sp = nullptr;
+        if ((rc = static_scratch(&sp))) return rc;
+        q.workspace = sp;
+        q.workspace_bytes = FGE_STATIC_SCRATCH_BYTES;
+    }
+    return fused_gemm_epilogue(X, W, b, act, norm, &q, out, stream);
+}
+
 int fge_gemm_bias(const void *X, const void *W, const float *b, const fge_params *p, void *Y, void *stream) {
     return do_gemm_bias(X, W, b, p, Y, (hipStream_t)stream);
 }
@@ -796,7 +853,7 @@ const char *fge_status_string(int status) {
     case FGE_ERR_BAD_SHAPE:   return "non-positive extent or stride smaller than the extent";
     case FGE_ERR_UNSUPPORTED: return "valid request outside the supported set";
     case FGE_ERR_ALIGN:       return "base pointer not 16-byte aligned";
-    case FGE_ERR_WORKSPACE:   return "workspace missing or too small";
+    case FGE_ERR_WORKSPACE:   return "workspace missing or too small (static form: problem beyond the library's scratch array)";
     case FGE_ERR_HIP:         return "HIP launch failed";
     default:                  return "unknown status";
     }

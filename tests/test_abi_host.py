@@ -206,3 +206,21 @@ def test_gated_small_problem_planning():
     q = prm(300, 520, 1152)                                                                           # not worth slicing
     assert L.fge_gated_tile_name(4, 3, ctypes.byref(q)) == b"partial_products_then_gate"
     assert L.fge_gated_workspace_bytes(1, 4, 3, ctypes.byref(q)) == 3 * ((300 * 520 * 4 + 255) // 256 * 256)
+
+
+def test_static_scratch_entry_point_refuses_what_does_not_fit():
+    """fused_gemm_epilogue_static checks its arguments, and the problem against the size of the
+    library's scratch array, before the device is touched."""
+    L = B.lib()
+    assert L.fge_static_scratch_bytes() == 16 << 20
+    fn = L.fused_gemm_epilogue_static
+    assert fn(FAKE, FAKE, None, 1, 1, None, FAKE, None) == 1
+    assert fn(FAKE, FAKE, None, 9, 1, ctypes.byref(_params()), FAKE, None) == 2
+    assert fn(FAKE + 4, FAKE, None, 1, 1, ctypes.byref(_params()), FAKE, None) == 5
+    # statistics of 65536 rows x 16 column tiles x 4 strips in the two-pass form: 32 MiB
+    big = _params(M=65536, N=4096, K=64, ldx=64, ldw=64, ldo=4096, in_dtype=1, out_dtype=1, flags=B.FLAG_TWO_PASS)
+    assert L.fge_workspace_bytes(1, 4, 3, ctypes.byref(big)) == 65536 * 64 * 8
+    assert fn(FAKE, FAKE, None, 4, 3, ctypes.byref(big), FAKE, None) == 6
+    # element-granular kernels: the fp32 intermediate of 3000 x 3001 rows does not fit either
+    odd = _params(M=3000, N=3001, K=17, ldx=17, ldw=17, ldo=3001)
+    assert fn(FAKE, FAKE, None, 1, 1, ctypes.byref(odd), FAKE, None) == 6
