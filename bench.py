@@ -5,8 +5,15 @@
 
 A step is one call of fused_gemm_epilogue (every kernel of the fused path) on one batch of the
 workload's seeded synthetic inputs, already resident in HBM.  The headline workload is the
-largest MFMA-bound one (cfg3: bf16 8192x4096x4096, SiLU, RMSNorm).  The single JSON line
-printed on stdout carries, besides the headline throughput:
+largest MFMA-bound one (cfg3: bf16 8192x4096x4096, SiLU, RMSNorm).
+
+Timing protocol (every figure): W untimed warm-up calls, then the same call repeated for at
+least 50 ms so that the chip has settled on the clock it sustains under this load, then
+`--blocks` (default 5) blocks of exactly K calls, each block bracketed by a synchronise and a
+pair of events on the launch stream.  `ms_per_step` is the MEDIAN block; the fastest and the
+slowest block are reported next to it (`ms_per_step_blocks`).
+
+The single JSON line printed on stdout carries, besides the headline throughput:
 
   roofline     - the dominant kernel (the fused tile kernel) timed with events recorded on the
                  launch stream around each of its launches, against the MFMA (or HBM) peak
@@ -31,6 +38,28 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3, "f8": 5000.0}      # dense MFMA pea
 PEAK_HBM_GBS = 8000.0
 # which roof binds each workload's dominant kernel
 BOUND = {"cfg1": "mfma", "cfg2": "mfma", "cfg3": "mfma", "cfg4": "mfma", "cfg5": "hbm", "cfg3_f8": "mfma"}
+# Plain vector-ALU roof: 256 compute units x 64 lanes per clock x 2.4 GHz = 39.3e12 lane-
+# operations per second (the 157.3 TFLOP/s fp32 vector peak counts a packed pair of fused
+# multiply-adds, 4 FLOP, per lane and clock; the library is built without packed fp32).
+PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9
+# Vector-ALU lane-cycles per output element of a workload's fused kernel, from the shader-
+# sequencer counters in profiles/sq_activity_<workload>.txt: SQ_ACTIVE_INST_VALU (busy time of the
+# vector ALUs, in units of 4 cycles, a quarter-rate transcendental counting four times as long as
+# an addition) x 4 cycles x 16 lanes per SIMD / output elements, minus the issue slots of the
+# MFMAs.  None where no profile has been taken.
+def valu_lane_cycles_per_element(workload: str):
+    path = os.path.join(ROOT, "profiles", f"sq_activity_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    rec = {}
+    for ln in open(path):
+        if ":" in ln and not ln.startswith("#"):
+            k, v = ln.split(":", 1)
+            rec[k.strip()] = v.strip().split()[0] if v.strip() else ""
+    try:
+        return float(rec["valu_lane_cycles_per_element"])
+    except (KeyError, ValueError):
+        return None
 
 
 def log(*a):
@@ -285,6 +314,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-others", action="store_true", help="skip the per-config table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--blocks", type=int, default=5, help="timed blocks of --steps calls; the median is reported")
+    ap.add_argument("--precondition-ms", type=float, default=50.0,
+                    help="run the timed call for at least this long before the first timed block")
     ap.add_argument("--only-fused", action="store_true",
                     help="run a known-size copy, then just the fused steps (for profiler runs)")
     ap.add_argument("--sources-digest", action="store_true",
@@ -382,17 +414,35 @@ def main() -> int:
                 e1.record()
                 B.fge_fused_finish(self.w.act, self.w.norm, self.p[s], out)
 
-    def timed(fn, steps, warmup):
+    def timed_blocks(fn, steps, warmup, blocks=None, pre_ms=None):
+        """ms per step of each of `blocks` blocks of exactly `steps` calls (see the module text)."""
+        blocks = args.blocks if blocks is None else blocks
+        pre_ms = args.precondition_ms if pre_ms is None else pre_ms
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for i in range(warmup):
             fn(i & 1)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(steps):
-            fn(i & 1)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps          # ms per step
+        if pre_ms > 0:
+            e0.record()
+            fn(0)
+            e1.record()
+            torch.cuda.synchronize()
+            one = max(e0.elapsed_time(e1), 1e-3)
+            for i in range(min(20000, int(pre_ms / one) + 1)):
+                fn(i & 1)
+        out = []
+        for _ in range(max(1, blocks)):
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(steps):
+                fn(i & 1)
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / steps)
+        return out
+
+    def timed(fn, steps, warmup):
+        return float(np.median(timed_blocks(fn, steps, warmup)))          # ms per step, median block
 
     def graphed(fn, calls=100, replays=10):
         """ms per step with the launches recorded once into a HIP graph and replayed: what a
@@ -453,12 +503,23 @@ def main() -> int:
         gbs = w.algorithmic_bytes / (t_fused * 1e-3) / 1e9
         r = {"tile": case.tile, "kernels_fused": 2 if case.two_pass else 1,
              "ms_fused": round(t_fused, 5), "tflops": round(tf, 2), "gbs": round(gbs, 1),
-             "frac_mfma": round(tf / PEAK_TFLOPS[dt], 4), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+             "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
         if dt == "f32" and "splitbf16" in case.tile:
             # fp32 operands multiplied as three bf16 products on the bf16 matrix pipe: the roof
-            # of that pipe for useful FLOPs is a third of its peak (frac_mfma above stays the
-            # fraction of the fp32-instruction peak and may exceed 1)
-            r["frac_mfma_bf16_pipe"] = round(tf / (PEAK_TFLOPS["bf16"] / 3.0), 4)
+            # for useful FLOPs is a third of that pipe's peak
+            r["frac_mfma"] = round(tf / (PEAK_TFLOPS["bf16"] / 3.0), 4)
+            r["mfma_roof"] = "bf16 pipe / 3 (split product)"
+        else:
+            r["frac_mfma"] = round(tf / PEAK_TFLOPS[dt], 4)
+        # plain vector-ALU roof (the activation and row-op arithmetic), where the kernel's lane-
+        # cycles per element have been counted
+        lc = valu_lane_cycles_per_element(w.name)
+        if lc is not None:
+            lane_ops = lc * w.rows * w.N
+            r["frac_valu"] = round(lane_ops / (t_fused * 1e-3) / PEAK_VALU_LANE_OPS, 4)
+            r["valu_lane_cycles_per_element"] = lc
+        fr = {k: r[k] for k in ("frac_mfma", "frac_hbm", "frac_valu") if k in r}
+        r["binding_roof"] = max(fr, key=fr.get)[5:]
         if t_unfused is not None:
             r["ms_unfused"] = round(t_unfused, 5)
             r["speedup_vs_unfused"] = round(t_unfused / t_fused, 3)
@@ -485,7 +546,8 @@ def main() -> int:
         t_fused = timed(case.fused, args.steps, args.warmup)
         log(f"[bench] fused {t_fused:.4f} ms/step")
         return 0
-    t_fused = timed(case.fused, args.steps, args.warmup)
+    fused_blocks = timed_blocks(case.fused, args.steps, args.warmup)
+    t_fused = float(np.median(fused_blocks))
     # The dominant kernel's average launch duration.  When the fused path is that one kernel, the
     # events around the timed region measure exactly it, under the same sustained load (the chip
     # lowers its clock a few milliseconds into a run of back-to-back launches; launches timed one
@@ -573,7 +635,10 @@ def main() -> int:
     line = {
         "metric": "fused GEMM+epilogue TFLOP/s (% MFMA or HBM roofline) and speedup vs unfused",
         "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": head["ms_fused"], "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": head["ms_fused"],
+        "ms_per_step_blocks": {"n": len(fused_blocks), "min": round(min(fused_blocks), 5), "max": round(max(fused_blocks), 5),
+                               "precondition_ms": args.precondition_ms},
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": f"{w.name}: M={w.rows} K={w.K} N={w.N}, "
                                f"{'bf16 in/out' if dt == 'bf16' else 'E4M3 in, bf16 out' if dt == 'f8' else 'fp32'}, fp32 accumulate, "

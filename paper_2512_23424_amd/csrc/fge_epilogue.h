@@ -61,12 +61,29 @@ struct TileArgs {
 // of the tile shape), so no row or column needs a guard.  STREAM_OUT: the output is too large
 // for the last-level cache; it is stored with the streaming hint, which keeps it from displacing
 // the operands on its way out (nothing of it would still be cached for a consumer anyway).
+// ACT_CT / NORM_CT (>= 0): activation and row op fixed at compile time - the tile's epilogue is
+// then one straight line of code the compiler can schedule as a whole, instead of a chain of
+// uniform branches; BOUNDED_CT says which softmax / logsumexp variant (see `bounded`) that is.
+// PLAIN_ACC: the caller's accumulators already hold post*(alpha*x.w + b) (scale folded into an
+// operand, bias into the initial accumulator value), so no scale + bias step is applied.
 template <typename OutT, int MB, int NB, int WAVES_N, int PATCH_ROWS, bool JOINT, bool WAIT_VM, bool COOP = false,
-          bool FULL_TILE = false, bool STREAM_OUT = false>
+          bool FULL_TILE = false, bool STREAM_OUT = false, int ACT_CT = -1, int NORM_CT = -1, bool BOUNDED_CT = false,
+          bool PLAIN_ACC = false>
 struct TileEpilogue {
     static constexpr int WTN = NB * 32;               // columns of a wave strip
-    static constexpr int SSTR = WTN + 8;              // floats per patch row: +8 puts lanes 0-31
-                                                      // and 32-63 (four rows apart) on other banks
+    // Patch layout.  A patch row is written 32 columns at a time by the lanes 0-31 (row R) and
+    // 32-63 (row R + 4) of an accumulator register, and read back 16 bytes per lane by 16 lanes
+    // at a time.  With 4-byte results and 64-column strips a lane reads two 16-byte groups half a
+    // strip apart, so 16 lanes cover one half of two neighbouring rows: writes and reads are both
+    // free of bank conflicts (64 banks of 4 bytes) when rows are unpadded (one bank line each)
+    // and the two 32-column halves are swapped in the rows whose bits 0 and 2 differ - rows four
+    // apart and neighbouring rows then sit in opposite halves of the bank line.  (Measured on
+    // the narrow-K kernel: conflicts 30 % -> 2 % of the LDS-active cycles.)  Every other case
+    // keeps rows padded by 8 floats: conflict-free writes, two-way conflicts on the reads; the
+    // analogous swap of 4-column groups for 16-bit results measured 1.5 % slower on the
+    // epilogue-heavy batched workload (two more address registers in a kernel short of them).
+    static constexpr bool XORP = WTN == 64 && sizeof(OutT) == 4;
+    static constexpr int SSTR = XORP ? WTN : WTN + 8;   // floats per patch row
     static constexpr int VEC = 8;                     // columns per lane in the row-wise layout, as
                                                       // two groups of 4: neighbours for bf16 (one
                                                       // 16-byte store), half a strip apart for fp32
@@ -94,6 +111,8 @@ struct TileEpilogue {
     int prow, pcol, gcol;       // row-wise layout: row in a pass, first column (of group 0) in
                                 // the strip / globally; group 1 lies G4STEP columns further
     int sub;                    // lane index inside its row segment
+    int wsel[2];                // patch layout: column of this lane in a 32-column write, by (block ^ row bit 0)
+    int rsel[2];                // ... and first column of its two 4-column read groups
     bool ok4[2];                // columns gcol..+3 / gcol+4..+7 lie inside N (N is a multiple of 4)
     int xch_par;                // which exchange buffer the next exchange uses
     float scale, bias[NB];      // y = scale * acc + bias  (scale = post*alpha, bias = post*b)
@@ -118,6 +137,14 @@ struct TileEpilogue {
         gcol = n0 + wave_n * WTN + pcol;
         ok4[0] = gcol < a.N;
         ok4[1] = gcol + G4STEP < a.N;
+        if constexpr (XORP) {                              // halves swapped where row bits 0 and 2 differ
+            const int f = (prow ^ (prow >> 2)) & 1;
+            wsel[0] = (h << 5) + l32;        wsel[1] = ((h ^ 1) << 5) + l32;
+            rsel[0] = pcol + (f << 5);       rsel[1] = pcol + ((f ^ 1) << 5);
+        } else {
+            wsel[0] = wsel[1] = l32;
+            rsel[0] = pcol;                  rsel[1] = pcol + G4STEP;
+        }
         xch_par = 0;
         whole_row = a.tiles_n == 1;
         // (not in the cooperative form, whose registers are too scarce for two more variants)
@@ -135,7 +162,8 @@ struct TileEpilogue {
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) blk[j][r] = activate<ACT>(scale * blk[j][r] + bias[j], a.lo, a.hi);
+            for (int r = 0; r < 16; ++r)
+                blk[j][r] = activate<ACT>(PLAIN_ACC ? blk[j][r] : scale * blk[j][r] + bias[j], a.lo, a.hi);
     }
 
     // Publish the strip pair of pass q: to the workspace for the second pass, or (cooperative
@@ -349,6 +377,10 @@ struct TileEpilogue {
     // norm_group with the runtime row-op code (and the clamp bound) turned into constants
     // (mkeep: the references the exponentials of a softmax / logsumexp group were taken against)
     template <bool FULL> __device__ __forceinline__ void norm_dispatch(float (&v)[NPG][VEC], int grow0, float (&mkeep)[NPG]) {
+        if constexpr (NORM_CT >= 0) {
+            if constexpr (NORM_CT != FGE_NORM_NONE) norm_group<NORM_CT, FULL, BOUNDED_CT>(v, grow0, mkeep);
+            return;
+        }
         switch (a.norm + (bounded ? 8 : 0)) {
         case FGE_NORM_NONE: case FGE_NORM_NONE + 8: break;
         case FGE_NORM_SOFTMAX:       norm_group<FGE_NORM_SOFTMAX, FULL, false>(v, grow0, mkeep); break;
@@ -368,14 +400,16 @@ struct TileEpilogue {
             for (int j = 0; j < NB; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (PATCH_ROWS == 32 || (r >> 3) == half)
-                        patch[(brow(r) - half * PATCH_ROWS) * SSTR + j * 32 + l32] = blk[j][r];
+                    if (PATCH_ROWS == 32 || (r >> 3) == half) {
+                        // (row bit 0 is r & 1, row bit 2 is h: see brow)
+                        const int col = XORP ? wsel[(j ^ r) & 1] : j * 32 + wsel[0];
+                        patch[(brow(r) - half * PATCH_ROWS) * SSTR + col] = blk[j][r];
+                    }
 #pragma unroll
             for (int p = 0; p < NPH; ++p)
 #pragma unroll
                 for (int e = 0; e < VEC; e += 4) {
-                    const floatx4 f = *reinterpret_cast<const floatx4 *>(patch + (p * RPP + prow) * SSTR + pcol +
-                                                                         (e >> 2) * G4STEP);
+                    const floatx4 f = *reinterpret_cast<const floatx4 *>(patch + (p * RPP + prow) * SSTR + rsel[e >> 2]);
                     v[B * NPB + half * NPH + p][e] = f[0];
                     v[B * NPB + half * NPH + p][e + 1] = f[1];
                     v[B * NPB + half * NPH + p][e + 2] = f[2];
@@ -385,7 +419,8 @@ struct TileEpilogue {
     }
     // activation in place (accumulator layout), then the transpose
     template <int B> __device__ __forceinline__ void to_rows(floatx16 (&blk)[NB], float (&v)[NPG][VEC]) {
-        dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) { act_block<ACT>(blk); });
+        if constexpr (ACT_CT >= 0) act_block<ACT_CT>(blk);
+        else dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) { act_block<ACT>(blk); });
         transpose_block<B>(blk, v);
     }
 

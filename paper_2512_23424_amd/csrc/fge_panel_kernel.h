@@ -7,8 +7,12 @@
 //     already split, for the whole launch;
 //   * every wave multiplies all 64 rows of a tile, so the fp32 X tile is split into its bf16
 //     parts once per workgroup (each thread fetches and splits 8 values) and parked in LDS as
-//     two bf16 images; the fetch of the next tile is issued before the current product and its
-//     result is parked before the current tile's stores are queued, so nothing waits on a store;
+//     two bf16 images; a tile's values are fetched a whole iteration before they are parked (the
+//     fetch of the tile after next is issued right behind the parking of the next one, ahead of
+//     the current tile's stores), so neither memory latency nor a store queue is waited for;
+//   * scale and bias cost nothing per element: post_scale*alpha is folded into the register-
+//     resident W fragments before they are split (one fp32 rounding per weight, none when the
+//     factor is a power of two) and post_scale*b is the initial value of the accumulators;
 //   * the product uses the bf16 matrix instruction on a two-term split of the fp32 operands,
 //         x = xh + xl,  w = wh + wl  (xh, wh: bf16 roundings; xl, wl: bf16 roundings of the rest)
 //         x*w ~= xh*wh + xh*wl + xl*wh          (fp32 accumulate)
@@ -45,7 +49,9 @@ struct PanelShape {
 
 // FULL: M is a multiple of 64 and N == 512, so the epilogue needs no row or column guards.
 // STREAM: the output is larger than the last-level cache and is stored with the streaming hint.
-template <typename OutT, bool FULL, bool STREAM>
+// ACT_CT / NORM_CT / BOUNDED_CT: the chain fixed at compile time (see TileEpilogue), -1 to take
+// it from the arguments.
+template <typename OutT, bool FULL, bool STREAM, int ACT_CT = -1, int NORM_CT = -1, bool BOUNDED_CT = false>
 __global__ __launch_bounds__(PanelShape::THREADS)
 void panel_kernel(const TileArgs a) {
     constexpr int BM = PanelShape::BM, WAVES_N = PanelShape::WAVES_N;
@@ -54,7 +60,7 @@ void panel_kernel(const TileArgs a) {
     constexpr int SROWB = 128;                        // LDS bytes per row of a bf16 image: 64 values
     constexpr int SIMG = BM * SROWB;                  // 8 KB; an X buffer is the image of the high
     constexpr int XBUF = 2 * SIMG;                    // parts followed by the image of the low parts
-    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, false, false, false, FULL, STREAM>;
+    using Epi = TileEpilogue<OutT, MB, NB, WAVES_N, 16, false, false, false, FULL, STREAM, ACT_CT, NORM_CT, BOUNDED_CT, true>;
     static_assert(NT == BM * 8, "one thread per (row, 8 values of k) of an X tile");
 
     __shared__ __attribute__((aligned(16))) unsigned char xs[2 * XBUF];
@@ -70,10 +76,16 @@ void panel_kernel(const TileArgs a) {
 
     // ---------------- W fragments of this wave's 64 columns, split once, kept in registers
     // fragment (j, t): column wave_n*64 + j*32 + l32, k = 16t + 8h .. +7
+    // scaled by post*alpha on the way in; the accumulators start from post*b (column l32 of block j
+    // in every register of the block), so that they end as post*(alpha*x.w + b)
+    const float wscale = a.post * a.alpha;
     u32x4 whi[NB][4], wlo[NB][4];
+    float binit[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-        const float *wr = W + (int64_t)min(wave_n * WTN + j * 32 + l32, a.N - 1) * a.ldw;
+        const int col = wave_n * WTN + j * 32 + l32;
+        binit[j] = (a.b != nullptr && col < a.N) ? a.post * a.b[col] : 0.0f;
+        const float *wr = W + (int64_t)min(col, a.N - 1) * a.ldw;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int k0 = 16 * t + 8 * h;
@@ -82,7 +94,7 @@ void panel_kernel(const TileArgs a) {
             for (int c = 0; c < 2; ++c) {
                 floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (k0 + 4 * c < a.K) v = *reinterpret_cast<const floatx4 *>(wr + k0 + 4 * c);
-                f[4 * c] = v[0]; f[4 * c + 1] = v[1]; f[4 * c + 2] = v[2]; f[4 * c + 3] = v[3];
+                f[4 * c] = wscale * v[0]; f[4 * c + 1] = wscale * v[1]; f[4 * c + 2] = wscale * v[2]; f[4 * c + 3] = wscale * v[3];
             }
             split_bf16x8(f, whi[j][t], wlo[j][t]);
         }
@@ -123,25 +135,27 @@ void panel_kernel(const TileArgs a) {
 
     Epi epi(a, out, xch, patches + wave * Epi::PATCH_FLOATS, BM, 0, 0, 0, 0, wave_n, lane);
 
-    // ---------------- persistent loop over 64-row tiles
+    // ---------------- persistent loop over 64-row tiles.  At the top of an iteration the tile is
+    // parked in LDS buffer `buf` and the registers hold the values of the next tile, fetched a
+    // whole iteration ago; they are parked behind this tile's product, and the fetch of the tile
+    // after next follows at once, still ahead of this tile's stores.
     const int ntiles = a.tiles_m;
     int tile = blockIdx.x;
     if (tile < ntiles) {
         load_x(tile * BM);
         park_x(0);
+        if (tile + (int)gridDim.x < ntiles) load_x((tile + (int)gridDim.x) * BM);
     }
     // Whole-row logsumexp leaves `out` final without any exchange between the waves; only aux
     // needs all strips of a row.  The strips' pairs are parked in LDS and merged one iteration
     // later, behind the barrier the loop has anyway.
-    epi.defer_lse = a.norm == FGE_NORM_LOGSUMEXP;
+    epi.defer_lse = (NORM_CT >= 0 ? NORM_CT : a.norm) == FGE_NORM_LOGSUMEXP;
     int it = 0;
     for (; tile < ntiles; tile += gridDim.x, ++it) {
         const int buf = it & 1;
         __syncthreads();    // tile `it` is parked by every wave; reads of the other buffer are over
         if (epi.defer_lse && it > 0) epi.flush_lse(tid, (it - 1) & 1, (tile - (int)gridDim.x) * BM);
-        const int next = tile + gridDim.x;
-        if (next < ntiles) load_x(next * BM);
-        __builtin_amdgcn_sched_barrier(0);            // the fetch stays ahead of the product
+        const int next = tile + gridDim.x, next2 = next + gridDim.x;
 
         floatx16 acc[MB][NB];
 #pragma unroll
@@ -149,7 +163,7 @@ void panel_kernel(const TileArgs a) {
 #pragma unroll
             for (int j = 0; j < NB; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = binit[j];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             u32x4 ahi[MB], alo[MB];
@@ -172,9 +186,8 @@ void panel_kernel(const TileArgs a) {
 #pragma unroll
                 for (int j = 0; j < NB; ++j) mfma_bf16(ahi[i], whi[j][t], acc[i][j]);
         }
-        // the next tile has had the whole product to arrive; it is parked before this tile's
-        // stores are queued, so the wait never sits behind them
         if (next < ntiles) park_x(buf ^ 1);
+        if (next2 < ntiles) load_x(next2 * BM);
         __builtin_amdgcn_sched_barrier(0);
         epi.m0 = tile * BM;
         epi.lse_par = buf;
