@@ -275,3 +275,41 @@ def generate_gated(w: Workload) -> Dict[str, Optional[np.ndarray]]:
     d = w.dist.get("b")
     out["b2"] = None if d is None else draw(w.seed, "b2", (w.N,), d, F32)
     return out
+
+
+def adversarial(w: Workload, kind: str) -> Dict[str, Optional[np.ndarray]]:
+    """The tensors of generate(w) reshaped into rows that stress a row operation (the paper's
+    benchmark section names hidden assumptions about the inputs as the typical failure of
+    generated kernels).  Only stored values are chosen here; nothing of the chain is computed.
+
+      "dominant" : the bias carries one dominant column (+80) over a spread of -80 .. 0, so the
+                   activations of a row (with act = none) reach |a| = 80 and one element holds
+                   almost all of a softmax's mass;
+      "constant" : W = 0 and a constant bias - every row is constant;
+      "tied"     : W = 0 and a bias whose maximum recurs every 64 columns, so that all column
+                   tiles (and wave strips) of a row report exactly the same maximum;
+      "offset"   : the first contraction index carries x = 1.2345678, w = 810.0123 for every row
+                   and column: the product puts a common offset of about 1000 under every row,
+                   against a spread of order one from the remaining random terms."""
+    t = generate(w)
+    n = np.arange(w.N)
+    if kind == "dominant":
+        b = -80.0 * ((n * 37) % 101) / 100.0
+        b[(w.N * 5) // 7] = 80.0
+        t["b"] = b.astype(np.float32)
+    elif kind == "constant":
+        t["W"] = _store(np.zeros((w.N, w.K)), w.in_dtype)
+        t["b"] = np.full(w.N, 3.25, dtype=np.float32)
+    elif kind == "tied":
+        t["W"] = _store(np.zeros((w.N, w.K)), w.in_dtype)
+        b = -1.0 - ((n * 13) % 17) / 4.0
+        b[n % 64 == 5] = 5.0
+        t["b"] = b.astype(np.float32)
+    elif kind == "offset":
+        X, W = as_f64(t["X"]).copy(), as_f64(t["W"]).copy()
+        X[:, 0] = 1.2345678
+        W[:, 0] = 810.0123
+        t["X"], t["W"] = _store(X, w.in_dtype), _store(W, w.in_dtype)
+    else:
+        raise ValueError(kind)
+    return t
