@@ -257,6 +257,62 @@ def few_rows(torch, B, I, timed, log):
     return r
 
 
+def odd_extents(torch, B, I, timed, log):
+    """The headline chain on extents off the 16-byte grid: 4097 x 4095 x 4099 (bf16, dense rows, so
+    every row of X, W and out starts at an odd element).  The fused call repacks the operands
+    into zero-padded buffers, runs the tile kernels and lets the element-granular row kernel write
+    the result; against the same chain at the next shape on the grid, 4104 x 4096 x 4104 (the same
+    17 x 17 tiles of 256 x 256: the cost of the odd extents alone), at 4096^3 (16 x 16 tiles, one
+    round of the chip instead of two: what the one row and three columns past the tile boundary
+    cost) and against the element-granular product (what such a shape ran on before; two steps
+    only, it is slow)."""
+    from oracle import compare as C
+    from oracle import oracle as O
+    res = {}
+    for name, (M, K, N) in (("odd", (4097, 4095, 4099)), ("aligned", (4104, 4096, 4104)), ("cube", (4096, 4096, 4096))):
+        w = I.scaled(I.WORKLOADS["cfg3"], M=M, K=K, N=N, dist=dict(I.WORKLOADS["cfg3"].dist, W=("normal", 0.0, 1.0 / 64)))
+        t = I.generate(w)
+        X = torch.from_numpy(t["X"].view(np.int16)).cuda().view(torch.bfloat16)
+        W = torch.from_numpy(t["W"].view(np.int16)).cuda().view(torch.bfloat16)
+        gamma = torch.from_numpy(t["gamma"]).cuda()
+        out = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        p = B.make_params(X, W, out, eps=w.eps, gamma=gamma)
+        n = max(B.fge_workspace_bytes(True, w.act, w.norm, p), 16)
+        ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), n
+        out.fill_(float("nan"))
+        B.fused_gemm_epilogue(X, W, None, w.act, w.norm, p, out)
+        torch.cuda.synchronize()
+        rows = np.unique(np.concatenate([[0, M - 1], np.random.default_rng(8).integers(0, M, 6)]))
+        ref, _ = O.chain(I.as_f64(t["X"][rows]), I.as_f64(t["W"]), None, I.as_f64(t["gamma"]), None, act=w.act, norm=w.norm, eps=w.eps)
+        err = C.max_rel_err(out[torch.from_numpy(rows).cuda()].to(torch.float64).cpu().numpy(), ref)
+        if not (err <= 2e-2):
+            raise SystemExit(f"bench.py: odd-extents result ({name}) off the oracle: {err:.3e}")
+        res[name] = {"tile": B.fge_tile_name(True, w.act, w.norm, p), "parity_err": float(f"{err:.3e}"),
+                     "ms": round(timed(lambda i: B.fused_gemm_epilogue(X, W, None, w.act, w.norm, p, out), 20, 5), 5)}
+        if name == "odd":           # the element-granular path: a workspace that only holds its fp32 rows
+            q = B.make_params(X, W, out, eps=w.eps, gamma=gamma)
+            q.workspace, q.workspace_bytes = ws.data_ptr(), (M * N * 4 + 255) // 256 * 256
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            B.fused_gemm_epilogue(X, W, None, w.act, w.norm, q, out)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(2):
+                B.fused_gemm_epilogue(X, W, None, w.act, w.norm, q, out)
+            e1.record()
+            torch.cuda.synchronize()
+            res[name]["ms_element_granular"] = round(e0.elapsed_time(e1) / 2, 4)
+        del X, W, out, ws
+        torch.cuda.empty_cache()
+    r = {"workload": "cfg3's chain, bf16, M=4097 K=4095 N=4099 (dense rows)", "path": res["odd"]["tile"],
+         "ms_fused": res["odd"]["ms"], "ms_fused_4104x4096x4104": res["aligned"]["ms"],
+         "ratio_to_aligned": round(res["odd"]["ms"] / res["aligned"]["ms"], 3), "ms_fused_4096_cubed": res["cube"]["ms"],
+         "ms_element_granular": res["odd"]["ms_element_granular"],
+         "tflops": round(2.0 * 4097 * 4095 * 4099 / (res["odd"]["ms"] * 1e-3) / 1e12, 2), "parity_err": res["odd"]["parity_err"]}
+    log(f"[bench] odd extents: {json.dumps(r)}")
+    return r
+
+
 def wide_rows(torch, B, I, timed, log):
     """Rows wider than a wave's registers hold: 2048 x 4096 x 32000 (bf16), logits with a row
     softmax and with a row logsumexp (out = the logits, aux = lse) - the rows are split over 125
@@ -630,6 +686,7 @@ def main() -> int:
     rows = None if args.no_others else row_ops(torch, B, I, timed, log)
     few = None if args.no_others else few_rows(torch, B, I, timed, log)
     wide = None if args.no_others else wide_rows(torch, B, I, timed, log)
+    odd = None if args.no_others else odd_extents(torch, B, I, timed, log)
     geo = math.exp(sum(math.log(s) for s in sp) / len(sp)) if sp else None
 
     line = {
@@ -644,7 +701,7 @@ def main() -> int:
                                f"{'bf16 in/out' if dt == 'bf16' else 'E4M3 in, bf16 out' if dt == 'f8' else 'fp32'}, fp32 accumulate, "
                                f"act={w.act} rowop={w.norm} (codes of include/fge.h)",
                    "tile": head["tile"], "speedup_vs_unfused": head.get("speedup_vs_unfused")},
-        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated, "fp8_operands": f8, "row_ops": rows, "few_rows": few, "wide_rows": wide,
+        "roofline": roof, "cpu_baseline": cpu, "per_config": per, "gated_ffn": gated, "fp8_operands": f8, "row_ops": rows, "few_rows": few, "wide_rows": wide, "odd_extents": odd,
         "speedup_geomean": None if geo is None else round(geo, 3),
         "paper_context": "paper reports 1.46x geomean over PyTorch eager (Triton, Ascend 910B, "
                          "KernelBench L1); no number for this chain",

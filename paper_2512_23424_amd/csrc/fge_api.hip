@@ -263,12 +263,26 @@ KSplit k_split(const fge_params *p, int norm, const Plan &pl) {
     return ks;
 }
 
+struct Repack {
+    bool use;
+    bool odd_out;                // the result is not storable in 16-byte units either
+    int Kp, Np;                  // padded contraction length / padded width of the fp32 rows
+    int64_t rows, w_rows;        // rows of the padded X / W
+    size_t off_w, off_b, off_mid, off_inner, bytes;      // workspace layout; the padded X sits at 0
+    fge_params inner;            // the padded problem (workspace still to be filled in)
+};
+
+Repack plan_repack(const fge_params *p, int norm);
+
 // Workspace of the fused path: enough for either form of split rows, since a launch on a
 // stream under graph capture takes the two-pass form whatever the flags say - and for the
 // K-split where the one-call entry point would take it.
 size_t fused_workspace(const fge_params *p, int norm) {
     const Plan p1 = make_plan(p, norm, false), p2 = make_plan(p, norm, true);
-    if (p1.generic) return p1.ws_generic;
+    if (p1.generic) {                // room for the repacked operands where the problem is worth repacking
+        const Repack rp = plan_repack(p, norm);
+        return rp.use && rp.bytes > p1.ws_generic ? rp.bytes : p1.ws_generic;
+    }
     const size_t a = p1.ws_stats + p1.ws_marks, b = p2.ws_stats + p2.ws_marks, c = k_split(p, norm, p1).bytes();
     return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
@@ -459,6 +473,86 @@ int run_k_split(const void *X, const void *W, const float *b, int act, int norm,
     return finish_partials(part, nullptr, b, nullptr, act, norm, p, pl, S, slice, part + ks.ws_part, out, s);
 }
 
+int run_fused(const void *X, const void *W, const float *b, int act, int norm, const fge_params *p, void *out,
+              hipStream_t s);
+
+// Operands or results whose extents or strides are not whole 16-byte units (K = 4095, a row
+// stride of 4099 elements ...) cannot be staged or stored by the vectorised kernels as they
+// lie.  Where the problem is large enough to pay for one more read and write of its operands,
+// fused_gemm_epilogue repacks them instead of leaving the product to the element-granular
+// kernel: X and W are copied into dense workspace buffers with K padded by zeros to a whole
+// chunk (the extra terms of every sum are exact zeros), and the padded problem runs on the
+// tile kernels.  When the result's own extents or strides are odd as well, the tile kernel
+// applies the activation and writes fp32 rows of padded width into the workspace (W gets zero
+// rows, b zero entries for the padding columns), and the element-granular row kernel - which
+// walks a row element by element and never looks at the padding - turns them into `out`.
+// The stage entry points and the unfused sequence keep the element-granular product.
+constexpr double REPACK_MIN_FLOP = 3.0e7;   // below this the element-granular product is as fast as four launches
+
+Repack plan_repack(const fge_params *p, int norm) {
+    Repack r{};
+    if (vectorisable(p, norm, true)) return r;
+    const size_t is = esize(p->in_dtype), os = esize(p->out_dtype);
+    const int64_t rows = (int64_t)p->M * p->batch;
+    if (2.0 * (double)rows * p->N * p->K < REPACK_MIN_FLOP || rows > INT32_MAX / 2) return r;
+    const int cw = (int)(16 / is);
+    r.Kp = (p->K + cw - 1) / cw * cw;
+    r.odd_out = (p->N * os) % 16 || (p->ldo * os) % 16 || (p->batch > 1 && (p->batch_stride_o * os) % 16);
+    r.Np = r.odd_out ? (p->N + 3) / 4 * 4 : p->N;
+    r.rows = rows;
+    r.w_rows = r.Np;
+    r.inner = *p;
+    r.inner.K = r.Kp;
+    r.inner.ldx = r.inner.ldw = r.Kp;
+    r.inner.batch_stride_x = (int64_t)p->M * r.Kp;
+    r.inner.workspace = nullptr;
+    r.inner.workspace_bytes = 0;
+    if (r.odd_out) {             // one tall problem into dense fp32 rows of padded width
+        r.inner.M = (int32_t)rows;
+        r.inner.batch = 1;
+        r.inner.N = r.Np;
+        r.inner.ldo = r.Np;
+        r.inner.batch_stride_x = r.inner.batch_stride_o = 0;
+        r.inner.out_dtype = FGE_F32;
+        r.inner.gamma = r.inner.beta = nullptr;
+        r.inner.aux_out = nullptr;
+    }
+    if (!vectorisable(&r.inner, r.odd_out ? FGE_NORM_NONE : norm, true)) return r;     // (cannot happen)
+    const size_t xp = round256((size_t)rows * r.Kp * is), wp = round256((size_t)r.w_rows * r.Kp * is);
+    r.off_w = xp;
+    r.off_b = r.off_w + wp;
+    r.off_mid = r.off_b + (r.odd_out ? round256((size_t)r.Np * sizeof(float)) : 0);
+    r.off_inner = r.off_mid + (r.odd_out ? round256((size_t)rows * r.Np * sizeof(float)) : 0);
+    r.bytes = r.off_inner + fused_workspace(&r.inner, r.odd_out ? FGE_NORM_NONE : norm);
+    r.use = true;
+    return r;
+}
+
+int run_repacked(const void *X, const void *W, const float *b, int act, int norm, const fge_params *p,
+                 const Repack &rp, void *out, hipStream_t s) {
+    char *ws = static_cast<char *>(p->workspace);
+    int rc;
+    const PadArgs ax{X, ws, p->M, p->batch, p->K, rp.Kp, p->ldx, p->batch > 1 ? p->batch_stride_x : 0, rp.rows};
+    if ((rc = hip_status(launch_pad_rows(p->in_dtype, s, ax)))) return rc;
+    const PadArgs aw{W, ws + rp.off_w, p->N, 1, p->K, rp.Kp, p->ldw, 0, rp.w_rows};
+    if ((rc = hip_status(launch_pad_rows(p->in_dtype, s, aw)))) return rc;
+    fge_params q = rp.inner;
+    q.workspace = ws + rp.off_inner;
+    q.workspace_bytes = p->workspace_bytes - rp.off_inner;
+    if (!rp.odd_out) return run_fused(ws, ws + rp.off_w, b, act, norm, &q, out, s);
+    const float *bp = nullptr;
+    if (b != nullptr) {
+        float *dst = reinterpret_cast<float *>(ws + rp.off_b);
+        if ((rc = hip_status(launch_pad_vec(b, dst, p->N, rp.Np, s)))) return rc;
+        bp = dst;
+    }
+    void *mid = ws + rp.off_mid;
+    if ((rc = run_fused(ws, ws + rp.off_w, bp, act, FGE_NORM_NONE, &q, mid, s))) return rc;
+    GenArgs g = gen_args(p);
+    g.X = mid; g.ldx = rp.Np; g.bsx = (int64_t)p->M * rp.Np; g.dst = out; g.norm = norm;
+    return hip_status(launch_generic_row(FGE_F32, p->out_dtype, s, g));
+}
+
 // one_call: fused_gemm_epilogue, which runs the second pass, if any, from the plan returned here.
 // It may finish split rows inside the tile kernel (cooperative form; if the device cannot hold
 // that grid the launcher refuses it before anything runs and the two-pass form is taken) and cut
@@ -476,6 +570,10 @@ int do_fused_tiles(const void *X, const void *W, const float *b, int act, int no
     const Plan pl = make_plan(p, norm, !one_call || capturing(s));
     if (plan_out) *plan_out = pl;
     if (pl.generic) {
+        if (one_call) {
+            const Repack rp = plan_repack(p, norm);
+            if (rp.use && p->workspace && p->workspace_bytes >= rp.bytes) return run_repacked(X, W, b, act, norm, p, rp, out, s);
+        }
         // GEMM + activation straight into out, or into an fp32 rows x N intermediate that the row
         // kernel then reads (several passes) and turns into out
         GenArgs g = gen_args(p);
@@ -542,6 +640,14 @@ int launch_finish(const Plan &pl, int act, int norm, const fge_params *p, void *
     else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((finish_kernel<f16_t, 1>), grid, block, 0, s, r);
     else                              hipLaunchKernelGGL((finish_kernel<float, 1>), grid, block, 0, s, r);
     return hip_status(hipGetLastError());
+}
+
+int run_fused(const void *X, const void *W, const float *b, int act, int norm, const fge_params *p, void *out,
+              hipStream_t s) {
+    Plan pl{};
+    const int rc = do_fused_tiles(X, W, b, act, norm, p, out, s, &pl, true);
+    if (rc || !pl.needs_finish) return rc;
+    return launch_finish(pl, act, norm, p, out, s);    // with the plan the tiles ran under
 }
 
 int do_gemm_bias(const void *X, const void *W, const float *b, const fge_params *p, void *Y, hipStream_t s) {
@@ -649,10 +755,7 @@ int fge_fused_k_slices(int act, int norm, const fge_params *p) {
 
 int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
                         const fge_params *p, void *out, void *stream) {
-    Plan pl{};
-    int rc = do_fused_tiles(X, W, b, act, norm, p, out, (hipStream_t)stream, &pl, true);
-    if (rc || !pl.needs_finish) return rc;
-    return launch_finish(pl, act, norm, p, out, (hipStream_t)stream);    // with the plan the tiles ran under
+    return run_fused(X, W, b, act, norm, p, out, (hipStream_t)stream);
 }
 
 int fge_static_scratch_init(void) {
@@ -864,7 +967,7 @@ int fge_last_hip_error(void) { return g_last_hip; }
 const char *fge_tile_name(int fused, int act, int norm, const fge_params *p) {
     if (check_common(p, act, norm, true)) return nullptr;
     const Plan pl = make_plan(p, fused ? norm : FGE_NORM_NONE);
-    if (pl.generic) return "generic32x32_scalar";
+    if (pl.generic) return fused && plan_repack(p, norm).use ? "repacked_operands" : "generic32x32_scalar";
     const TileInfo &ti = tile_info(pl.tile);
     return p->in_dtype == FGE_F32 && !(p->flags & FGE_FLAG_IEEE_FP32) ? ti.name_split : ti.name;
 }

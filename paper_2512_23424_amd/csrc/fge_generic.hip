@@ -7,6 +7,9 @@
 //   generic_act_kernel  : dst = act(src) [* second operand]   elementwise
 //   generic_row_kernel  : out = rowop(src)                    one wave per row, passes over src
 //   splitk_sum_kernel   : dst = act(post*(alpha*sum_s P_s + b))  the slices of a K-split product, summed in slice order
+//   pad_rows_kernel     : dense copy of a matrix with K padded by zeros to whole 16-byte chunks
+//                         (and zero rows appended): what makes an operand with odd extents or
+//                         strides fit the vectorised kernels, at one extra read and write of it
 #include "fge_launch.h"
 
 namespace fge {
@@ -168,7 +171,54 @@ __global__ __launch_bounds__(256) void splitk_sum_kernel(const GenArgs a) {
     });
 }
 
+// dst: rows_dst x Kp dense (Kp a multiple of the 16-byte chunk); row r < batch * M is row r of the
+// source (M rows per problem, strides ld / bs), zero filled from K on; rows beyond are zero.
+// One thread per 16-byte chunk of dst: element-granular reads (the source rows need not be
+// aligned), one 16-byte store.
+template <typename T>
+__global__ __launch_bounds__(256) void pad_rows_kernel(const PadArgs a) {
+    constexpr int CW = 16 / (int)sizeof(T);
+    const int cpr = a.Kp / CW;
+    const int64_t total = a.rows_dst * cpr;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int64_t r = idx / cpr;
+        const int k0 = (int)(idx - r * cpr) * CW;
+        T v[CW];
+        const bool live = r < (int64_t)a.batch * a.M;
+        const T *src = live ? row_ptr<T>(a.src, r, a.M, a.ld, a.bs) : nullptr;
+#pragma unroll
+        for (int e = 0; e < CW; ++e) {
+            T z{};
+            v[e] = (live && k0 + e < a.K) ? src[k0 + e] : z;
+        }
+        *reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.dst) + r * a.Kp + k0) = *reinterpret_cast<const uint4 *>(v);
+    }
+}
+
+// dst[0 .. np) = src[0 .. n), zero beyond
+__global__ __launch_bounds__(256) void pad_vec_kernel(const float *src, float *dst, int n, int np) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < np) dst[i] = i < n ? src[i] : 0.0f;
+}
+
 }  // namespace
+
+hipError_t launch_pad_rows(int dtype, hipStream_t s, const PadArgs &a) {
+    const int cw = dtype == FGE_F32 ? 4 : dtype == FGE_F8E4M3 ? 16 : 8;
+    const int64_t total = a.rows_dst * (a.Kp / cw);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;                           // grid-stride beyond that
+    const dim3 grid((unsigned)(blocks > 0 ? blocks : 1)), block(256);
+    if (dtype == FGE_F32)          hipLaunchKernelGGL((pad_rows_kernel<float>), grid, block, 0, s, a);
+    else if (dtype == FGE_F8E4M3)  hipLaunchKernelGGL((pad_rows_kernel<f8_t>), grid, block, 0, s, a);
+    else                           hipLaunchKernelGGL((pad_rows_kernel<bf16_t>), grid, block, 0, s, a);   // any 16-bit type: bits are copied
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_vec(const float *src, float *dst, int n, int np, hipStream_t s) {
+    hipLaunchKernelGGL(pad_vec_kernel, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, s, src, dst, n, np);
+    return hipGetLastError();
+}
 
 hipError_t launch_splitk_sum(int dst_dtype, hipStream_t s, const GenArgs &a) {
     const int64_t total = (int64_t)a.M * (a.N >> 2);

@@ -59,6 +59,18 @@ hipError_t launch_generic_row(int src_dtype, int out_dtype, hipStream_t s, const
 // times post*(alpha*sum2 + b2) when W points to the slices of a second product (gated form)
 hipError_t launch_splitk_sum(int dst_dtype, hipStream_t s, const GenArgs &a);
 
+// Dense, zero-padded copy of an operand (fge_generic.hip): dst is rows_dst x Kp of the same
+// element type, Kp a multiple of the 16-byte chunk; source: batch problems of M rows x K.
+struct PadArgs {
+    const void *src;
+    void *dst;
+    int M, batch, K, Kp;
+    int64_t ld, bs;             // source row stride / stride between problems, in elements
+    int64_t rows_dst;           // >= batch * M; the rows beyond are zero
+};
+hipError_t launch_pad_rows(int dtype, hipStream_t s, const PadArgs &a);
+hipError_t launch_pad_vec(const float *src, float *dst, int n, int np, hipStream_t s);
+
 // Workgroups of `kernel` the current device holds at the same time (0 if the query fails).
 inline int resident_workgroups(const void *kernel, int threads) {
     int per_cu = 0, dev = 0, cus = 0;

@@ -251,6 +251,63 @@ def test_any_shape_takes_the_element_granular_kernels(dt, shape):
             H.check(w, got, gaux, ref, raux, f"any-shape {path} {shape} norm{norm}")
 
 
+@pytest.mark.parametrize("case", [(I.BF16, I.BF16, 333, 257, 515), (I.F32, I.F32, 130, 301, 1001), (I.BF16, I.BF16, 300, 1027, 512),
+                                  (I.F16, I.F16, 260, 515, 2050), (I.F8E4M3, I.BF16, 300, 1000, 520), (I.BF16, I.F32, 2100, 130, 4099)])
+def test_odd_extents_of_large_problems_run_repacked(case):
+    """Extents off the 16-byte grid on a problem large enough to pay for it: the fused call copies
+    X and W into zero-padded dense buffers and runs the tile kernels on them - with the row op
+    fused where the result itself is storable in 16-byte units (third and fifth case), else through
+    fp32 rows of padded width and the element-granular row kernel.  Every row op against the
+    oracle; a workspace that only holds what the element-granular path needs still works."""
+    idt, odt, M, K, N = case
+    for norm in NORMS:
+        act = I.ACT_SILU if norm in (I.NORM_NONE, I.NORM_RMSNORM) else I.ACT_GELU_ERF
+        w = I.Workload(name=f"repack{norm}", M=M, K=K, N=N, in_dtype=idt, out_dtype=odt, act=act, norm=norm,
+                       alpha=1.0 / K ** 0.5 if idt == I.F8E4M3 else 0.5, post_scale=1.5, eps=1e-5,
+                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 1.0 if idt == I.F8E4M3 else 0.1),
+                             "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1), "beta": ("normal", 0.0, 0.1)})
+        t = I.generate(w)
+        d = {k: H.to_device(v) for k, v in t.items()}
+        out = torch.empty(M, N, dtype=H.tdtype(odt), device="cuda")
+        p = B.make_params(d["X"], d["W"], out)
+        assert B.fge_tile_name(True, act, norm, p) == "repacked_operands"
+        ref, raux = H.oracle_chain(w, t)
+        got, gaux = H.run_gpu(w, t, "fused", dev=d)
+        H.check(w, got, gaux, ref, raux, f"repacked {case} norm{norm}")
+    # the room for the element-granular path only: that path runs, same answer within the gate
+    aux = torch.full((M,), float("nan"), device="cuda")
+    out = torch.full((M, N), float("nan"), dtype=H.tdtype(odt), device="cuda")
+    p = B.make_params(d["X"], d["W"], out, alpha=w.alpha, post_scale=w.post_scale, eps=w.eps, gamma=d["gamma"],
+                      beta=d["beta"], aux_out=aux)
+    small = torch.empty(M * N * 4 + 256, dtype=torch.uint8, device="cuda")
+    assert small.numel() < B.fge_workspace_bytes(True, w.act, w.norm, p)
+    p.workspace, p.workspace_bytes = small.data_ptr(), small.numel()
+    B.fused_gemm_epilogue(d["X"], d["W"], d["b"], w.act, w.norm, p, out)
+    torch.cuda.synchronize()
+    H.check(w, H.to_host_f64(out), H.to_host_f64(aux), ref, raux, f"not repacked {case}")
+
+
+def test_odd_strides_of_a_large_batch_run_repacked():
+    """A batch with row and batch strides off the 16-byte grid, large enough to be repacked: the
+    padding between rows and problems is neither read into the result nor written."""
+    w = I.scaled(WL["cfg2"], M=150, K=257, N=515, batch=3)
+    t = I.generate(w)
+    ref, _ = H.oracle_chain(w, t)
+    Xd = torch.full((3, 153, 261), float("nan"), device="cuda"); Xd[:, :150, :257] = torch.from_numpy(t["X"]).cuda().view(3, 150, 257)
+    Wd = torch.full((515, 259), float("nan"), device="cuda"); Wd[:, :257] = torch.from_numpy(t["W"]).cuda()
+    bd, gd, be = (torch.from_numpy(t[k]).cuda() for k in ("b", "gamma", "beta"))
+    outd = torch.full((3, 151, 517), float("nan"), device="cuda")
+    X, W, out = Xd[:, :150, :257], Wd[:, :257], outd[:, :150, :515]
+    p = B.make_params(X, W, out, eps=w.eps, gamma=gd, beta=be)
+    assert B.fge_tile_name(True, w.act, w.norm, p) == "repacked_operands"
+    ws = torch.empty(B.fge_workspace_bytes(True, w.act, w.norm, p), dtype=torch.uint8, device="cuda")
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+    B.fused_gemm_epilogue(X, W, bd, w.act, w.norm, p, out)
+    torch.cuda.synchronize()
+    H.check(w, H.to_host_f64(out).reshape(-1, 515), None, ref, None, "odd strides, repacked")
+    assert torch.isnan(outd[:, 150:, :]).all() and torch.isnan(outd[:, :, 515:]).all()
+
+
 def test_unaligned_strides_and_odd_batches():
     """Aligned extents but row and batch strides that are not multiples of 16 bytes: padding is
     left untouched, results match the oracle."""
