@@ -121,20 +121,24 @@ typedef enum {
  *   operand type (or the narrow-K kernel outside K <= 64, N <= 512, fp32) yields
  *   FGE_ERR_UNSUPPORTED.  Ignored by the gated form and by shapes that take the element-granular
  *   kernels.
+ *   FGE_FLAG_NO_TABLE : choose the tile configuration by the library's rule alone.  Without it, for
+ *   16-bit and 8-bit operands, the choice first consults a table of the fastest verified
+ *   configuration at each point of a sweep over shapes (written by the configuration search of
+ *   the Python package on an MI355X) and takes the entry nearest to the problem when one is near.
  *   FGE_FLAG_TEST_EXPIRE_WAIT : for tests of the bounded wait only.  In the one-kernel form the
  *   first column tile of every row block keeps its arrival mark back and every wait gives up
  *   after one poll, so the waits run out while every workgroup still finishes normally; the
  *   affected rows must come back as NaN and the fault word set. */
-enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_NO_SPLIT_K = 4, FGE_FLAG_TILE_MASK = 0xF00,
+enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_NO_SPLIT_K = 4, FGE_FLAG_NO_TABLE = 8, FGE_FLAG_TILE_MASK = 0xF00,
        FGE_FLAG_TEST_EXPIRE_WAIT = 0x1000 };
 #define FGE_FLAG_TILE(t) ((((int)(t)) + 1) << 8)
 
 /* Tile configurations (rows x columns of one workgroup's output tile).  16-bit and 8-bit
- * operands: 64x64, 64x512, 128x128, 256x256; fp32 operands: 64x64, 64x512, 64x128, 128x128 (split
- * product only) and the persistent narrow-K kernel. */
+ * operands: 64x64, 64x512, 128x128, 128x256, 256x128, 256x256; fp32 operands: 64x64, 64x512,
+ * 64x128, 128x128 (split product only) and the persistent narrow-K kernel. */
 typedef enum {
     FGE_TILE_64x64 = 0, FGE_TILE_64x512 = 1, FGE_TILE_128x128 = 2, FGE_TILE_256x256 = 3,
-    FGE_TILE_NARROW_K = 4, FGE_TILE_64x128 = 5
+    FGE_TILE_NARROW_K = 4, FGE_TILE_64x128 = 5, FGE_TILE_128x256 = 7, FGE_TILE_256x128 = 8
 } fge_tile;
 
 typedef struct fge_params {

@@ -23,6 +23,7 @@ NORM = {"none": 0, "softmax": 1, "layernorm": 2, "rmsnorm": 3, "logsumexp": 4}
 FLAG_TWO_PASS = 1
 FLAG_IEEE_FP32 = 2
 FLAG_NO_SPLIT_K = 4
+FLAG_NO_TABLE = 8
 FLAG_TEST_EXPIRE_WAIT = 0x1000
 STATUS_OK = 0
 

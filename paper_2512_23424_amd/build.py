@@ -14,8 +14,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfge.so")
 OBJDIR = os.path.join(HERE, "_build")
-UNITS = ["fge_api.hip", "fge_tiles_f32.hip", "fge_tiles_f32s.hip", "fge_tiles_bf16.hip", "fge_tiles_f16.hip", "fge_tiles_f8.hip", "fge_panel_f32.hip", "fge_generic.hip", "fge_gated.hip"]
-HEADERS = ["fge_device.h", "fge_epilogue.h", "fge_tile_kernel.h", "fge_panel_kernel.h", "fge_rowops.h", "fge_launch.h"]
+UNITS = ["fge_api.hip", "fge_tiles_f32.hip", "fge_tiles_f32s.hip", "fge_tiles_bf16.hip", "fge_tiles_f16.hip", "fge_tiles_f8.hip", "fge_panel_f32.hip", "fge_generic.hip", "fge_gated.hip",
+         "fge_tiles_half_bf16.hip", "fge_tiles_half_f16.hip", "fge_tiles_half_f8.hip"]
+HEADERS = ["fge_device.h", "fge_epilogue.h", "fge_tile_kernel.h", "fge_panel_kernel.h", "fge_rowops.h", "fge_launch.h", "fge_tile_table.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -5,8 +5,11 @@
 #include <atomic>
 #include <chrono>
 
+#include <cmath>
+
 #include "fge_launch.h"
 #include "fge_rowops.h"
+#include "fge_tile_table.h"
 
 using namespace fge;
 
@@ -80,6 +83,7 @@ bool forced_tile_ok(const fge_params *p) {
     case TILE_128x128: return !f32 || !(p->flags & FGE_FLAG_IEEE_FP32);   // fp32: split product only
     case TILE_256x256: return !f32;
     case TILE_64x128: return f32;
+    case TILE_128x256: case TILE_256x128: return !f32;
     case TILE_PANEL:
         return f32 && !(p->flags & FGE_FLAG_IEEE_FP32) && p->K <= 64 && p->N <= 512 &&
                (p->batch == 1 || (p->batch_stride_x == (int64_t)p->M * p->ldx && p->batch_stride_o == (int64_t)p->M * p->ldo));
@@ -92,7 +96,7 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
     if (p == nullptr) return FGE_ERR_NULL;
     if (act < FGE_ACT_NONE || act > FGE_ACT_CLAMP) return FGE_ERR_BAD_ENUM;
     if (norm < FGE_NORM_NONE || norm > FGE_NORM_LOGSUMEXP) return FGE_ERR_BAD_ENUM;
-    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32 | FGE_FLAG_NO_SPLIT_K | FGE_FLAG_TILE_MASK | FGE_FLAG_TEST_EXPIRE_WAIT))
+    if (p->flags & ~(FGE_FLAG_TWO_PASS | FGE_FLAG_IEEE_FP32 | FGE_FLAG_NO_SPLIT_K | FGE_FLAG_TILE_MASK | FGE_FLAG_TEST_EXPIRE_WAIT | FGE_FLAG_NO_TABLE))
         return FGE_ERR_BAD_ENUM;
     if (!forced_tile_ok(p)) return FGE_ERR_UNSUPPORTED;
     if (p->in_dtype < FGE_F32 || p->in_dtype > FGE_F8E4M3 || p->out_dtype < FGE_F32 || p->out_dtype > FGE_F8E4M3)
@@ -137,7 +141,64 @@ constexpr int PANEL_MIN_ROWS = 4096;   // below this the persistent kernel canno
 // shapes).  The rule is the same everywhere: the largest tile of the operand type's list that
 // still gives every CU a workgroup and is not much wider than the row; whether the rows end up
 // split over column tiles matters little, since split rows cost one small exchange.
-int pick_tile(const Problem &pr, int in_dtype, int /*norm*/, bool ieee_fp32) {
+// 16- and 8-bit operands first ask the table that the configuration search wrote
+// (fge_tile_table.h: the fastest verified configuration at each point of a sweep over shapes): the
+// entry nearest to the problem - in 256-row and 256-column tiles and in K, on a log2 scale, with
+// the same operand class and the same answer to "does a row op follow" - decides when it lies
+// within a factor of about 1.5 of the problem in total; elsewhere, and where the rule below is
+// asked for by the caller, the rule decides.
+// Rounds of the chip a tiling of rows x cols outputs takes: workgroups over the workgroups the
+// chip holds at once (two per CU for tiles of up to 128x128, else one).
+int64_t tile_rounds(int t, int64_t rows, int64_t cols, int batch) {
+    const TileInfo &ti = tile_info(t);
+    const int64_t count = ((rows + ti.bm - 1) / ti.bm) * ((cols + ti.bn - 1) / ti.bn) * batch;
+    const int64_t capacity = (int64_t)num_cu() * (ti.bm * ti.bn <= 128 * 128 ? 2 : 1);
+    return (count + capacity - 1) / capacity;
+}
+
+// The nearest table entry of the problem's class whose tile configuration takes as many rounds
+// of the chip on this problem as it took at the entry's own shape: a find made where a tiling
+// just filled the chip says nothing about a slightly larger problem that spills into a second
+// round.
+const TileTableEntry *table_entry(const Problem &pr, int in_dtype, int norm) {
+    if (in_dtype == FGE_F32) return nullptr;
+    const int cls = in_dtype == FGE_F8E4M3 ? 1 : 0, rowop = norm != FGE_NORM_NONE;
+    const double mt = std::log2((double)((pr.M + 255) / 256) * pr.batch), nt = std::log2((double)((pr.N + 255) / 256)),
+                 k = std::log2((double)pr.K);
+    double best = 0.6;
+    const TileTableEntry *hit = nullptr;
+    for (const TileTableEntry &e : TILE_TABLE) {
+        if (e.cls != cls || e.rowop != rowop || e.tile >= TILE_COUNT) continue;
+        const double d = std::fabs(mt - std::log2((double)e.mt)) + std::fabs(nt - std::log2((double)e.nt)) +
+                         std::fabs(k - std::log2((double)e.K));
+        if (d >= best) continue;
+        if (tile_rounds(e.tile, pr.M, pr.N, pr.batch) != tile_rounds(e.tile, (int64_t)e.mt * 256, (int64_t)e.nt * 256, 1)) continue;
+        best = d;
+        hit = &e;
+    }
+    return hit;
+}
+
+int rule_tile(const Problem &pr, int in_dtype, bool ieee_fp32);
+
+// use_table false: the rule alone (FGE_FLAG_NO_TABLE - what the search compares its finds with).
+int pick_tile(const Problem &pr, int in_dtype, int norm, bool ieee_fp32, bool use_table = true) {
+    const int rule = rule_tile(pr, in_dtype, ieee_fp32);
+    if (!use_table) return rule;
+    // few 64x64 tiles and a long K: the K slices (k_split) build on that tile - the table was swept
+    // with K left whole and has no say here
+    const int64_t t64 = (int64_t)((pr.M + 63) / 64) * ((pr.N + 63) / 64) * pr.batch;
+    if (rule == TILE_64x64 && t64 <= num_cu() && pr.K >= 2048) return rule;
+    if (const TileTableEntry *e = table_entry(pr, in_dtype, norm)) {
+        const int t = e->tile;
+        if (t < TILE_COUNT && t != TILE_PANEL && t != TILE_64x128 && t != TILE_GATED &&
+            tile_info(t).bn <= (pr.N > 32 ? 2 * pr.N : 64))
+            return t;
+    }
+    return rule;
+}
+
+int rule_tile(const Problem &pr, int in_dtype, bool ieee_fp32) {
     auto count = [&](int t) {
         const TileInfo &ti = tile_info(t);
         return (int64_t)((pr.M + ti.bm - 1) / ti.bm) * ((pr.N + ti.bn - 1) / ti.bn) * pr.batch;
@@ -186,7 +247,8 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
     }
     pl.tile = force_tile >= 0        ? force_tile
               : forced_tile(p) >= 0 ? forced_tile(p)
-                                    : pick_tile(pr, p->in_dtype, norm, (p->flags & FGE_FLAG_IEEE_FP32) != 0);
+                                    : pick_tile(pr, p->in_dtype, norm, (p->flags & FGE_FLAG_IEEE_FP32) != 0,
+                                                !(p->flags & FGE_FLAG_NO_TABLE));
     const TileInfo &ti = tile_info(pl.tile);
     pl.tiles_m = (pr.M + ti.bm - 1) / ti.bm;
     pl.tiles_n = (pr.N + ti.bn - 1) / ti.bn;
@@ -199,7 +261,13 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
     // second pass; equal at 64); logsumexp leaves `out` final in the first pass, so its second
     // pass only writes aux and wins from 32 column tiles on
     const int coop_max_tiles = norm == FGE_NORM_LOGSUMEXP ? 16 : 64;
-    pl.coop = pl.split && !two_pass && !(p->flags & FGE_FLAG_TWO_PASS) && tile_has_coop(pl.tile, p->in_dtype) &&
+    // (the table may also say that the second pass is the faster way to finish this problem's rows:
+    // a persistent grid that does not divide the row blocks evenly idles part of the chip in its
+    // last round)
+    bool table_two_pass = false;
+    if (force_tile < 0 && forced_tile(p) < 0 && !(p->flags & FGE_FLAG_NO_TABLE))
+        if (const TileTableEntry *e = table_entry(pr, p->in_dtype, norm)) table_two_pass = e->tile == pl.tile && e->two_pass;
+    pl.coop = pl.split && !two_pass && !table_two_pass && !(p->flags & FGE_FLAG_TWO_PASS) && tile_has_coop(pl.tile, p->in_dtype) &&
               capacity >= pl.tiles_n && pl.tiles_n <= coop_max_tiles;
     if (pl.coop) {
         const int64_t total = (int64_t)pl.tiles_m * pl.tiles_n * pr.batch;
@@ -389,6 +457,10 @@ int launch_tiles(const TileArgs &a, const fge_params *p, const Plan &pl, hipStre
     }
     const dim3 grid(a.coop ? (unsigned)pl.coop_grid : (unsigned)(pl.tiles_m * pl.tiles_n), 1,
                     a.coop ? 1u : (unsigned)pl.pr.batch);
+    if (pl.tile == TILE_128x256 || pl.tile == TILE_256x128)
+        return hip_status(p->in_dtype == FGE_BF16  ? launch_half_bf16(pl.tile, p->out_dtype, grid, s, a)
+                          : p->in_dtype == FGE_F16 ? launch_half_f16(pl.tile, p->out_dtype, grid, s, a)
+                                                   : launch_half_f8(pl.tile, p->out_dtype, grid, s, a));
     const hipError_t e = p->in_dtype == FGE_BF16       ? launch_tile_bf16(pl.tile, p->out_dtype, grid, s, a)
                          : p->in_dtype == FGE_F16      ? launch_tile_f16(pl.tile, p->out_dtype, grid, s, a)
                          : p->in_dtype == FGE_F8E4M3   ? launch_tile_f8(pl.tile, p->out_dtype, grid, s, a)

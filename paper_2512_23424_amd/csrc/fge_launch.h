@@ -5,7 +5,7 @@
 namespace fge {
 
 enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_64x128 = 5,
-              TILE_GATED = 6, TILE_COUNT = 7 };
+              TILE_GATED = 6, TILE_128x256 = 7, TILE_256x128 = 8, TILE_COUNT = 9 };
 
 // coop_per_cu: workgroups of this tile's cooperative kernel that are resident on one CU at the
 // same time (from the compiler's register / LDS report; a lower bound is safe), 0 if the tile
@@ -23,6 +23,10 @@ inline const TileInfo &tile_info(int id) {
         {64, 128, 256, 2, 2, "64x128_w2x2", "64x128_w2x2_splitbf16"},
         // gated form, 16-bit operands: 256 rows x 128 output columns (two 256x128 products)
         {256, 128, 512, 4, 1, "gated256x128_w2x4", nullptr},
+        // 16-bit and 8-bit operands: half a 256x256 tile either way, eight waves of 64x64 - twice the
+        // workgroups of the 256x256 tiling for problems that leave it short of them
+        {128, 256, 512, 4, 1, "128x256_w2x4", nullptr},
+        {256, 128, 512, 2, 1, "256x128_w4x2", nullptr},
     };
     return t[id];
 }
@@ -194,6 +198,35 @@ inline hipError_t launch_gated_any(int out_dtype, dim3 grid, hipStream_t s, cons
 #undef FGE_GATED
     return hipGetLastError();
 }
+// The half-tile configurations (TILE_128x256, TILE_256x128), ordinary or cooperative launch;
+// defined in fge_tiles_half.hip.
+template <typename InT>
+inline hipError_t launch_half_any(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a) {
+    typedef typename NarrowOut<InT>::type NarrowT;
+#define FGE_HALF(BM, BN, WM, WN, OT)                                                            \
+    do {                                                                                        \
+        if (a.coop) {                                                                           \
+            auto kern = tile_kernel<InT, OT, BM, BN, WM, WN, true, false>;                      \
+            static const int resident = resident_workgroups(reinterpret_cast<const void *>(kern), 512); \
+            if ((int)grid.x > resident) return hipErrorCooperativeLaunchTooLarge;               \
+            hipLaunchKernelGGL(kern, grid, dim3(512), 0, s, a);                                 \
+        } else {                                                                                \
+            hipLaunchKernelGGL((tile_kernel<InT, OT, BM, BN, WM, WN, false, false>), grid, dim3(512), 0, s, a); \
+        }                                                                                       \
+    } while (0)
+    if (tile == TILE_128x256) {
+        if (out_dtype != FGE_F32) FGE_HALF(128, 256, 2, 4, NarrowT); else FGE_HALF(128, 256, 2, 4, float);
+    } else if (tile == TILE_256x128) {
+        if (out_dtype != FGE_F32) FGE_HALF(256, 128, 4, 2, NarrowT); else FGE_HALF(256, 128, 4, 2, float);
+    } else {
+        return hipErrorInvalidValue;
+    }
+#undef FGE_HALF
+    return hipGetLastError();
+}
+hipError_t launch_half_bf16(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
+hipError_t launch_half_f16(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
+hipError_t launch_half_f8(int tile, int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_gated_bf16(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_gated_f16(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
 hipError_t launch_gated_f8(int out_dtype, dim3 grid, hipStream_t s, const TileArgs &a);
@@ -201,6 +234,7 @@ hipError_t launch_gated_f8(int out_dtype, dim3 grid, hipStream_t s, const TileAr
 // Whether launch_tile_any has a cooperative kernel for this tile and operand type.
 inline bool tile_has_coop(int tile, int in_dtype) {
     if (tile == TILE_GATED) return true;
+    if (tile == TILE_128x256 || tile == TILE_256x128) return in_dtype != FGE_F32;
     return in_dtype != FGE_F32 ? (tile == TILE_128x128 || tile == TILE_256x256)
                                : (tile == TILE_64x128 || tile == TILE_128x128);
 }

@@ -1,47 +1,167 @@
-"""Search over the library's launch configurations for one problem.
+"""Search over the library's launch configurations, and the table the library's tile choice reads.
 
-The paper's optimisation loop (its evolutionary search, Section 3.5) proposes kernel variants,
-has the Verifier accept or reject each one, times the accepted ones and keeps the fastest.  The
-configuration space of this library is small and discrete - tile configuration x how split rows
-are finished x (fp32 operands) which matrix instruction multiplies x whether a long K is cut
-into slices - so the search here visits
-all of it instead of evolving a population: every configuration the library accepts for the
-problem is run, checked against the automatic configuration's result (the Verifier's element
-rule with the tolerance of the storage type), timed, and the table is returned fastest first.
+The paper optimises a kernel by proposing variants, letting its Verifier accept or reject each
+against the framework-level reference, timing the accepted ones and keeping the fastest (the
+evolutionary search of its Section 3.5, thresholds of Section 4.1).  Here the variants are the
+library's launch configurations - tile configuration x how split rows are finished x (fp32
+operands) which matrix instruction multiplies x whether a long K is cut into slices - selected
+through FGE_FLAG_TILE, FGE_FLAG_TWO_PASS, FGE_FLAG_IEEE_FP32 and FGE_FLAG_NO_SPLIT_K, and the
+language model is taken out: candidates are designed from what the fast and the slow members of
+a population disagree on.  Three uses:
 
-    python -m paper_2512_23424_amd.tune cfg2            # one of the built-in workloads
+    python -m paper_2512_23424_amd.tune cfg2                # every configuration of one workload, timed
+    python -m paper_2512_23424_amd.tune cfg2 --evolve       # the island search on the same space
+    python -m paper_2512_23424_amd.tune --write-table       # sweep of shapes -> csrc/fge_tile_table.h
 
-    python -m paper_2512_23424_amd.tune cfg2 --evolve   # the paper's loop instead of the full visit
-
-`evolve` is that loop itself (Section 3.5, its algorithm "Iterative Search-Based Optimization")
-with the language model taken out: K islands, R rounds, P candidates per island and round; the
-parents of a round are a stratified sample of the island's population (its fastest and its
-slowest members); a candidate is designed from an elite member by changing the choices on
-which the fast parents differ from the slow ones (else an untried choice); the Verifier admits
-it to the population only if its result passes; every M rounds each island receives the elite
-of its neighbour; the answer is the fastest member of any island.  Here it reaches the same
-configuration as the full visit with fewer kernel runs only when the space grows; it is kept
-as the search driver for larger configuration spaces and is tested on synthetic ones.
-
-The search only uses the public entry points; FGE_FLAG_TILE, FGE_FLAG_TWO_PASS, FGE_FLAG_IEEE_FP32
-and FGE_FLAG_NO_SPLIT_K select the configuration.  It is a tool around the library, not part of a call's hot path."""
+The Verifier (`Verifier` below) is the paper's: a candidate's result is compared, on sampled
+rows, with a reference written in the framework's own operators (torch, float64) under the
+element rule - relative error above a small constant, absolute below it, at most a fraction
+tau of the elements beyond tau - with tau of the storage type.  The table written by
+--write-table holds, per sweep shape, the configuration the search found fastest; the library's
+tile choice takes the entry nearest to a problem (in units of 256-row / 256-column tiles and K,
+on a log scale) and falls back to its rule where none is near.  This module is a tool around
+the library, not part of a call's hot path."""
 from __future__ import annotations
 
+import math
+import os
 import random
 import sys
-from typing import Callable, Dict, List, Optional, Sequence, Tuple
+from typing import Callable, Dict, Iterator, List, Optional, Sequence, Tuple
 
 import torch
 
 from . import binding as B
 from . import inputs as I
 
-TILES = {"64x64": 0, "64x512": 1, "128x128": 2, "256x256": 3, "narrow_k": 4, "64x128": 5}
+TILES = {"64x64": 0, "64x512": 1, "128x128": 2, "256x256": 3, "narrow_k": 4, "64x128": 5, "128x256": 7, "256x128": 8}
+_TAU = {I.F32: 1e-3, I.BF16: 2e-2, I.F16: 4e-3, I.F8E4M3: 2e-2}
 _TOL = {I.F32: 1e-4, I.BF16: 2e-2, I.F16: 4e-3, I.F8E4M3: 2e-2}
+TABLE_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "fge_tile_table.h")
 
 
 def flag_tile(tile: int) -> int:
     return (tile + 1) << 8
+
+
+# ---------------------------------------------------------------- the Verifier
+class Verifier:
+    """Accepts or rejects the result of one fused call.  The reference is the operator chain in
+    torch float64 on a sample of rows (the framework-level reference implementation of the
+    paper's Section 3.2.3), computed once per problem."""
+
+    def __init__(self, X, W, b, act: int, norm: int, *, rows: int = 48, alpha=1.0, post_scale=1.0, clamp_lo=0.0,
+                 clamp_hi=0.0, eps=0.0, gamma=None, beta=None, aux_out=None, **_):
+        X2 = X.reshape(-1, X.shape[-1])
+        n = X2.shape[0]
+        g = torch.Generator(device="cpu").manual_seed(5)
+        self.rows = torch.unique(torch.cat([torch.tensor([0, n - 1]), torch.randint(0, n, (min(rows, n),), generator=g)])).to(X.device)
+        def f64(t):              # (8-bit tensors: rows are picked on the byte view, widened through fp32)
+            return None if t is None else t.to(torch.float32).to(torch.float64)
+        Xs = X2.view(torch.uint8)[self.rows].view(X2.dtype) if X2.element_size() == 1 else X2[self.rows]
+        y = f64(Xs) @ f64(W).T * alpha
+        if b is not None:
+            y = y + f64(b)
+        y = y * post_scale
+        if act == I.ACT_RELU:
+            a = torch.clamp_min(y, 0.0)
+        elif act == I.ACT_GELU_TANH:
+            a = 0.5 * y * (1.0 + torch.tanh(math.sqrt(2.0 / math.pi) * (y + 0.044715 * y ** 3)))
+        elif act == I.ACT_GELU_ERF:
+            a = 0.5 * y * (1.0 + torch.erf(y / math.sqrt(2.0)))
+        elif act == I.ACT_SILU:
+            a = y * torch.sigmoid(y)
+        elif act == I.ACT_CLAMP:
+            a = torch.minimum(torch.maximum(y, torch.tensor(float(clamp_lo), dtype=torch.float64, device=y.device)),
+                              torch.tensor(float(clamp_hi), dtype=torch.float64, device=y.device))
+        else:
+            a = y
+        self.ref_aux = None
+        if norm == I.NORM_SOFTMAX:
+            ref = torch.softmax(a, dim=-1)
+        elif norm == I.NORM_LAYERNORM:
+            mu, var = a.mean(dim=-1, keepdim=True), a.var(dim=-1, unbiased=False, keepdim=True)
+            ref = (a - mu) / torch.sqrt(var + eps)
+            ref = ref * (f64(gamma) if gamma is not None else 1.0) + (f64(beta) if beta is not None else 0.0)
+        elif norm == I.NORM_RMSNORM:
+            ref = a / torch.sqrt((a * a).mean(dim=-1, keepdim=True) + eps) * (f64(gamma) if gamma is not None else 1.0)
+        elif norm == I.NORM_LOGSUMEXP:
+            ref, self.ref_aux = a, torch.logsumexp(a, dim=-1)
+        else:
+            ref = a
+        self.ref = ref
+        self.aux_out = aux_out
+        self.tau, self.tol = _TAU[B._dt(X)], _TOL[B._dt(X)]
+
+    def deviation(self, out: torch.Tensor) -> Tuple[float, float]:
+        """(largest row-floored relative error, fraction of elements beyond tau) on the sampled rows."""
+        got = out.reshape(-1, out.shape[-1])[self.rows].to(torch.float64)
+        floor = self.ref.abs().mean(dim=-1, keepdim=True)
+        floor = torch.where(floor > 0, floor, torch.ones_like(floor))
+        err = (got - self.ref).abs() / torch.maximum(self.ref.abs(), floor)
+        big = self.ref.abs() > floor
+        rule = torch.where(big, (got - self.ref).abs() / torch.where(big, self.ref.abs(), torch.ones_like(floor)), (got - self.ref).abs())
+        worst = float(err.max()) if bool(torch.isfinite(err).all()) else float("nan")
+        return worst, float((~(rule <= self.tau)).double().mean())
+
+    def accepts(self, out: torch.Tensor) -> Tuple[bool, float]:
+        worst, frac = self.deviation(out)
+        ok = worst <= 2.0 * self.tol and frac <= self.tau           # (NaN fails both)
+        if ok and self.ref_aux is not None:
+            aux = self.aux_out.reshape(-1)[self.rows].to(torch.float64)
+            ok = bool((((aux - self.ref_aux).abs() / self.ref_aux.abs()) <= self.tau).all())
+        return ok, worst
+
+
+def _timed(call: Callable[[], None], steps: int, warmup: int) -> float:
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+class Problem:
+    """One fused call to tune: the tensors, the chain, and a way to run it under given flags."""
+
+    def __init__(self, X, W, b, act, norm, out: torch.Tensor, **params):
+        self.X, self.W, self.b, self.act, self.norm, self.out, self.params = X, W, b, act, norm, out, params
+        self.verifier = Verifier(X, W, b, act, norm, **params)
+
+    def make_params(self, flags: int) -> B.FgeParams:
+        return B.make_params(self.X, self.W, self.out, flags=flags, **self.params)
+
+    def describe(self, flags: int) -> Optional[Dict]:
+        """What the library would run under `flags`, None if it refuses them."""
+        p = self.make_params(flags)
+        try:
+            kernel = B.fge_tile_name(True, self.act, self.norm, p)
+            slices = B.fge_fused_k_slices(self.act, self.norm, p)
+            one_kernel = B.fge_fault_word_offset(self.act, self.norm, p) is not None
+            finish = slices == 1 and not one_kernel and B.fge_fused_needs_finish(self.act, self.norm, p)
+        except B.FgeError:
+            return None
+        if slices > 1:                          # partial products, their sum, (row op)
+            kernel += f" k/{slices}"
+        return {"kernel": kernel, "finish": finish,
+                "kernels": (2 if self.norm == I.NORM_NONE else 3) if slices > 1 else 2 if finish else 1}
+
+    def run(self, flags: int, steps: int, warmup: int) -> Tuple[bool, float, float]:
+        """(accepted by the Verifier, ms per call, deviation)."""
+        p = self.make_params(flags)
+        ws = torch.empty(max(B.fge_workspace_bytes(True, self.act, self.norm, p), 16), dtype=torch.uint8, device=self.out.device)
+        p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+        call = lambda: B.fused_gemm_epilogue(self.X, self.W, self.b, self.act, self.norm, p, self.out)
+        self.out.fill_(float("nan"))
+        call()
+        torch.cuda.synchronize()
+        ok, dev = self.verifier.accepts(self.out)
+        return ok, _timed(call, steps, warmup), dev
 
 
 def candidates(make_params: Callable[[int], B.FgeParams], act, norm) -> List[Dict]:
@@ -58,7 +178,8 @@ def candidates(make_params: Callable[[int], B.FgeParams], act, norm) -> List[Dic
                     try:
                         kernel = B.fge_tile_name(True, act, norm, p)
                         slices = B.fge_fused_k_slices(act, norm, p)
-                        finish = slices == 1 and B.fge_fused_needs_finish(act, norm, p)
+                        one_kernel = B.fge_fault_word_offset(act, norm, p) is not None
+                        finish = slices == 1 and not one_kernel and B.fge_fused_needs_finish(act, norm, p)
                     except B.FgeError:
                         continue
                     if slices > 1:                      # partial products, their sum, (row op)
@@ -74,60 +195,58 @@ def candidates(make_params: Callable[[int], B.FgeParams], act, norm) -> List[Dic
     return out
 
 
-def _deviation(got: torch.Tensor, ref: torch.Tensor) -> float:
-    g, r = got.double(), ref.double()
-    floor = r.abs().mean(dim=-1, keepdim=True)
-    return float(((g - r).abs() / torch.maximum(r.abs(), floor)).max())
-
-
 def tune(X, W, b, act, norm, out: torch.Tensor, *, steps: int = 20, warmup: int = 5, **params) -> List[Dict]:
-    """Run, check and time every configuration for fused_gemm_epilogue(X, W, b, act, norm) -> out.
+    """Run, verify and time every configuration for fused_gemm_epilogue(X, W, b, act, norm) -> out.
     `params` are the keyword arguments of binding.make_params (alpha, eps, gamma, ...)."""
-    def make_params(flags: int) -> B.FgeParams:
-        return B.make_params(X, W, out, flags=flags, **params)
-    ref: Optional[torch.Tensor] = None
+    prob = Problem(X, W, b, act, norm, out, **params)
     table = []
-    for c in candidates(make_params, act, norm):
-        p = make_params(c["flags"])
-        ws = torch.empty(max(B.fge_workspace_bytes(True, act, norm, p), 16), dtype=torch.uint8, device=out.device)
-        p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
-        out.fill_(float("nan"))
-        B.fused_gemm_epilogue(X, W, b, act, norm, p, out)
-        torch.cuda.synchronize()
-        if ref is None:                     # the automatic configuration comes first
-            ref = out.clone()
-        dev = _deviation(out, ref)
-        ok = bool(torch.isfinite(out).all()) and dev <= 2.0 * _TOL[p.out_dtype if p.out_dtype != I.F32 else p.in_dtype]
-        for _ in range(warmup):
-            B.fused_gemm_epilogue(X, W, b, act, norm, p, out)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            B.fused_gemm_epilogue(X, W, b, act, norm, p, out)
-        e1.record()
-        torch.cuda.synchronize()
-        table.append(dict(c, ms=e0.elapsed_time(e1) / steps, deviation=dev, accepted=ok))
+    for c in candidates(prob.make_params, act, norm):
+        ok, ms, dev = prob.run(c["flags"], steps, warmup)
+        table.append(dict(c, ms=ms, deviation=dev, accepted=ok))
     return sorted(table, key=lambda r: (not r["accepted"], r["ms"]))
 
 
-# ---------------------------------------------------------------- the paper's search loop
+# ---------------------------------------------------------------- the island search
 Config = Tuple                      # one value per gene, in the order of the gene list
 
 
 class Island:
-    def __init__(self) -> None:
-        self.population: List[Tuple[Config, float]] = []     # verified candidates with their time
+    """A population of verified configurations with their times, and what was tried here."""
+
+    def __init__(self, rng: random.Random, genes: Sequence[Sequence], elite_size: int) -> None:
+        self.rng, self.genes, self.elite_size = rng, genes, elite_size
+        self.population: List[Tuple[Config, float]] = []
         self.tried: set = set()                                # everything evaluated here, valid or not
         self.elite: List[Tuple[Config, float]] = []
         self.received: List[Tuple[Config, float]] = []         # what migration brought in
+        self.turns = 0
 
-    def add(self, c: Config, ms: float) -> None:
+    def admit(self, c: Config, ms: float) -> None:
         if all(c != q for q, _ in self.population):
             self.population.append((c, ms))
 
-    def update_elite(self, n: int) -> None:
-        self.elite = sorted(self.population, key=lambda e: e[1])[:n]
+    def rank(self) -> None:
+        self.elite = sorted(self.population, key=lambda e: e[1])[:self.elite_size]
+
+    def proposals(self, n: int) -> Iterator[Config]:
+        """Up to n untried candidates, each designed from the population as it stood when the
+        turn began: an elite member changed where the island's fast and slow members disagree."""
+        top, bottom = stratified_sample(self.population)
+        pool = self.elite or top
+        for _ in range(n):
+            base = self.rng.choice(pool)[0] if pool else None
+            c = design(self.genes, base, top, bottom, self.tried, self.rng)
+            if c in self.tried:
+                continue                                        # nothing new around here
+            self.tried.add(c)
+            yield c
+
+    def receive(self, members: Sequence[Tuple[Config, float]]) -> None:
+        for c, ms in members:
+            self.admit(c, ms)
+            self.tried.add(c)
+            self.received.append((c, ms))
+        self.rank()
 
 
 def stratified_sample(population: Sequence[Tuple[Config, float]], n: int = 2):
@@ -165,96 +284,168 @@ def design(genes: Sequence[Sequence], base: Optional[Config], top, bottom, tried
     return tuple(rng.choice(list(v)) for v in genes)
 
 
+class IslandSearch:
+    """K islands take turns; in a turn an island proposes up to P candidates, the Verifier admits
+    the valid ones with their time, and the island re-ranks its elite.  After every
+    `migrate_every` rounds of turns each island receives the elite of its neighbour on a ring.
+    The answer is the fastest member of any island.  (Section 3.5 of the paper; R = 3, P = 4,
+    K = 2 are its settings, Section 4.1.)"""
+
+    def __init__(self, evaluate: Callable[[Config], Tuple[bool, float]], genes: Sequence[Sequence], *, parallel: int = 4,
+                 islands: int = 2, migrate_every: int = 1, elite: int = 2, seed: int = 0):
+        rng = random.Random(seed)
+        self.evaluate, self.parallel, self.migrate_every = evaluate, parallel, migrate_every
+        self.islands = [Island(rng, genes, elite) for _ in range(islands)]
+
+    def turn(self, island: Island) -> None:
+        for c in island.proposals(self.parallel):
+            valid, ms = self.evaluate(c)
+            if valid:
+                island.admit(c, ms)
+        island.rank()
+        island.turns += 1
+
+    def migrate(self) -> None:
+        outgoing = [list(k.elite) for k in self.islands]
+        for i, k in enumerate(self.islands):
+            k.receive(outgoing[i - 1])                           # ring: i receives from i-1
+
+    def run(self, rounds: int):
+        for r in range(1, rounds + 1):
+            for k in self.islands:
+                self.turn(k)
+            if len(self.islands) > 1 and r % self.migrate_every == 0:
+                self.migrate()
+        return self.best()
+
+    def best(self):
+        members = [e for k in self.islands for e in k.population]
+        if not members:
+            return None, float("inf")
+        return min(members, key=lambda e: e[1])
+
+
 def evolve(evaluate: Callable[[Config], Tuple[bool, float]], genes: Sequence[Sequence], *, rounds: int = 3,
            parallel: int = 4, islands: int = 2, migrate_every: int = 1, elite: int = 2, seed: int = 0):
-    """The loop of the paper's Section 3.5 over a discrete configuration space.  evaluate(config)
-    is the Verifier: (valid, time).  Defaults are the paper's settings (R = 3, P = 4, K = 2,
-    Section 4.1).  Returns (best config, its time, the islands)."""
-    rng = random.Random(seed)
-    isl = [Island() for _ in range(islands)]
-    for r in range(1, rounds + 1):
-        for k in isl:
-            top, bottom = stratified_sample(k.population)
-            for _ in range(parallel):
-                pool = k.elite or top
-                base = rng.choice(pool)[0] if pool else None
-                c = design(genes, base, top, bottom, k.tried, rng)
-                if c in k.tried:
-                    continue                              # nothing new around here
-                k.tried.add(c)
-                valid, ms = evaluate(c)
-                if valid:
-                    k.add(c, ms)
-            k.update_elite(elite)
-        if r % migrate_every == 0 and islands > 1:
-            incoming = [list(isl[i - 1].elite) for i in range(islands)]      # ring: i receives from i-1
-            for i, k in enumerate(isl):
-                for c, ms in incoming[i]:
-                    k.add(c, ms)
-                    k.tried.add(c)
-                    k.received.append((c, ms))
-                k.update_elite(elite)
-    members = [e for k in isl for e in k.population]
-    if not members:
-        return None, float("inf"), isl
-    best = min(members, key=lambda e: e[1])
-    return best[0], best[1], isl
+    """IslandSearch over a discrete configuration space; evaluate(config) is the Verifier:
+    (valid, time).  Returns (best config, its time, the islands)."""
+    s = IslandSearch(evaluate, genes, parallel=parallel, islands=islands, migrate_every=migrate_every, elite=elite, seed=seed)
+    best, ms = s.run(rounds)
+    return best, ms, s.islands
+
+
+def library_genes(in_dtype: int) -> List[List]:
+    """Tile configuration (None: the library's own choice), split-row form, fp32 instruction, K slices."""
+    return [[None] + list(TILES), [0, B.FLAG_TWO_PASS], [0, B.FLAG_IEEE_FP32] if in_dtype == I.F32 else [0],
+            [0, B.FLAG_NO_SPLIT_K]]
 
 
 def evolve_library(X, W, b, act, norm, out: torch.Tensor, *, steps: int = 20, warmup: int = 5, seed: int = 0,
-                   **params):
-    """evolve() over the library's launch configurations for one problem: genes are the tile
-    configuration (None = the automatic choice), the split-row form and, for fp32 operands, the
-    matrix instruction.  The Verifier runs the candidate, compares with the automatic
-    configuration's result (element rule, tolerance of the storage type) and times it; a
-    configuration the library refuses is invalid."""
-    base = B.make_params(X, W, out, flags=0, **params)
-    genes = [[None] + list(TILES), [0, B.FLAG_TWO_PASS], [0, B.FLAG_IEEE_FP32] if base.in_dtype == I.F32 else [0],
-             [0, B.FLAG_NO_SPLIT_K]]
-    ref: List[Optional[torch.Tensor]] = [None]
+                   rounds: int = 3, **params):
+    """The island search over the library's launch configurations for one problem.  The Verifier
+    runs the candidate, checks it against the torch float64 reference and times it; a
+    configuration the library refuses is invalid.  Returns (best, its ms, everything evaluated)."""
+    prob = Problem(X, W, b, act, norm, out, **params)
     seen: Dict[Config, Dict] = {}
-
-    def run(flags):
-        p = B.make_params(X, W, out, flags=flags, **params)
-        ws = torch.empty(max(B.fge_workspace_bytes(True, act, norm, p), 16), dtype=torch.uint8, device=out.device)
-        p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
-        return p, ws
+    by_kernel: Dict[Tuple, Dict] = {}
 
     def evaluate(c: Config):
         if c in seen:                               # another island has run it already
             return seen[c]["accepted"], seen[c]["ms"]
         tname, two_pass, ieee, whole_k = c
         flags = (0 if tname is None else flag_tile(TILES[tname])) | two_pass | ieee | whole_k
-        try:
-            p, ws = run(flags)
-            kernel = B.fge_tile_name(True, act, norm, p)
-        except B.FgeError:
+        d = prob.describe(flags)
+        if d is None:
             return False, float("inf")
-        if ref[0] is None:
-            p0, ws0 = run(0)
-            out.fill_(float("nan"))
-            B.fused_gemm_epilogue(X, W, b, act, norm, p0, out)
-            torch.cuda.synchronize()
-            ref[0] = out.clone()
-        out.fill_(float("nan"))
-        B.fused_gemm_epilogue(X, W, b, act, norm, p, out)
-        torch.cuda.synchronize()
-        dev = _deviation(out, ref[0])
-        ok = bool(torch.isfinite(out).all()) and dev <= 2.0 * _TOL[p.out_dtype if p.out_dtype != I.F32 else p.in_dtype]
-        for _ in range(warmup):
-            B.fused_gemm_epilogue(X, W, b, act, norm, p, out)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            B.fused_gemm_epilogue(X, W, b, act, norm, p, out)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
-        seen[c] = {"kernel": kernel, "ms": ms, "accepted": ok, "deviation": dev}
-        return ok, ms
-    best, ms, isl = evolve(evaluate, genes, seed=seed)
+        key = (d["kernel"], d["finish"])
+        if key not in by_kernel:                    # different genes, same launch: timed once
+            ok, ms, dev = prob.run(flags, steps, warmup)
+            by_kernel[key] = {"kernel": d["kernel"], "ms": ms, "accepted": ok, "deviation": dev, "flags": flags}
+        seen[c] = by_kernel[key]
+        return seen[c]["accepted"], seen[c]["ms"]
+    best, ms, _ = evolve(evaluate, library_genes(B._dt(X)), seed=seed, rounds=rounds)
     return best, ms, seen
+
+
+# ---------------------------------------------------------------- the tile table
+# One entry per sweep point: operand class (0: 16-bit, 1: 8-bit), whether a row op follows,
+# ceil(M / 256), ceil(N / 256), K, and the tile id of the fastest verified configuration.
+SWEEP_MT = (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 64)
+SWEEP_NT = (2, 4, 8, 16, 32)
+SWEEP_K = (256, 1024, 4096)
+
+
+def sweep(quick: bool = False, log=print) -> List[Tuple]:
+    """Per sweep point (class, row op, mt, nt, K, tile id, two-pass form, ms of that configuration, ms
+    of the rule's own choice, whether the search's find was confirmed).  The island search proposes;
+    its winner replaces the rule's own choice only if a second, longer timing of the two -
+    alternating, three blocks each - confirms it at more than 4 %: launches of ten microseconds
+    time noisily, and the table should not record noise."""
+    rows = []
+    g = torch.Generator(device="cuda").manual_seed(0)
+
+    def tile_of(kernel: str) -> Optional[int]:
+        return next((tid for name, tid in TILES.items() if kernel.startswith(name + "_")), None)
+
+    for cls, dt in ((0, torch.bfloat16), (1, torch.float8_e4m3fn)):
+        for K in SWEEP_K:
+            for nt in SWEEP_NT[::2] if quick else SWEEP_NT:
+                W = (torch.randn(nt * 256, K, device="cuda", generator=g) * (1.0 if cls else K ** -0.5)).to(dt)
+                gamma = 1.0 + 0.1 * torch.randn(nt * 256, device="cuda", generator=g)
+                for mt in SWEEP_MT[::3] if quick else SWEEP_MT:
+                    X = torch.randn(mt * 256, K, device="cuda", generator=g).to(dt)
+                    out = torch.empty(mt * 256, nt * 256, dtype=torch.bfloat16, device="cuda")
+                    for has_norm, norm in ((0, I.NORM_NONE), (1, I.NORM_RMSNORM)):
+                        kw = dict(alpha=K ** -0.5 if cls else 1.0, eps=1e-6, gamma=gamma)
+                        prob = Problem(X, W, None, I.ACT_SILU, norm, out, **kw)
+                        own_flags = B.FLAG_NO_SPLIT_K | B.FLAG_NO_TABLE          # the rule's own choice, K left whole (the slices have a rule of their own)
+                        own = prob.describe(own_flags)
+                        best, _, seen = evolve_library(X, W, None, I.ACT_SILU, norm, out, steps=12, warmup=3, **kw)
+                        found = seen[best]
+                        fd = prob.describe(found["flags"])
+                        if " k/" in found["kernel"] or tile_of(found["kernel"]) is None:
+                            found, fd = None, own
+                        t_own = t_found = None
+                        confirmed = False
+                        if found is not None and (fd["kernel"], fd["finish"]) != (own["kernel"], own["finish"]):
+                            a, b_ = [], []
+                            for _ in range(3):
+                                a.append(prob.run(own_flags, 30, 3)[1])
+                                b_.append(prob.run(found["flags"] | B.FLAG_NO_SPLIT_K, 30, 3)[1])
+                            t_own, t_found = sorted(a)[1], sorted(b_)[1]
+                            confirmed = t_own > 1.04 * t_found
+                        if t_own is None:
+                            t_own = t_found = prob.run(own_flags, 30, 3)[1]
+                        pick = fd if confirmed else own
+                        tile = tile_of(pick["kernel"])
+                        if tile is None:
+                            continue
+                        rows.append((cls, has_norm, mt, nt, K, tile, int(pick["finish"]), t_found if confirmed else t_own, t_own, confirmed))
+                        log(f"  class {cls} rowop {has_norm} mt {mt:3d} nt {nt:3d} K {K:5d}: {pick['kernel']:20s}{'+second pass' if pick['finish'] else '':13s}"
+                            f"{rows[-1][7]:8.4f} ms (rule {own['kernel']:16s} {t_own:8.4f} ms{', %.2fx' % (t_own / t_found) if confirmed else ''})")
+    return rows
+
+
+def write_table(rows, path: str = TABLE_PATH) -> None:
+    names = {v: k for k, v in TILES.items()}
+    with open(path, "w") as f:
+        f.write("// Fastest verified tile configuration per sweep point, read by the tile choice (pick_tile).\n"
+                "// Written by `python -m paper_2512_23424_amd.tune --write-table` on an MI355X: the island search\n"
+                "// of tune.py over every configuration the library accepts, SiLU with and without a row op\n"
+                "// (RMSNorm), bf16 and E4M3 operands, bf16 results; a find replaces the rule's own choice only\n"
+                "// when a second timing confirms it at more than 4 %.  Columns: operand class (0: 16-bit,\n"
+                "// 1: 8-bit), row op follows (0 / 1), ceil(M / 256), ceil(N / 256), K, tile id, split rows finished\n"
+                "// by the second pass (0 / 1); the comment gives the time in ms and, for a confirmed find, the\n"
+                "// time of the rule's choice.\n"
+                "#pragma once\nnamespace fge {\n"
+                "struct TileTableEntry { unsigned char cls, rowop; unsigned short mt, nt; int K; unsigned char tile, two_pass; };\n"
+                "static const TileTableEntry TILE_TABLE[] = {\n")
+        for cls, has_norm, mt, nt, K, tile, two_pass, ms, t_own, confirmed in rows:
+            note = f"{names[tile]}: {ms:.4f}" + (f" (rule {t_own:.4f})" if confirmed else "")
+            f.write(f"    {{{cls}, {has_norm}, {mt}, {nt}, {K}, {tile}, {two_pass}}},   // {note}\n")
+        if not rows:
+            f.write("    {255, 0, 0, 0, 0, 0, 0},   // (no sweep yet: the rule decides everywhere)\n")
+        f.write("};\n}  // namespace fge\n")
 
 
 def _upload(a):
@@ -275,7 +466,16 @@ def main(argv: List[str]) -> int:
                                  description="Time every configuration the library accepts for a workload.")
     ap.add_argument("workload", nargs="?", default="cfg2", choices=known)
     ap.add_argument("--evolve", action="store_true", help="island search instead of the exhaustive visit")
+    ap.add_argument("--write-table", action="store_true", help="sweep shapes with the island search and write csrc/fge_tile_table.h")
+    ap.add_argument("--quick", action="store_true", help="with --write-table: a third of the sweep points")
+    ap.add_argument("--table-path", default=TABLE_PATH)
     args = ap.parse_args(argv[1:])
+    if args.write_table:
+        rows = sweep(args.quick)
+        write_table(rows, args.table_path)
+        better = sum(1 for r in rows if r[9])
+        print(f"{len(rows)} sweep points written to {args.table_path}; a find of the search replaced the rule's choice on {better}")
+        return 0
     name = args.workload
     w = I.WORKLOADS[name] if name in I.WORKLOADS else I.EXTRA_WORKLOADS[name]
     t = {k: _upload(v) for k, v in I.generate(w).items()}

@@ -91,7 +91,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert 4096 * 8 * 8 + 64 * 8 * 4 + 256 < need == 4096 * (8 * 2) * 8
     p.flags = B.FLAG_TWO_PASS
     assert B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p)) == 4096 * (8 * 2) * 8
-    p.flags = 8
+    p.flags = 0x10
     assert _call(p, act=2, norm=2) == 2        # unknown flag bit
     p.flags = 0
     assert _call(p, act=2, norm=2) == 6
@@ -224,3 +224,20 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit():
     # element-granular kernels: the fp32 intermediate of 3000 x 3001 rows does not fit either
     odd = _params(M=3000, N=3001, K=17, ldx=17, ldw=17, ldo=3001)
     assert fn(FAKE, FAKE, None, 1, 1, ctypes.byref(odd), FAKE, None) == 6
+
+
+def test_tile_choice_reads_the_search_table_and_respects_its_limits():
+    """16-bit operands: the choice takes the nearest entry of the table the configuration search
+    wrote - here the 128x256 tile, which just fills the chip at 2048 x 4096 - unless the caller asks
+    for the rule alone, the problem spills that tiling into another round of the chip (2304 rows), or
+    few tiles and a long K call for the K slices."""
+    def prm(M, N, K, **kw):
+        return _params(M=M, N=N, K=K, ldx=K, ldw=K, ldo=N, in_dtype=1, out_dtype=1, **kw)
+    assert B.fge_tile_name(True, 4, 3, prm(2048, 4096, 4096)) == "128x256_w2x4"
+    assert B.fge_tile_name(True, 4, 3, prm(2048, 4096, 4096, flags=B.FLAG_NO_TABLE)) == "128x128_w2x2"
+    assert B.fge_tile_name(True, 4, 3, prm(2304, 4096, 4096)) == "256x256_w2x4"
+    assert B.fge_tile_name(True, 4, 3, prm(2304, 4096, 4096, flags=B.FLAG_NO_TABLE)) == "256x256_w2x4"
+    assert B.fge_tile_name(True, 4, 3, prm(64, 4096, 4096)) == "64x64_w2x2" and B.fge_fused_k_slices(4, 3, prm(64, 4096, 4096)) == 8
+    # fp32 operands are not in the table
+    f32 = _params(M=2048, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096)
+    assert B.fge_tile_name(True, 4, 3, f32) == B.fge_tile_name(True, 4, 3, _params(M=2048, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, flags=B.FLAG_NO_TABLE))

@@ -97,7 +97,7 @@ def test_split_rows_one_kernel_and_two_pass(norm, case):
         H.check(w, got, gaux, ref, raux, f"f8 split flags={flags}")
 
 
-@pytest.mark.parametrize("tile", ["64x64", "64x512", "128x128", "256x256"])
+@pytest.mark.parametrize("tile", ["64x64", "64x512", "128x128", "256x256", "128x256", "256x128"])
 def test_every_tile_configuration(tile):
     from paper_2512_23424_amd import tune as T
     w = _wl(520, 400, 1040, I.ACT_GELU_ERF, I.NORM_SOFTMAX, I.F32)

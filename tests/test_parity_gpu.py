@@ -156,6 +156,30 @@ def test_split_rows_one_kernel_and_two_pass(norm, case):
     assert np.array_equal(H.to_host_f64(outs[0]), H.run_gpu(w, t, "fused", dev=d, flags=force)[0])
 
 
+@pytest.mark.parametrize("norm", NORMS)
+@pytest.mark.parametrize("case", [(I.BF16, I.BF16, 2050, 200, 2040), (I.F16, I.F32, 1100, 72, 1288), (I.F8E4M3, I.BF16, 2100, 272, 2064)])
+@pytest.mark.parametrize("tile", [(7, "128x256_w2x4"), (8, "256x128_w4x2")])
+def test_half_tile_configurations(tile, case, norm):
+    """The 128x256 and 256x128 tiles (asked for by flag; the tile choice takes them where its table
+    says so): ragged M / N / K, split rows in the one-kernel form (where the grid is large enough
+    for it) and in the two-pass form, every row op, against the oracle."""
+    tid, tname = tile
+    idt, odt, M, K, N = case
+    force = (tid + 1) << 8
+    w = I.Workload(name=f"half{norm}", M=M, K=K, N=N, in_dtype=idt, out_dtype=odt, act=I.ACT_SILU, norm=norm,
+                   alpha=1.0 / K ** 0.5 if idt == I.F8E4M3 else 0.5, post_scale=1.5, eps=1e-5,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 1.0 if idt == I.F8E4M3 else 0.1),
+                         "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1), "beta": ("normal", 0.0, 0.1)})
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(odt), device="cuda"), flags=force)
+    assert B.fge_tile_name(True, w.act, norm, p) == tname
+    ref, raux = H.oracle_chain(w, t)
+    for flags in (force, force | B.FLAG_TWO_PASS):
+        got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
+        H.check(w, got, gaux, ref, raux, f"{tname} flags={flags:#x}")
+
+
 @pytest.mark.parametrize("shape", [(300, 1024, 1024), (1030, 520, 2040), (77, 136, 328), (5000, 40, 328)])
 def test_fp32_matrix_instruction_on_request(shape):
     """FGE_FLAG_IEEE_FP32 multiplies fp32 operands with the fp32 matrix instruction (products exact
