@@ -59,16 +59,23 @@ def run_gpu(w: I.Workload, t: Dict[str, Optional[np.ndarray]], path: str = "fuse
     p = B.make_params(X, d["W"], out, alpha=w.alpha, post_scale=w.post_scale, clamp_lo=w.clamp_lo,
                       clamp_hi=w.clamp_hi, eps=w.eps, gamma=d["gamma"], beta=d["beta"], aux_out=aux, flags=flags)
     nbytes = B.fge_workspace_bytes(path == "fused", w.act, w.norm, p)
-    ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
-    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * 4
+    # the workspace is told to be exactly the size asked for, with a canary behind it: nothing may
+    # be written past the end of what the call was given
+    CANARY = 1024
+    ws_bytes = (max(nbytes, 16) + 255) // 256 * 256
+    raw = torch.full((ws_bytes + CANARY,), 0xA5, dtype=torch.uint8, device="cuda")
+    ws = raw[:ws_bytes].view(torch.float32)
+    ws.fill_(float("nan"))
+    p.workspace, p.workspace_bytes = ws.data_ptr(), nbytes
     fn = B.fused_gemm_epilogue if path == "fused" else B.unfused_gemm_epilogue
     # one-kernel form of split rows: clear the word that reports a wait that ran out, check it after
     off = B.fge_fault_word_offset(w.act, w.norm, p) if path == "fused" else None
-    fault = ws.view(torch.int32)[off // 4: off // 4 + 1] if off is not None and off + 4 <= ws.numel() * 4 else None
+    fault = ws.view(torch.int32)[off // 4: off // 4 + 1] if off is not None and off + 4 <= nbytes else None
     if fault is not None:
         fault.zero_()
     fn(X, d["W"], d["b"], w.act, w.norm, p, out)
     torch.cuda.synchronize()
+    assert bool((raw[ws_bytes:] == 0xA5).all()), "the call wrote past the end of its workspace"
     if fault is not None and not expect_fault:
         assert int(fault.item()) == 0, "a tile's wait for its row block ran out"
     if expect_fault:
