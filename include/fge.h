@@ -43,11 +43,16 @@
  * 16-byte aligned (else FGE_ERR_ALIGN).  The fast kernels move data in 16-byte units: they run
  * when K*sizeof(in), N*sizeof(out), ldx, ldw, ldo and the batch strides are multiples of 16 bytes
  * (the fused path splits rows of any width over column tiles; a row operation on its own -
- * unfused K3, fge_row_op - spans at most 8192 columns there).  Every other shape is computed by
- * element-granular kernels (plain fp32 FMA, not tuned; fge_tile_name reports
- * "generic32x32_scalar"), never refused and never computed wrongly - the paper's benchmark
- * section names silent divisibility assumptions as the typical failure of generated kernels
- * under dynamic shapes.  out must not alias X or W.
+ * unfused K3, fge_row_op - spans at most 8192 columns there).  Every other shape is computed too,
+ * never refused and never computed wrongly - the paper's benchmark section names silent
+ * divisibility assumptions as the typical failure of generated kernels under dynamic shapes:
+ * fused_gemm_epilogue copies the operands of a large enough problem (from about 3e7 floating
+ * point operations on) into dense buffers in the workspace with K padded by zeros to whole
+ * 16-byte units and runs the fast kernels on those (fge_tile_name reports "repacked_operands";
+ * when the result's own extents or strides are odd too, it passes through fp32 rows of padded
+ * width and an element-granular row kernel); small problems, the stage entry points, the unfused
+ * sequence and calls whose workspace only covers it run element-granular kernels (plain fp32 FMA,
+ * not tuned; "generic32x32_scalar").  out must not alias X or W.
  */
 #ifndef FGE_H
 #define FGE_H
@@ -157,15 +162,19 @@ typedef struct fge_params {
     size_t  workspace_bytes;       /* its size                                                 */
 } fge_params;
 
-/* The fused path: one tile kernel that keeps the accumulators in registers through scale,
- * bias, activation and the in-tile row reduction.  When a row spans several column tiles the
+/* The fused path (the paper's Section 4.3: a fused operator avoids the intermediate memory
+ * accesses and the launches of the composed small operators; chain and row operations as in its
+ * Section 3.6 categories and the RMSNorm sketch of Fig. 2): one tile kernel that keeps the
+ * accumulators in registers through scale, bias, activation and the in-tile row reduction.  When a row spans several column tiles the
  * tiles publish mergeable row statistics to the workspace; large problems then finish their
  * rows inside the same kernel (see FGE_FLAG_TWO_PASS), others with a light second kernel that
  * merges the statistics and normalises `out` in place.  b may be NULL (no bias). */
 int fused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
                         const fge_params *p, void *out, void *stream);
 
-/* The unfused reference sequence built from the same device pieces: K1 Y = post_scale*(alpha*
+/* The unfused reference sequence - what the paper's Section 4.3 describes eager execution as:
+ * one operator after the other, every intermediate through memory - built from the same device
+ * pieces: K1 Y = post_scale*(alpha*
  * X.W^T + b) -> workspace, K2 A = act(Y) -> workspace (-> out for NONE / LOGSUMEXP), K3
  * out = rowop(A).  Intermediates are stored in out_dtype, as an eager framework would. */
 int unfused_gemm_epilogue(const void *X, const void *W, const float *b, int act, int norm,
@@ -193,7 +202,8 @@ int fused_gemm_epilogue_static(const void *X, const void *W, const float *b, int
 int fge_static_scratch_init(void);
 size_t fge_static_scratch_bytes(void);
 
-/* Bytes of workspace the fused (fused != 0) or unfused (fused == 0) path needs for these
+/* Device scratch is the caller's (the paper's kernels come with a host wrapper that owns all
+ * buffers, Section 3.2, the Coder).  Bytes of workspace the fused (fused != 0) or unfused (fused == 0) path needs for these
  * arguments; 0 is a valid answer.  Returns (size_t)-1 when the arguments are invalid.  The fused
  * figure includes the room for the optional K slices (FGE_FLAG_NO_SPLIT_K); a smaller workspace
  * that still holds the row statistics of split rows is accepted and runs unsliced. */
@@ -259,7 +269,8 @@ int fge_activation(const void *Y, int act, const fge_params *p, void *A, void *s
 /* Unfused K3: out = rowop(A), both rows x N in out_dtype with row stride ldo; out may equal A. */
 int fge_row_op(const void *A, int norm, const fge_params *p, void *out, void *stream);
 
-/* Static description of a status code. */
+/* Static description of a status code (every refusal is explicit: the paper's Section 3.6 counts
+ * a silently wrong result as the failure, not an error return). */
 const char *fge_status_string(int status);
 /* hipError_t (as int) recorded by the calling thread's last FGE_ERR_HIP, else 0. */
 int fge_last_hip_error(void);

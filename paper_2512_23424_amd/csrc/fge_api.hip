@@ -443,6 +443,11 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
         a.gen = g_generation.fetch_add(1) + 1;
         a.arrive = reinterpret_cast<unsigned *>(base);
         a.fault = reinterpret_cast<int *>(base + pl.ws_marks - 256);
+        // staggered start of the row blocks (see the kernel): measured 1 to 7 % on problems whose
+        // tiles are short (K = 256 ... 2048; 7 % on the batched K = 512 workload), nothing either
+        // way on K = 4096, where a round's stores are a small part of its time
+        a.stagger = pl.pr.K <= 2048 ? 4 : 0;
+        a.stagger_mask = 7;
         const bool expire = (p->flags & FGE_FLAG_TEST_EXPIRE_WAIT) != 0;
         a.spin_limit = expire ? 1u : WAIT_POLLS;
         a.withhold = expire ? 1 : 0;

@@ -45,6 +45,7 @@ struct TileArgs {
     unsigned gen;               // value that marks "arrived" in this launch
     unsigned *arrive;           // [batch * tiles_m][tiles_n] arrival marks
     int *fault;                 // set to 1 if a wait ran out (the rows of that tile are then stored as NaN)
+    int stagger, stagger_mask;  // cooperative form: row block rb of the first round starts (rb & mask) * stagger * 1024 clocks late
     unsigned spin_limit;        // polls after which a wait gives up
     int withhold;               // tests only: column tile 0 never marks itself as arrived
 };

@@ -183,6 +183,13 @@ void tile_kernel(const TileArgs a) {
         rowblock = round * rpr + rb;
         z = rowblock / a.tiles_m;
         tm = rowblock - z * a.tiles_m;
+        // Staggered start: the row blocks of the first round begin a little apart (all column
+        // tiles of a row block together - they wait for each other).  Equal tiles keep the whole
+        // chip in lockstep otherwise, and every round would end in one burst of stores at the
+        // memory system's write ceiling, behind which the next round's first loads queue up.
+        if (round == 0 && a.stagger > 0) {
+            for (int i = (rb & a.stagger_mask) * a.stagger; i > 0; --i) __builtin_amdgcn_s_sleep(16);     // 1024 clocks each
+        }
     } else {
         if (round > 0) break;
         tile_coords(blockIdx.x, a.tiles_m, a.tiles_n, a.group_m, tm, tn);
