@@ -45,6 +45,7 @@ struct TileArgs {
     unsigned gen;               // value that marks "arrived" in this launch
     unsigned *arrive;           // [batch * tiles_m][tiles_n] arrival marks
     int *fault;                 // set to 1 if a wait ran out (the rows of that tile are then stored as NaN)
+    int stream_out;             // store `out` with the streaming hint
     int stagger, stagger_mask;  // cooperative form: row block rb of the first round starts (rb & mask) * stagger * 1024 clocks late
     unsigned spin_limit;        // polls after which a wait gives up
     int withhold;               // tests only: column tile 0 never marks itself as arrived
@@ -425,9 +426,10 @@ struct TileEpilogue {
         transpose_block<B>(blk, v);
     }
 
-    // 16-byte store of output; STREAM_OUT stores carry the streaming (non-temporal) hint.
-    static __device__ __forceinline__ void put16(OutT *o, const uint4 &u) {
-        if constexpr (STREAM_OUT) {
+    // 16-byte store of output; with STREAM_OUT, or when the launch asks for it (a.stream_out: an
+    // output of half the last-level cache or more), stores carry the streaming (non-temporal) hint.
+    __device__ __forceinline__ void put16(OutT *o, const uint4 &u) const {
+        if (STREAM_OUT || a.stream_out) {
             const u32x4 w = {u.x, u.y, u.z, u.w};
             __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(o));
         } else {
