@@ -6,6 +6,7 @@
 #include <chrono>
 
 #include <cmath>
+#include <vector>
 
 #include "fge_launch.h"
 #include "fge_rowops.h"
@@ -163,19 +164,36 @@ int64_t tile_rounds(int t, int64_t rows, int64_t cols, int batch) {
 const TileTableEntry *table_entry(const Problem &pr, int in_dtype, int norm) {
     if (in_dtype == FGE_F32) return nullptr;
     const int cls = in_dtype == FGE_F8E4M3 ? 1 : 0, rowop = norm != FGE_NORM_NONE;
-    const double mt = std::log2((double)((pr.M + 255) / 256) * pr.batch), nt = std::log2((double)((pr.N + 255) / 256)),
-                 k = std::log2((double)pr.K);
-    double best = 0.6;
+    // the answer for the shapes a caller keeps coming back with is remembered (per thread)
+    struct Memo { int cls, rowop, M, N, K, batch; const TileTableEntry *hit; bool valid; };
+    thread_local Memo memo[16] = {};
+    Memo &slot = memo[((unsigned)pr.M * 2654435761u ^ (unsigned)pr.N * 40503u ^ (unsigned)pr.K * 9176u ^ (unsigned)(cls * 2 + rowop)) >> 28];
+    if (slot.valid && slot.cls == cls && slot.rowop == rowop && slot.M == pr.M && slot.N == pr.N && slot.K == pr.K &&
+        slot.batch == pr.batch)
+        return slot.hit;
+    // log2 of every entry's coordinates, once
+    struct Lg { float mt, nt, k; };
+    static const std::vector<Lg> lg = [] {
+        std::vector<Lg> v;
+        for (const TileTableEntry &e : TILE_TABLE)
+            v.push_back(Lg{std::log2((float)(e.mt ? e.mt : 1)), std::log2((float)(e.nt ? e.nt : 1)), std::log2((float)(e.K ? e.K : 1))});
+        return v;
+    }();
+    const float mt = std::log2((float)((pr.M + 255) / 256) * pr.batch), nt = std::log2((float)((pr.N + 255) / 256)),
+                k = std::log2((float)pr.K);
+    float best = 0.6f;
     const TileTableEntry *hit = nullptr;
+    size_t i = 0;
     for (const TileTableEntry &e : TILE_TABLE) {
+        const Lg &l = lg[i++];
         if (e.cls != cls || e.rowop != rowop || e.tile >= TILE_COUNT) continue;
-        const double d = std::fabs(mt - std::log2((double)e.mt)) + std::fabs(nt - std::log2((double)e.nt)) +
-                         std::fabs(k - std::log2((double)e.K));
+        const float d = std::fabs(mt - l.mt) + std::fabs(nt - l.nt) + std::fabs(k - l.k);
         if (d >= best) continue;
         if (tile_rounds(e.tile, pr.M, pr.N, pr.batch) != tile_rounds(e.tile, (int64_t)e.mt * 256, (int64_t)e.nt * 256, 1)) continue;
         best = d;
         hit = &e;
     }
+    slot = Memo{cls, rowop, pr.M, pr.N, pr.K, pr.batch, hit, true};
     return hit;
 }
 
