@@ -467,9 +467,12 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
         a.arrive = reinterpret_cast<unsigned *>(base);
         a.fault = reinterpret_cast<int *>(base + pl.ws_marks - 256);
         // staggered start of the row blocks (see the kernel): measured 1 to 7 % on problems whose
-        // tiles are short (K = 256 ... 2048; 7 % on the batched K = 512 workload), nothing either
-        // way on K = 4096, where a round's stores are a small part of its time
-        a.stagger = pl.pr.K <= 2048 ? 4 : 0;
+        // tiles are short (K = 256 ... 2048; 7 % on the batched K = 512 workload) and that take at
+        // least three rounds of the grid; nothing either way at K = 4096, where a round's stores are a
+        // small part of its time - and a plain loss on a single round, which the stagger only
+        // lengthens (the 4096 x 1024 x 1024 fp32 workload: 42 -> 51 us)
+        const int64_t row_blocks = (int64_t)pl.tiles_m * pl.pr.batch, per_round = pl.coop_grid / pl.tiles_n;
+        a.stagger = pl.pr.K <= 2048 && row_blocks >= 3 * per_round ? 4 : 0;
         a.stagger_mask = 7;
         const bool expire = (p->flags & FGE_FLAG_TEST_EXPIRE_WAIT) != 0;
         a.spin_limit = expire ? 1u : WAIT_POLLS;
