@@ -42,6 +42,7 @@
  * strides >= the extents.  Base pointers (X, W, b, out, gamma, beta, aux_out, workspace) must be
  * 16-byte aligned (else FGE_ERR_ALIGN).  The fast kernels move data in 16-byte units: they run
  * when K*sizeof(in), N*sizeof(out), ldx, ldw, ldo and the batch strides are multiples of 16 bytes
+ * and a row of X or W is less than 8 MiB from the next
  * (the fused path splits rows of any width over column tiles; a row operation on its own -
  * unfused K3, fge_row_op - spans at most 8192 columns there).  Every other shape is computed too,
  * never refused and never computed wrongly - the paper's benchmark section names silent

@@ -131,6 +131,10 @@ bool vectorisable(const fge_params *p, int norm, bool need_in) {
     if (need_in) {
         if ((p->K * is) % 16 || (p->ldx * is) % 16 || (p->ldw * is) % 16) return false;
         if (p->batch > 1 && (p->batch_stride_x * is) % 16) return false;
+        // the tile kernels address an operand row by a 32-bit byte offset from the first row of
+        // the tile (at most 256 rows)
+        constexpr int64_t SPAN = ((int64_t)1 << 31) / 256;
+        if (p->ldx * (int64_t)is >= SPAN || p->ldw * (int64_t)is >= SPAN) return false;
     }
     if (norm != FGE_NORM_NONE && !need_in && p->N > MAX_ROWOP_N) return false;
     return true;

@@ -32,10 +32,17 @@ __device__ __forceinline__ uint32_t as_u32(float v) { return __builtin_bit_cast(
 // kernels (no other LDS-direct, GWS or indexed-register instruction is emitted).  It cannot be
 // declared as clobbered: the compiler treats m0 as a reserved register and rejects it on the
 // clobber list with a warning that the entry has no effect.
-__device__ __forceinline__ void lds_dma16(const void *g, void *lds_base) {
-    typedef __attribute__((address_space(3))) void *lptr_t;
-    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)lds_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds), "v"(g) : "memory");
+// The global address is a wave-uniform 64-bit base (scalar registers) plus a 32-bit byte offset
+// per lane, the LDS address a wave-uniform byte address: stepping along K and switching stage
+// buffers is then scalar arithmetic only, and a lane keeps one register per copy instead of a
+// 64-bit pointer.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    typedef __attribute__((address_space(3))) const void *lptr_t;
+    return (uint32_t)(uintptr_t)(lptr_t)p;
+}
+__device__ __forceinline__ void lds_dma16(const void *base, uint32_t lane_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
 __device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

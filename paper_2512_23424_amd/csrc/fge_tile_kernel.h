@@ -212,28 +212,34 @@ void tile_kernel(const TileArgs a) {
     // which is what a direct global->LDS load writes (lane l lands at base + 16*l).
     const int ld_gc = ld_c ^ swz(ld_row);          // global chunk of this thread
     const int ld_soff = ld_row * ROWB + (ld_c << 4);
-    const InT *gA[A_LD];
-    const InT *gB[B_LD];
+    // A copy's global address is a scalar base (first row of the tile, current k) plus the lane's
+    // byte offset from it, which does not change along K: 32 bits (the host keeps tiles whose
+    // rows span 2 GB or more off this kernel).
+    const InT *Xt = X + (int64_t)m0 * a.ldx;
+    const InT *Wt = W + (int64_t)n0 * a.ldw;
+    const InT *W2t = GATED ? reinterpret_cast<const InT *>(a.W2) + (int64_t)z * a.bsw + (int64_t)n0 * a.ldw : nullptr;
+    constexpr int B_FIRST2 = GATED ? BNO / RSTEP : B_LD;   // gated: copies from here on fetch rows of W2
+    static_assert(!GATED || BNO % RSTEP == 0, "a copy instruction fetches from one matrix");
+    uint32_t oA[A_LD], oB[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-        gA[i] = X + (int64_t)min(m0 + ld_row + i * RSTEP, a.M - 1) * a.ldx + ld_gc * CW;
+        oA[i] = (uint32_t)((int64_t)(min(m0 + ld_row + i * RSTEP, a.M - 1) - m0) * a.ldx + ld_gc * CW) * (uint32_t)sizeof(InT);
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
-        const int prow = ld_row + i * RSTEP;         // panel row; gated: rows >= BNO come from W2
-        const bool second = GATED && prow >= BNO;
-        const InT *Wm = second ? reinterpret_cast<const InT *>(a.W2) : W;
-        gB[i] = Wm + (int64_t)min(n0 + prow - (second ? BNO : 0), a.N - 1) * a.ldw + ld_gc * CW;
+        const int prow = ld_row + i * RSTEP - (i >= B_FIRST2 ? BNO : 0);   // row of W (gated: or of W2) in the tile
+        oB[i] = (uint32_t)((int64_t)(min(n0 + prow, a.N - 1) - n0) * a.ldw + ld_gc * CW) * (uint32_t)sizeof(InT);
     }
 
     // full tile: asynchronous global -> LDS, no registers involved; completion is tracked by
     // the vector-memory counter (wait for it, then barrier, before anyone reads the tile)
-    const int wave_soff = (tid >> 6) * 8 * ROWB;      // first byte of this wave's 8 rows
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)((tid >> 6) * 8 * ROWB));   // this wave's 8 rows
     constexpr int NS = A_LD + B_LD;                  // copy instructions per thread per tile
     static_assert(NS % 2 == 0, "copies are issued in two halves");
     auto dma_chunk = [&](int buf, int k0, int w) __attribute__((always_inline)) {
-        unsigned char *sA = smem + buf * STAGE + wave_soff, *sB = sA + BM * ROWB;
-        if (w < A_LD) lds_dma16(gA[w] + k0, sA + w * RSTEP * ROWB);
-        else          lds_dma16(gB[w - A_LD] + k0, sB + (w - A_LD) * RSTEP * ROWB);
+        const uint32_t sA = lds_wave + buf * STAGE, sB = sA + BM * ROWB;
+        if (w < A_LD)                 lds_dma16(Xt + k0, oA[w], sA + w * RSTEP * ROWB);
+        else if (w - A_LD < B_FIRST2) lds_dma16(Wt + k0, oB[w - A_LD], sB + (w - A_LD) * RSTEP * ROWB);
+        else                          lds_dma16(W2t + k0, oB[w - A_LD], sB + (w - A_LD) * RSTEP * ROWB);
     };
     auto dma_tile = [&](int buf, int k0) __attribute__((always_inline)) {
 #pragma unroll
@@ -246,13 +252,13 @@ void tile_kernel(const TileArgs a) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (kok) v = *reinterpret_cast<const u32x4 *>(gA[i] + k0);
+            if (kok) v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const unsigned char *>(Xt + k0) + oA[i]);
             *reinterpret_cast<u32x4 *>(sA + i * RSTEP * ROWB) = v;
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (kok) v = *reinterpret_cast<const u32x4 *>(gB[i] + k0);
+            if (kok) v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const unsigned char *>((i < B_FIRST2 ? Wt : W2t) + k0) + oB[i]);
             *reinterpret_cast<u32x4 *>(sB + i * RSTEP * ROWB) = v;
         }
     };
