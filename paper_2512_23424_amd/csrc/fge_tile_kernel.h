@@ -434,7 +434,8 @@ void tile_kernel(const TileArgs a) {
     // one k-step: MFMAs of step t on fragment set t&1; behind MFMA m: reads of (rbuf, t+1)
     // dma_part: 0 none, 1 / 2: first / second half of the copy instructions of the tile at
     // (dbuf, dk0), one behind each of the first MFMAs - a burst of copies would stall the
-    // wave's in-order issue, and with it its MFMAs, on the address unit
+    // wave's in-order issue, and with it its MFMAs, on the address unit; 3: all of them, spread
+    // evenly over the MFMAs of the k-step
     auto kstep = [&]<int DMA_PART>(int t, bool do_read, int rbuf, bool do_dma, int dbuf, int dk0) __attribute__((always_inline)) {
         constexpr int HALF = NS / 2;
 #pragma unroll
@@ -453,7 +454,11 @@ void tile_kernel(const TileArgs a) {
 #pragma unroll
                 for (int s = (m * NR) / RSPAN; s < ((m + 1) * NR) / RSPAN && s < NR; ++s) read_frag(rbuf, t + 1, slot(s));
             }
-            if constexpr (DMA_PART != 0) {
+            if constexpr (DMA_PART == 3) {
+#pragma unroll
+                for (int w = (m * NS) / NM; w < ((m + 1) * NS) / NM; ++w)
+                    if (do_dma) dma_chunk(dbuf, dk0, w);
+            } else if constexpr (DMA_PART != 0) {
 #pragma unroll
                 for (int w = (m * HALF) / NM; w < ((m + 1) * HALF) / NM; ++w)
                     if (do_dma) dma_chunk(dbuf, dk0, (DMA_PART - 1) * HALF + w);
@@ -508,23 +513,29 @@ void tile_kernel(const TileArgs a) {
     if (KF > 0) { dma_tile(0, 0); lds_dma_wait(); }
     else        stage_tail(0, 0);
     __syncthreads();
+    // 8-bit operands have two k-steps per tile only: the whole copy of tile kt+1 is issued behind
+    // the last k-step of tile kt-1 (measured 4 % faster).  With the four k-steps of 16-bit operands
+    // the copy stays in two halves: all at once measured 3 % slower there.
+    constexpr bool EARLY = F8;
     if (KF > 1) {
 #pragma unroll
-        for (int w = 0; w < NS / 2; ++w) dma_chunk(1, BK, w);
+        for (int w = 0; w < (EARLY ? NS : NS / 2); ++w) dma_chunk(1, BK, w);
     }
     __builtin_amdgcn_sched_barrier(0);
     read_t0(0);
     int kt = 0;
     for (; kt + 1 < KF; ++kt) {                       // tile kt+1 is a full one
         const int buf = kt & 1;
-        kstep.template operator()<2>(0, true, buf, true, buf ^ 1, (kt + 1) * BK);
+        if constexpr (EARLY) kstep.template operator()<0>(0, true, buf, false, 0, 0);
+        else                 kstep.template operator()<2>(0, true, buf, true, buf ^ 1, (kt + 1) * BK);
         static_for<1, KS - 1>([&]<int t>() __attribute__((always_inline)) {
             kstep.template operator()<0>(t, true, buf, false, 0, 0);
         });
         lds_dma_wait();                                   // tile kt+1 has landed in buf^1
         __syncthreads();                              // ... for every wave; reads of buf are over
         __builtin_amdgcn_sched_barrier(0);
-        kstep.template operator()<1>(KS - 1, true, buf ^ 1, kt + 2 < KF, buf, (kt + 2) * BK);   // then k-step 0
+        if constexpr (EARLY) kstep.template operator()<3>(KS - 1, true, buf ^ 1, kt + 2 < KF, buf, (kt + 2) * BK);
+        else                 kstep.template operator()<1>(KS - 1, true, buf ^ 1, kt + 2 < KF, buf, (kt + 2) * BK);   // then k-step 0
     }
     if (KF > 0 && ragged_k) {                         // last full tile, then the partial tile
         compute_last(kt & 1);
