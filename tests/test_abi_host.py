@@ -227,16 +227,31 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit():
 
 
 def test_tile_choice_reads_the_search_table_and_respects_its_limits():
-    """16-bit operands: the choice takes the nearest entry of the table the configuration search
-    wrote - here the 128x256 tile, which just fills the chip at 2048 x 4096 - unless the caller asks
-    for the rule alone, the problem spills that tiling into another round of the chip (2304 rows), or
+    """16-bit operands: at a sweep point where the configuration search's find beat the rule, the
+    choice is the table's entry - unless the caller asks for the rule alone, the problem needs
+    another number of rounds of the chip than the entry's shape did (same tile, a few more rows), or
     few tiles and a long K call for the K slices."""
+    import re
     def prm(M, N, K, **kw):
         return _params(M=M, N=N, K=K, ldx=K, ldw=K, ldo=N, in_dtype=1, out_dtype=1, **kw)
-    assert B.fge_tile_name(True, 4, 3, prm(2048, 4096, 4096)) == "128x256_w2x4"
-    assert B.fge_tile_name(True, 4, 3, prm(2048, 4096, 4096, flags=B.FLAG_NO_TABLE)) == "128x128_w2x2"
-    assert B.fge_tile_name(True, 4, 3, prm(2304, 4096, 4096)) == "256x256_w2x4"
-    assert B.fge_tile_name(True, 4, 3, prm(2304, 4096, 4096, flags=B.FLAG_NO_TABLE)) == "256x256_w2x4"
+    names = {0: "64x64_w2x2", 1: "64x512_w1x4", 2: "128x128_w2x2", 3: "256x256_w2x4", 7: "128x256_w2x4", 8: "256x128_w4x2"}
+    table = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2512_23424_amd", "csrc", "fge_tile_table.h")
+    finds = 0
+    for line in open(table):
+        m = re.match(r"\s*\{0, 1, (\d+), (\d+), (\d+), (\d+), 0\},.*\(rule", line)      # 16-bit, row op, one-kernel form, a confirmed find
+        if not m:
+            continue
+        mt, nt, K, tile = (int(v) for v in m.groups())
+        if mt * nt < 64:             # (small problems: the K slices have a rule of their own)
+            continue
+        p = prm(mt * 256, nt * 256, K)
+        assert B.fge_tile_name(True, 4, 3, p) == names[tile], line
+        assert B.fge_tile_name(True, 4, 3, prm(mt * 256, nt * 256, K, flags=B.FLAG_NO_TABLE)) != names[tile], line
+        finds += 1
+    assert finds >= 5
+    # same neighbourhood of the table, another number of rounds: the rule decides
+    assert B.fge_tile_name(True, 4, 3, prm(6144, 4096, 4096)) == "128x256_w2x4"
+    assert B.fge_tile_name(True, 4, 3, prm(6400, 4096, 4096)) == B.fge_tile_name(True, 4, 3, prm(6400, 4096, 4096, flags=B.FLAG_NO_TABLE)) == "256x256_w2x4"
     assert B.fge_tile_name(True, 4, 3, prm(64, 4096, 4096)) == "64x64_w2x2" and B.fge_fused_k_slices(4, 3, prm(64, 4096, 4096)) == 8
     # fp32 operands are not in the table
     f32 = _params(M=2048, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096)
