@@ -40,9 +40,19 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
     typedef __attribute__((address_space(3))) const void *lptr_t;
     return (uint32_t)(uintptr_t)(lptr_t)p;
 }
-__device__ __forceinline__ void lds_dma16(const void *base, uint32_t lane_off, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+// The instruction's immediate offset (here step * 1024, step = 0 .. 3) is added to the LDS address
+// and to the global address alike (checked on the hardware), so up to four copies whose LDS
+// destinations lie 1024 bytes apart share one value of the LDS base register: set_base says
+// whether this copy writes it (the first copy of a run and of every group of four) or relies on
+// the value the previous copy of its group left there.  Callers lower lane_off by step * 1024.
+__device__ __forceinline__ void lds_dma16(const void *base, uint32_t lane_off, uint32_t lds_addr, int step, bool set_base) {
+    if (set_base) asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" :: "s"(lds_addr) : "memory");
+    switch (step) {
+    case 0:  asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(lane_off), "s"(base) : "memory"); break;
+    case 1:  asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" :: "v"(lane_off), "s"(base) : "memory"); break;
+    case 2:  asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" :: "v"(lane_off), "s"(base) : "memory"); break;
+    default: asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" :: "v"(lane_off), "s"(base) : "memory"); break;
+    }
 }
 __device__ __forceinline__ void lds_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

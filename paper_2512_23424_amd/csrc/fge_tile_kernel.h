@@ -131,7 +131,7 @@ void tile_kernel(const TileArgs a) {
     constexpr int FR = F8 ? 2 : 1;                   // 16-byte chunks per fragment per k-step
     constexpr int KS = 4 / FR;                       // k-steps per staged tile (the split product has its own loop)
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile");
-    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && RSTEP % 16 == 0, "load plan");
+    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "load plan");
     constexpr int STAGE = (BM + BN) * ROWB;
     // DEEP: a K tile of a small tile is multiplied in a fraction of the time its copy takes to
     // arrive, so one tile of lookahead leaves the loop waiting on memory latency.  The 64x64 tile
@@ -203,63 +203,77 @@ void tile_kernel(const TileArgs a) {
     OutT *out = reinterpret_cast<OutT *>(a.out) + (int64_t)z * a.bso;
 
     // ---------------- global -> LDS staging plan
-    // Thread t stages rows (t >> 3) + i*RSTEP.  Rows past the end of X / W are clamped to the
-    // last valid row: they only feed outputs that are never stored or counted.  Only a partial
-    // last K tile needs zero fill; it goes through registers.
-    const int ld_row = tid >> 3, ld_c = tid & 7;
-    // The thread at (row ld_row, physical chunk ld_c) of the panel fetches global chunk
-    // ld_c ^ swizzle(row): the LDS image of a wave's 64 chunks is then 1024 contiguous bytes,
-    // which is what a direct global->LDS load writes (lane l lands at base + 16*l).
-    const int ld_gc = ld_c ^ swz(ld_row);          // global chunk of this thread
-    const int ld_soff = ld_row * ROWB + (ld_c << 4);
+    // A copy instruction of a wave fills 1024 contiguous LDS bytes = 8 panel rows (lane l lands at
+    // base + 16*l).  Wave w stages the 8*A_LD rows of the A panel from row w*8*A_LD on and the
+    // 8*B_LD rows of the B panel from row w*8*B_LD on, copy i the rows 8i .. 8i+7 of those: the
+    // copies of an operand land 1024 bytes apart, which the instruction's own 12-bit offset
+    // reaches - it moves the LDS address and the global address alike, so the lane offset of copy
+    // i is lowered by the same amount -, and one write of the LDS base register serves four
+    // copies.  Rows past the end of X / W are clamped to the last valid row: they only feed
+    // outputs that are never stored or counted.  Only a partial last K tile needs zero fill; it
+    // goes through registers.
+    // The lane at (row, physical chunk c) of the panel fetches global chunk c ^ swizzle(row): the
+    // LDS image of a wave's 64 chunks is then the 1024 contiguous bytes a copy writes.
+    const int ld_r = (tid & 63) >> 3, ld_c = tid & 7;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+    constexpr int PRE = 3072;                         // bytes the scalar bases start early (keeps lane offsets >= 0)
+    static_assert(!GATED || BNO % (8 * B_LD) == 0, "a wave's B rows come from one matrix");
+    // gated: the waves whose B rows lie at or beyond BNO stage the same rows of W2
+    const bool second = GATED && wave_id * 8 * B_LD >= BNO;
+    const unsigned char *Xt = reinterpret_cast<const unsigned char *>(X + (int64_t)m0 * a.ldx) - PRE;
+    const unsigned char *Wt = reinterpret_cast<const unsigned char *>(
+                                  (second ? reinterpret_cast<const InT *>(a.W2) + (int64_t)z * a.bsw : W) + (int64_t)n0 * a.ldw) - PRE;
     // A copy's global address is a scalar base (first row of the tile, current k) plus the lane's
     // byte offset from it, which does not change along K: 32 bits (the host keeps tiles whose
     // rows span 2 GB or more off this kernel).
-    const InT *Xt = X + (int64_t)m0 * a.ldx;
-    const InT *Wt = W + (int64_t)n0 * a.ldw;
-    const InT *W2t = GATED ? reinterpret_cast<const InT *>(a.W2) + (int64_t)z * a.bsw + (int64_t)n0 * a.ldw : nullptr;
-    constexpr int B_FIRST2 = GATED ? BNO / RSTEP : B_LD;   // gated: copies from here on fetch rows of W2
-    static_assert(!GATED || BNO % RSTEP == 0, "a copy instruction fetches from one matrix");
     uint32_t oA[A_LD], oB[B_LD];
+    int rowA[A_LD], rowB[B_LD], gcA[A_LD], gcB[B_LD];  // panel row and global chunk of this lane per copy
 #pragma unroll
-    for (int i = 0; i < A_LD; ++i)
-        oA[i] = (uint32_t)((int64_t)(min(m0 + ld_row + i * RSTEP, a.M - 1) - m0) * a.ldx + ld_gc * CW) * (uint32_t)sizeof(InT);
+    for (int i = 0; i < A_LD; ++i) {
+        rowA[i] = wave_id * 8 * A_LD + i * 8 + ld_r;
+        gcA[i] = ld_c ^ swz(rowA[i]);
+        oA[i] = (uint32_t)((int64_t)(min(m0 + rowA[i], a.M - 1) - m0) * a.ldx + gcA[i] * CW) * (uint32_t)sizeof(InT) + PRE - (i & 3) * 1024;
+    }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
-        const int prow = ld_row + i * RSTEP - (i >= B_FIRST2 ? BNO : 0);   // row of W (gated: or of W2) in the tile
-        oB[i] = (uint32_t)((int64_t)(min(n0 + prow, a.N - 1) - n0) * a.ldw + ld_gc * CW) * (uint32_t)sizeof(InT);
+        rowB[i] = wave_id * 8 * B_LD + i * 8 + ld_r;
+        gcB[i] = ld_c ^ swz(rowB[i]);
+        const int prow = rowB[i] - (second ? BNO : 0);   // row of W (gated: or of W2) in the tile
+        oB[i] = (uint32_t)((int64_t)(min(n0 + prow, a.N - 1) - n0) * a.ldw + gcB[i] * CW) * (uint32_t)sizeof(InT) + PRE - (i & 3) * 1024;
     }
 
     // full tile: asynchronous global -> LDS, no registers involved; completion is tracked by
     // the vector-memory counter (wait for it, then barrier, before anyone reads the tile)
-    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)((tid >> 6) * 8 * ROWB));   // this wave's 8 rows
+    const uint32_t lds_waveA = lds_address(smem) + (uint32_t)(wave_id * A_LD * 1024);
+    const uint32_t lds_waveB = lds_address(smem) + (uint32_t)(BM * ROWB + wave_id * B_LD * 1024);
     constexpr int NS = A_LD + B_LD;                  // copy instructions per thread per tile
     static_assert(NS % 2 == 0, "copies are issued in two halves");
-    auto dma_chunk = [&](int buf, int k0, int w) __attribute__((always_inline)) {
-        const uint32_t sA = lds_wave + buf * STAGE, sB = sA + BM * ROWB;
-        if (w < A_LD)                 lds_dma16(Xt + k0, oA[w], sA + w * RSTEP * ROWB);
-        else if (w - A_LD < B_FIRST2) lds_dma16(Wt + k0, oB[w - A_LD], sB + (w - A_LD) * RSTEP * ROWB);
-        else                          lds_dma16(W2t + k0, oB[w - A_LD], sB + (w - A_LD) * RSTEP * ROWB);
+    // copy w of the tile at k0 into stage `buf`; `first`: the first copy of a run of copies (the
+    // LDS base register is written then and whenever a copy starts another group of four)
+    auto dma_chunk = [&](int buf, int k0, int w, bool first) __attribute__((always_inline)) {
+        const int i = w < A_LD ? w : w - A_LD;
+        const bool set_base = first || (i & 3) == 0 || w == A_LD;
+        if (w < A_LD) lds_dma16(Xt + (int64_t)k0 * sizeof(InT), oA[i], lds_waveA + buf * STAGE + (i >> 2) * 4096, i & 3, set_base);
+        else          lds_dma16(Wt + (int64_t)k0 * sizeof(InT), oB[i], lds_waveB + buf * STAGE + (i >> 2) * 4096, i & 3, set_base);
     };
     auto dma_tile = [&](int buf, int k0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int w = 0; w < NS; ++w) dma_chunk(buf, k0, w);
+        for (int w = 0; w < NS; ++w) dma_chunk(buf, k0, w, w == 0);
     };
     // partial last tile: through registers, zero filled past K
     auto stage_tail = [&](int buf, int k0) __attribute__((always_inline)) {
-        const bool kok = k0 + ld_gc * CW < a.K;       // K is a multiple of CW: chunks are whole
-        unsigned char *sA = smem + buf * STAGE + ld_soff, *sB = sA + BM * ROWB;
+        unsigned char *sA = smem + buf * STAGE + (ld_c << 4), *sB = sA + BM * ROWB;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (kok) v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const unsigned char *>(Xt + k0) + oA[i]);
-            *reinterpret_cast<u32x4 *>(sA + i * RSTEP * ROWB) = v;
+            u32x4 v = {0u, 0u, 0u, 0u};             // (K is a multiple of CW: chunks are whole)
+            if (k0 + gcA[i] * CW < a.K) v = *reinterpret_cast<const u32x4 *>(Xt + (int64_t)k0 * sizeof(InT) + oA[i] + (i & 3) * 1024);
+            *reinterpret_cast<u32x4 *>(sA + rowA[i] * ROWB) = v;
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (kok) v = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const unsigned char *>((i < B_FIRST2 ? Wt : W2t) + k0) + oB[i]);
-            *reinterpret_cast<u32x4 *>(sB + i * RSTEP * ROWB) = v;
+            if (k0 + gcB[i] * CW < a.K) v = *reinterpret_cast<const u32x4 *>(Wt + (int64_t)k0 * sizeof(InT) + oB[i] + (i & 3) * 1024);
+            *reinterpret_cast<u32x4 *>(sB + rowB[i] * ROWB) = v;
         }
     };
 
@@ -457,11 +471,11 @@ void tile_kernel(const TileArgs a) {
             if constexpr (DMA_PART == 3) {
 #pragma unroll
                 for (int w = (m * NS) / NM; w < ((m + 1) * NS) / NM; ++w)
-                    if (do_dma) dma_chunk(dbuf, dk0, w);
+                    if (do_dma) dma_chunk(dbuf, dk0, w, w == 0);
             } else if constexpr (DMA_PART != 0) {
 #pragma unroll
                 for (int w = (m * HALF) / NM; w < ((m + 1) * HALF) / NM; ++w)
-                    if (do_dma) dma_chunk(dbuf, dk0, (DMA_PART - 1) * HALF + w);
+                    if (do_dma) dma_chunk(dbuf, dk0, (DMA_PART - 1) * HALF + w, w == 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -519,7 +533,7 @@ void tile_kernel(const TileArgs a) {
     constexpr bool EARLY = F8;
     if (KF > 1) {
 #pragma unroll
-        for (int w = 0; w < (EARLY ? NS : NS / 2); ++w) dma_chunk(1, BK, w);
+        for (int w = 0; w < (EARLY ? NS : NS / 2); ++w) dma_chunk(1, BK, w, w == 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     read_t0(0);
