@@ -256,3 +256,16 @@ def test_tile_choice_reads_the_search_table_and_respects_its_limits():
     # fp32 operands are not in the table
     f32 = _params(M=2048, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096)
     assert B.fge_tile_name(True, 4, 3, f32) == B.fge_tile_name(True, 4, 3, _params(M=2048, N=4096, K=4096, ldx=4096, ldw=4096, ldo=4096, flags=B.FLAG_NO_TABLE))
+
+
+def test_rows_far_apart_leave_the_tile_kernels():
+    """The tile kernels address an operand row by a 32-bit byte offset from its tile's first row:
+    rows of X or W 8 MiB apart or more are repacked (large problems) or go to the element-granular
+    kernels (small ones); just below the limit the tile kernels still take them."""
+    def name(M, ld):
+        return B.fge_tile_name(True, 4, 3, _params(M=M, N=1024 if M > 64 else 64, K=1024 if M > 64 else 64, ldx=ld,
+                                                   ldw=1024 if M > 64 else 64, ldo=1024 if M > 64 else 64, in_dtype=1, out_dtype=1))
+    assert name(512, (8 << 20) // 2 - 8) == "64x64_w2x2"
+    assert name(512, (8 << 20) // 2) == "repacked_operands"
+    assert name(64, (8 << 20) // 2) == "generic32x32_scalar"
+

@@ -585,6 +585,31 @@ def test_k_split_with_row_strides():
     assert bool(torch.isnan(ob[:, w.N:]).all())          # the padding columns are never written
 
 
+@pytest.mark.parametrize("ld", [(8 << 20) // 2 - 8, (8 << 20) // 2])
+def test_rows_of_x_almost_8_mib_apart(ld):
+    """X as a view whose rows are just under / exactly 8 MiB apart (a 2.1 GB buffer for 300 rows):
+    below the limit the tile kernels address the rows by 32-bit offsets close to 2^31 from the
+    tile's first row; at the limit the operands are repacked.  Same values, same result."""
+    w = I.scaled(WL["cfg3"], M=300, K=1024, N=520, act=I.ACT_SILU, norm=I.NORM_RMSNORM)
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    ref, _ = H.oracle_chain(w, t)
+    Xb = torch.empty(w.M * ld, dtype=torch.bfloat16, device="cuda")
+    X = Xb.as_strided((w.M, w.K), (ld, 1))
+    X.copy_(d["X"])
+    out = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    below = ld * 2 < (8 << 20)
+    # (below the limit: 256-row tiles, so that the last row of a tile lies 255 x 8388592 bytes from its first)
+    p = B.make_params(X, d["W"], out, eps=w.eps, gamma=d["gamma"], flags=(3 + 1) << 8 if below else 0)
+    assert p.ldx == ld
+    assert B.fge_tile_name(True, w.act, w.norm, p) == ("256x256_w2x4" if below else "repacked_operands")
+    ws = torch.empty(max(B.fge_workspace_bytes(True, w.act, w.norm, p), 16), dtype=torch.uint8, device="cuda")
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel()
+    B.fused_gemm_epilogue(X, d["W"], None, w.act, w.norm, p, out)
+    torch.cuda.synchronize()
+    H.check(w, H.to_host_f64(out), None, ref, None, f"rows {ld * 2} bytes apart")
+
+
 @pytest.mark.parametrize("dt", [I.F16, I.F8E4M3])
 @pytest.mark.parametrize("act,norm", [(I.ACT_GELU_TANH, I.NORM_NONE), (I.ACT_RELU, I.NORM_SOFTMAX),
                                       (I.ACT_CLAMP, I.NORM_LOGSUMEXP), (I.ACT_NONE, I.NORM_LAYERNORM)])
