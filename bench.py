@@ -435,7 +435,7 @@ def main() -> int:
             p0 = self.params(0, None)
             nf = B.fge_workspace_bytes(True, w.act, w.norm, p0)
             nu = B.fge_workspace_bytes(False, w.act, w.norm, p0)
-            self.ws = torch.empty(max(nf, nu, 16), dtype=torch.uint8, device="cuda")
+            self.ws = torch.zeros(max(nf, nu, 16), dtype=torch.uint8, device="cuda")    # (zeros: the fault word starts cleared)
             self.p = [self.params(s, self.ws) for s in range(2)]
             self.tile = B.fge_tile_name(True, w.act, w.norm, p0)
             # what fused_gemm_epilogue runs: one kernel (whole rows, or split rows finished by
@@ -454,6 +454,13 @@ def main() -> int:
         def fused(self, s):
             Xs, out, _ = self.sets[s]
             B.fused_gemm_epilogue(Xs, self.W, self.b, self.w.act, self.w.norm, self.p[s], out)
+
+        def check_fault_word(self):
+            """One-kernel form: no wait of any launch so far may have run out (call after a
+            synchronise; the word lies in the workspace and is only ever raised)."""
+            off = B.fge_fault_word_offset(self.w.act, self.w.norm, self.p[0])
+            if off is not None and int(self.ws[off:off + 4].view(torch.int32)[0]) != 0:
+                raise SystemExit(f"bench.py: {self.w.name}: a wait between workgroups ran out (fault word set)")
 
         def unfused(self, s):
             Xs, out, _ = self.sets[s]
@@ -498,7 +505,11 @@ def main() -> int:
         return out
 
     def timed(fn, steps, warmup):
-        return float(np.median(timed_blocks(fn, steps, warmup)))          # ms per step, median block
+        t = float(np.median(timed_blocks(fn, steps, warmup)))             # ms per step, median block
+        owner = getattr(fn, "__self__", None)
+        if hasattr(owner, "check_fault_word"):
+            owner.check_fault_word()
+        return t
 
     def graphed(fn, calls=100, replays=10):
         """ms per step with the launches recorded once into a HIP graph and replayed: what a
@@ -603,6 +614,7 @@ def main() -> int:
         log(f"[bench] fused {t_fused:.4f} ms/step")
         return 0
     fused_blocks = timed_blocks(case.fused, args.steps, args.warmup)
+    case.check_fault_word()
     t_fused = float(np.median(fused_blocks))
     # The dominant kernel's average launch duration.  When the fused path is that one kernel, the
     # events around the timed region measure exactly it, under the same sustained load (the chip
