@@ -455,12 +455,13 @@ def main() -> int:
             Xs, out, _ = self.sets[s]
             B.fused_gemm_epilogue(Xs, self.W, self.b, self.w.act, self.w.norm, self.p[s], out)
 
-        def check_fault_word(self):
-            """One-kernel form: no wait of any launch so far may have run out (call after a
-            synchronise; the word lies in the workspace and is only ever raised)."""
+        def fault_word(self):
+            """The int32 in the workspace that a one-kernel launch raises when a wait between its
+            workgroups runs out (None for the other forms).  The unfused sequence keeps its
+            intermediates in the same workspace, so the word is cleared before fused calls are
+            timed and read after them."""
             off = B.fge_fault_word_offset(self.w.act, self.w.norm, self.p[0])
-            if off is not None and int(self.ws[off:off + 4].view(torch.int32)[0]) != 0:
-                raise SystemExit(f"bench.py: {self.w.name}: a wait between workgroups ran out (fault word set)")
+            return None if off is None else self.ws[off:off + 4].view(torch.int32)
 
         def unfused(self, s):
             Xs, out, _ = self.sets[s]
@@ -505,11 +506,18 @@ def main() -> int:
         return out
 
     def timed(fn, steps, warmup):
-        t = float(np.median(timed_blocks(fn, steps, warmup)))             # ms per step, median block
-        owner = getattr(fn, "__self__", None)
-        if hasattr(owner, "check_fault_word"):
-            owner.check_fault_word()
-        return t
+        return float(np.median(timed_blocks(fn, steps, warmup)))          # ms per step, median block
+
+    def fused_blocks_checked(case, steps, warmup):
+        """timed_blocks of the case's fused call; stops if a one-kernel launch reported a wait
+        that ran out."""
+        word = case.fault_word()
+        if word is not None:
+            word.zero_()
+        blocks = timed_blocks(case.fused, steps, warmup)
+        if word is not None and int(word[0]) != 0:
+            raise SystemExit(f"bench.py: {case.w.name}: a wait between workgroups ran out (fault word set)")
+        return blocks
 
     def graphed(fn, calls=100, replays=10):
         """ms per step with the launches recorded once into a HIP graph and replayed: what a
@@ -610,11 +618,10 @@ def main() -> int:
         for _ in range(5):
             B.fge_activation(src, 0, pc, dst)
         torch.cuda.synchronize()
-        t_fused = timed(case.fused, args.steps, args.warmup)
+        t_fused = float(np.median(fused_blocks_checked(case, args.steps, args.warmup)))
         log(f"[bench] fused {t_fused:.4f} ms/step")
         return 0
-    fused_blocks = timed_blocks(case.fused, args.steps, args.warmup)
-    case.check_fault_word()
+    fused_blocks = fused_blocks_checked(case, args.steps, args.warmup)
     t_fused = float(np.median(fused_blocks))
     # The dominant kernel's average launch duration.  When the fused path is that one kernel, the
     # events around the timed region measure exactly it, under the same sustained load (the chip
@@ -677,7 +684,7 @@ def main() -> int:
             c = Case(wl)
             e = parity(c)
             steps = 1000 if name == "cfg1" else 50
-            tf_ = timed(c.fused, steps, 10)
+            tf_ = float(np.median(fused_blocks_checked(c, steps, 10)))
             tk_ = kernel_time(c, min(steps, 50))
             tu_ = timed(c.unfused, steps if name == "cfg1" else 25, 5)
             per[name] = report(c, tf_, tu_, tk_)
