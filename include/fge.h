@@ -141,10 +141,12 @@ enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_NO_SPLIT_K = 4, F
 
 /* Tile configurations (rows x columns of one workgroup's output tile).  16-bit and 8-bit
  * operands: 64x64, 64x512, 128x128, 128x256, 256x128, 256x256; fp32 operands: 64x64, 64x512,
- * 64x128, 128x128 (split product only) and the persistent narrow-K kernel. */
+ * 64x128, 128x128 (split product only; on four waves, or on eight - FGE_TILE_128x128_W8 - for
+ * problems with one tile per CU) and the persistent narrow-K kernel. */
 typedef enum {
     FGE_TILE_64x64 = 0, FGE_TILE_64x512 = 1, FGE_TILE_128x128 = 2, FGE_TILE_256x256 = 3,
-    FGE_TILE_NARROW_K = 4, FGE_TILE_64x128 = 5, FGE_TILE_128x256 = 7, FGE_TILE_256x128 = 8
+    FGE_TILE_NARROW_K = 4, FGE_TILE_64x128 = 5, FGE_TILE_128x256 = 7, FGE_TILE_256x128 = 8,
+    FGE_TILE_128x128_W8 = 9
 } fge_tile;
 
 typedef struct fge_params {

@@ -85,6 +85,7 @@ bool forced_tile_ok(const fge_params *p) {
     case TILE_256x256: return !f32;
     case TILE_64x128: return f32;
     case TILE_128x256: case TILE_256x128: return !f32;
+    case TILE_128x128_W8: return f32 && !(p->flags & FGE_FLAG_IEEE_FP32);
     case TILE_PANEL:
         return f32 && !(p->flags & FGE_FLAG_IEEE_FP32) && p->K <= 64 && p->N <= 512 &&
                (p->batch == 1 || (p->batch_stride_x == (int64_t)p->M * p->ldx && p->batch_stride_o == (int64_t)p->M * p->ldo));
@@ -231,10 +232,17 @@ int rule_tile(const Problem &pr, int in_dtype, bool ieee_fp32) {
         // bound by the output stream; the kernel for it exists with the split product only
         if (!ieee_fp32 && pr.K <= 64 && pr.N > 256 && pr.N <= 512 && pr.batch == 1 && pr.M >= PANEL_MIN_ROWS)
             return TILE_PANEL;
-        // 128x128 tiles (split product only) once there is one for every CU: a third less operand
-        // traffic from the L2s than 64x128 tiles - fp32 operands make the staging, not the MFMAs,
-        // the bound of these kernels
-        if (!ieee_fp32 && fits(TILE_128x128) && count(TILE_128x128) >= num_cu()) return TILE_128x128;
+        // 128x128 tiles (split product only): a third less operand traffic from the L2s than 64x128
+        // tiles - fp32 operands make the staging, not the MFMAs, the bound of these kernels.  With
+        // more of them than CUs: four waves each, two workgroups per CU.  With one per CU at most:
+        // eight waves each (the four-wave form leaves each SIMD a single wave there and nothing to
+        // run under its stalls; 4096 x 1024 x 1024: 41.1 -> 36.8 us), and that already from 5/8 of
+        // the CUs on (2560 x 1024 x 1024, 160 tiles: 31.9 us against 37.3 us on 64x64 tiles; at 128
+        // tiles the small tiles still win, 29.2 against 31.4 us)
+        if (!ieee_fp32 && fits(TILE_128x128)) {
+            if (count(TILE_128x128) > num_cu()) return TILE_128x128;
+            if (count(TILE_128x128) * 8 >= num_cu() * 5) return TILE_128x128_W8;
+        }
         // fp32 instruction, very large problems: the wide tile halves the operand traffic per flop
         if (ieee_fp32 && fits(TILE_64x512) && pr.K >= 1024 && count(TILE_64x512) >= 2 * num_cu()) return TILE_64x512;
         // otherwise 64x128 tiles, two or three of which share a CU so that one's epilogue hides

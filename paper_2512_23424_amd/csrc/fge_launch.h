@@ -5,7 +5,7 @@
 namespace fge {
 
 enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_64x128 = 5,
-              TILE_GATED = 6, TILE_128x256 = 7, TILE_256x128 = 8, TILE_COUNT = 9 };
+              TILE_GATED = 6, TILE_128x256 = 7, TILE_256x128 = 8, TILE_128x128_W8 = 9, TILE_COUNT = 10 };
 
 // coop_per_cu: workgroups of this tile's cooperative kernel that are resident on one CU at the
 // same time (from the compiler's register / LDS report; a lower bound is safe), 0 if the tile
@@ -27,6 +27,10 @@ inline const TileInfo &tile_info(int id) {
         // workgroups of the 256x256 tiling for problems that leave it short of them
         {128, 256, 512, 4, 1, "128x256_w2x4", nullptr},
         {256, 128, 512, 2, 1, "256x128_w4x2", nullptr},
+        // fp32 operands, split product: the 128x128 tile on eight waves of 64x32 (one workgroup per
+        // CU) - for problems that give a CU one tile only, where the four-wave form leaves each
+        // SIMD a single wave and nothing to run under its stalls
+        {128, 128, 512, 4, 1, nullptr, "128x128_w2x4_splitbf16"},
     };
     return t[id];
 }
@@ -87,7 +91,8 @@ inline int resident_workgroups(const void *kernel, int threads) {
 // Which tiles exist for which operand type (tile selection on the host must agree):
 //   bf16, fp16, fp8: 64x64, 64x512, 128x128 (+ cooperative), 256x256 (+ cooperative)
 //   fp32: 64x64, 64x512, 64x128 (+ cooperative) - once with the fp32 matrix instruction and once
-//         with the split-bf16 product (SPLIT); 128x128 (+ cooperative) with the split product only
+//         with the split-bf16 product (SPLIT); 128x128 (+ cooperative; four waves, and eight for one
+//         tile per CU) with the split product only
 // The 16-bit output type that goes with an operand type (the other output type is fp32).
 template <typename InT> struct NarrowOut { typedef bf16_t type; };
 template <> struct NarrowOut<f16_t> { typedef f16_t type; };
@@ -160,6 +165,13 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
         if constexpr (BF) {
             if (a.coop) FGE_LAUNCH_COOP(256, 256, 2, 4);
             else        FGE_LAUNCH(256, 256, 2, 4);
+            break;
+        }
+        return hipErrorInvalidValue;
+    case TILE_128x128_W8:
+        if constexpr (SPLIT) {
+            if (a.coop) FGE_LAUNCH_COOP(128, 128, 2, 4);
+            else        FGE_LAUNCH(128, 128, 2, 4);
             break;
         }
         return hipErrorInvalidValue;
@@ -236,7 +248,7 @@ inline bool tile_has_coop(int tile, int in_dtype) {
     if (tile == TILE_GATED) return true;
     if (tile == TILE_128x256 || tile == TILE_256x128) return in_dtype != FGE_F32;
     return in_dtype != FGE_F32 ? (tile == TILE_128x128 || tile == TILE_256x256)
-                               : (tile == TILE_64x128 || tile == TILE_128x128);
+                               : (tile == TILE_64x128 || tile == TILE_128x128 || tile == TILE_128x128_W8);
 }
 
 }  // namespace fge

@@ -34,7 +34,7 @@ import torch
 from . import binding as B
 from . import inputs as I
 
-TILES = {"64x64": 0, "64x512": 1, "128x128": 2, "256x256": 3, "narrow_k": 4, "64x128": 5, "128x256": 7, "256x128": 8}
+TILES = {"64x64": 0, "64x512": 1, "128x128": 2, "256x256": 3, "narrow_k": 4, "64x128": 5, "128x256": 7, "256x128": 8, "128x128_w2x4": 9}
 _TAU = {I.F32: 1e-3, I.BF16: 2e-2, I.F16: 4e-3, I.F8E4M3: 2e-2}
 _TOL = {I.F32: 1e-4, I.BF16: 2e-2, I.F16: 4e-3, I.F8E4M3: 2e-2}
 TABLE_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "fge_tile_table.h")

@@ -86,11 +86,12 @@ def test_argument_errors_are_reported_before_any_launch():
     p = _params(M=4096, N=1024, K=1024, ldx=1024, ldw=1024, ldo=1024)
     need = B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p))
     # enough for both forms of split rows.  One-kernel form: a pair per (row, column tile), an
-    # arrival mark per tile, a flag line; two-pass form: 8 column tiles x 2 waves across = 16
-    # strips per row
-    assert 4096 * 8 * 8 + 64 * 8 * 4 + 256 < need == 4096 * (8 * 2) * 8
+    # arrival mark per tile, a flag line; two-pass form: 8 column tiles x 4 waves across (one
+    # 128x128 tile per CU: the eight-wave form) = 32 strips per row
+    assert B.fge_tile_name(True, 2, 2, p) == "128x128_w2x4_splitbf16"
+    assert 4096 * 8 * 8 + 64 * 8 * 4 + 256 < need == 4096 * (8 * 4) * 8
     p.flags = B.FLAG_TWO_PASS
-    assert B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p)) == 4096 * (8 * 2) * 8
+    assert B.lib().fge_workspace_bytes(1, 2, 2, ctypes.byref(p)) == 4096 * (8 * 4) * 8
     p.flags = 0x10
     assert _call(p, act=2, norm=2) == 2        # unknown flag bit
     p.flags = 0

@@ -180,6 +180,31 @@ def test_half_tile_configurations(tile, case, norm):
         H.check(w, got, gaux, ref, raux, f"{tname} flags={flags:#x}")
 
 
+@pytest.mark.parametrize("norm", NORMS)
+@pytest.mark.parametrize("case", [(I.F32, 2060, 100, 2040), (I.F32, 1100, 72, 1288), (I.F32, 4096, 1024, 1024)])
+def test_eight_wave_tile_of_the_split_product(case, norm):
+    """fp32 operands, the 128x128 tile on eight waves (the choice for one tile per CU, here also asked
+    for by flag): ragged and whole shapes, split rows in both forms, every
+    row op, against the oracle at the fp32 gate."""
+    odt, M, K, N = case
+    force = (9 + 1) << 8
+    w = I.Workload(name=f"w8{norm}", M=M, K=K, N=N, in_dtype=I.F32, out_dtype=odt, act=I.ACT_GELU_TANH, norm=norm,
+                   alpha=0.5, post_scale=1.5, eps=1e-5,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1),
+                         "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1), "beta": ("normal", 0.0, 0.1)})
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    p = B.make_params(d["X"], d["W"], torch.empty(M, N, dtype=H.tdtype(odt), device="cuda"), flags=force)
+    assert B.fge_tile_name(True, w.act, norm, p) == "128x128_w2x4_splitbf16"
+    if (M, K, N) == (4096, 1024, 1024):        # one tile per CU: also the automatic choice
+        p.flags = 0
+        assert B.fge_tile_name(True, w.act, norm, p) == "128x128_w2x4_splitbf16"
+    ref, raux = H.oracle_chain(w, t)
+    for flags in (force, force | B.FLAG_TWO_PASS):
+        got, gaux = H.run_gpu(w, t, "fused", dev=d, flags=flags)
+        H.check(w, got, gaux, ref, raux, f"128x128_w2x4_splitbf16 flags={flags:#x}")
+
+
 @pytest.mark.parametrize("shape", [(300, 1024, 1024), (1030, 520, 2040), (77, 136, 328), (5000, 40, 328)])
 def test_fp32_matrix_instruction_on_request(shape):
     """FGE_FLAG_IEEE_FP32 multiplies fp32 operands with the fp32 matrix instruction (products exact
