@@ -388,6 +388,152 @@ __global__ __launch_bounds__(256) void rownorm_wide_kernel(const RowArgs a) {
     }
 }
 
+// Row op over a K-split product for the few rows such problems have: one workgroup of four
+// waves per row.  Every thread owns up to NCH chunks of four neighbouring columns (N <= 1024 * NCH),
+// adds the S partial products of its chunks in slice order - the loads of a chunk's slices are
+// independent of each other, so they are all in flight together: one memory round trip for the
+// whole row, where a single wave walking the slices of a row paid one per slice -, applies scale,
+// bias, activation (and the gate of the gated form), keeps the fp32 row in registers, reduces the
+// row statistic over the workgroup and stores the finished row.  The result does not depend on
+// the schedule (slice order, fixed reduction tree).
+struct SplitRowArgs {
+    const float *P, *P2;        // S dense fp32 rows x N partial products each, `slice` elements apart (P2: second product of the gated form, or null)
+    const float *b, *b2, *gamma, *beta;
+    void *out;
+    float *aux;
+    int M, N, S;                // rows per problem (row r of the partials is row r % M of problem r / M), columns, slices
+    int64_t slice, ldo, bso;
+    float scale, post, lo, hi, eps;
+    int act, norm;
+};
+template <typename OutT, int NCH>
+__global__ __launch_bounds__(256) void splitk_rows_kernel(const SplitRowArgs a) {
+    __shared__ float red[2][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t rowg = blockIdx.x;
+    OutT *out = reinterpret_cast<OutT *>(a.out) + (rowg / a.M) * a.bso + (rowg % a.M) * a.ldo;
+    const int n4 = a.N >> 2;
+    const float inv_n = 1.0f / (float)a.N;
+    int turn = 0;
+    auto block_reduce = [&]<typename Op>(Op, float v) __attribute__((always_inline)) {
+        v = allreduce64<Op>(v);
+        if (lane == 0) red[turn][wave] = v;
+        __syncthreads();
+        const float r = Op::f(Op::f(red[turn][0], red[turn][1]), Op::f(red[turn][2], red[turn][3]));
+        turn ^= 1;
+        return r;
+    };
+    auto slices = [&](const float *q) __attribute__((always_inline)) {
+        floatx4 acc = *reinterpret_cast<const floatx4 *>(q);
+#pragma unroll 4
+        for (int sl = 1; sl < a.S; ++sl) {
+            const floatx4 v = *reinterpret_cast<const floatx4 *>(q + sl * a.slice);
+            acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+        }
+        return acc;
+    };
+    float v[NCH][4];
+    bool ok[NCH];
+    dispatch_act(a.act, [&]<int ACT>() __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) {
+            const int q = tid + j * 256;
+            ok[j] = q < n4;
+            const int col = (ok[j] ? q : 0) << 2;
+            const floatx4 acc = slices(a.P + rowg * a.N + col);
+            floatx4 gate = {1.0f, 1.0f, 1.0f, 1.0f};
+            if (a.P2 != nullptr) {
+                const floatx4 u = slices(a.P2 + rowg * a.N + col);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) gate[e] = a.scale * u[e] + (a.b2 != nullptr ? a.post * a.b2[col + e] : 0.0f);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float bias = a.b != nullptr ? a.post * a.b[col + e] : 0.0f;
+                v[j][e] = activate<ACT>(a.scale * acc[e] + bias, a.lo, a.hi) * gate[e];
+            }
+        }
+    });
+    auto put = [&](int j, const float (&r)[4]) __attribute__((always_inline)) {
+        if (!ok[j]) return;
+        OutT *o = out + ((tid + j * 256) << 2);
+        if constexpr (sizeof(OutT) == 4) {
+            *reinterpret_cast<floatx4 *>(o) = floatx4{r[0], r[1], r[2], r[3]};
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) Store<OutT>::put(o + e, r[e]);
+        }
+    };
+    if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
+        float m = OpMax::ident();
+#pragma unroll
+        for (int j = 0; j < NCH; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (ok[j]) m = max_nc(m, v[j][e]);
+        m = block_reduce(OpMax{}, m);
+        const float c = -m * LOG2E;
+        float sum = 0.0f;
+        float ex[NCH][4];
+#pragma unroll
+        for (int j = 0; j < NCH; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { ex[j][e] = ok[j] ? exp_rel(v[j][e], c) : 0.0f; sum += ex[j][e]; }
+        sum = block_reduce(OpSum{}, sum);
+        if (a.norm == FGE_NORM_LOGSUMEXP) {
+            if (tid == 0) a.aux[rowg] = m + __logf(sum);
+#pragma unroll
+            for (int j = 0; j < NCH; ++j) put(j, v[j]);
+            return;
+        }
+        const float inv = fast_rcp(sum);
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ex[j][e] *= inv;
+            put(j, ex[j]);
+        }
+        return;
+    }
+    float shift = 0.0f;
+    if (a.norm == FGE_NORM_LAYERNORM) {
+        float sm = 0.0f;
+#pragma unroll
+        for (int j = 0; j < NCH; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (ok[j]) sm += v[j][e];
+        shift = block_reduce(OpSum{}, sm) * inv_n;
+    }
+    float q2 = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) if (ok[j]) q2 += (v[j][e] - shift) * (v[j][e] - shift);
+    const float rstd = rsqrtf(block_reduce(OpSum{}, q2) * inv_n + a.eps);
+    const bool use_beta = a.norm == FGE_NORM_LAYERNORM && a.beta != nullptr;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+        if (!ok[j]) continue;
+        const int col = (tid + j * 256) << 2;
+        floatx4 g = {1.0f, 1.0f, 1.0f, 1.0f}, be = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (a.gamma != nullptr) g = *reinterpret_cast<const floatx4 *>(a.gamma + col);
+        if (use_beta) be = *reinterpret_cast<const floatx4 *>(a.beta + col);
+        float r[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = (v[j][e] - shift) * rstd * g[e] + be[e];
+        put(j, r);
+    }
+}
+template <typename OutT> inline hipError_t launch_splitk_rows_t(const SplitRowArgs &a, int64_t rows, hipStream_t s) {
+    const dim3 grid((unsigned)rows), block(256);
+    const int nch = (a.N / 4 + 255) / 256;
+    if (nch <= 1)      hipLaunchKernelGGL((splitk_rows_kernel<OutT, 1>), grid, block, 0, s, a);
+    else if (nch <= 2) hipLaunchKernelGGL((splitk_rows_kernel<OutT, 2>), grid, block, 0, s, a);
+    else if (nch <= 4) hipLaunchKernelGGL((splitk_rows_kernel<OutT, 4>), grid, block, 0, s, a);
+    else if (nch <= 8) hipLaunchKernelGGL((splitk_rows_kernel<OutT, 8>), grid, block, 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 // Second pass of the fused path for rows split over several column strips.  The tile kernel
 // left one pair per (row, strip) in the workspace - `tiles_n` strips of `bn` columns per row -
 // and the row itself parked in `out`; this kernel merges the pairs and finishes the row in

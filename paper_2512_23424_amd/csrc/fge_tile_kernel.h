@@ -126,7 +126,6 @@ void tile_kernel(const TileArgs a) {
     constexpr int BK = ROWB / (int)sizeof(InT);      // 128 fp8 / 64 bf16 / 32 fp32
     constexpr int CW = 16 / (int)sizeof(InT);        // elements per 16-byte chunk
     constexpr int A_LD = BM * 8 / NT, B_LD = BN * 8 / NT;
-    constexpr int RSTEP = NT / 8;                    // rows between a thread's successive chunks
     constexpr bool F8 = sizeof(InT) == 1;            // 64 k per matrix instruction
     constexpr int FR = F8 ? 2 : 1;                   // 16-byte chunks per fragment per k-step
     constexpr int KS = 4 / FR;                       // k-steps per staged tile (the split product has its own loop)
