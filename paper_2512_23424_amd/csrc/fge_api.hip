@@ -853,6 +853,23 @@ int do_rownorm(const void *A, int norm, const fge_params *p, void *out, hipStrea
         if (A == out) return FGE_OK;
         return do_act(A, FGE_ACT_NONE, p, out, s);       // plain copy
     }
+    {
+        // Rows of 8 KB and more: one workgroup per row with the row parked in LDS (the kernel of the
+        // rows too wide for registers) instead of one wave per row with the row in its registers -
+        // measured on 65536 rows: bf16 x 4096 columns +5 to +10 %, bf16 x 8192 +8 to +20 %, fp32 x 8192
+        // (128 registers of row per lane in the wave kernel) up to +60 %, fp32 x 4096 within +-4 %;
+        // below 8 KB the wave kernel wins (fp32 x 512: 5.9 against 3.9 TB/s).  With few rows the
+        // workgroup form also puts four times as many waves on the chip.
+        const int64_t rows = (int64_t)r.batch * r.M;
+        const size_t row_bytes = (size_t)r.N * esize(p->out_dtype);
+        if (row_bytes >= ((size_t)8 << 10) && row_bytes <= ((size_t)64 << 10) - 256 && rows <= INT32_MAX) {
+            const dim3 grid((unsigned)rows), block(256);
+            if (p->out_dtype == FGE_BF16)     hipLaunchKernelGGL((rownorm_wide_kernel<bf16_t, true>), grid, block, row_bytes, s, r);
+            else if (p->out_dtype == FGE_F16) hipLaunchKernelGGL((rownorm_wide_kernel<f16_t, true>), grid, block, row_bytes, s, r);
+            else                              hipLaunchKernelGGL((rownorm_wide_kernel<float, true>), grid, block, row_bytes, s, r);
+            return hip_status(hipGetLastError());
+        }
+    }
     return p->out_dtype == FGE_BF16  ? launch_rownorm<bf16_t>(r, s)
            : p->out_dtype == FGE_F16 ? launch_rownorm<f16_t>(r, s)
                                      : launch_rownorm<float>(r, s);
