@@ -146,7 +146,7 @@ enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_NO_SPLIT_K = 4, F
 typedef enum {
     FGE_TILE_64x64 = 0, FGE_TILE_64x512 = 1, FGE_TILE_128x128 = 2, FGE_TILE_256x256 = 3,
     FGE_TILE_NARROW_K = 4, FGE_TILE_64x128 = 5, FGE_TILE_128x256 = 7, FGE_TILE_256x128 = 8,
-    FGE_TILE_128x128_W8 = 9
+    FGE_TILE_128x128_W8 = 9, FGE_TILE_128x128_S3 = 10
 } fge_tile;
 
 typedef struct fge_params {

@@ -86,6 +86,7 @@ bool forced_tile_ok(const fge_params *p) {
     case TILE_64x128: return f32;
     case TILE_128x256: case TILE_256x128: return !f32;
     case TILE_128x128_W8: return f32 && !(p->flags & FGE_FLAG_IEEE_FP32);
+    case TILE_128x128_S3: return !f32;
     case TILE_PANEL:
         return f32 && !(p->flags & FGE_FLAG_IEEE_FP32) && p->K <= 64 && p->N <= 512 &&
                (p->batch == 1 || (p->batch_stride_x == (int64_t)p->M * p->ldx && p->batch_stride_o == (int64_t)p->M * p->ldo));
@@ -279,6 +280,13 @@ Plan make_plan(const fge_params *p, int norm, bool two_pass = false, int force_t
               : forced_tile(p) >= 0 ? forced_tile(p)
                                     : pick_tile(pr, p->in_dtype, norm, (p->flags & FGE_FLAG_IEEE_FP32) != 0,
                                                 !(p->flags & FGE_FLAG_NO_TABLE));
+    // 16- and 8-bit 128x128 tiles, no more of them than CUs (however the tile was chosen): the form
+    // on eight waves with three stage buffers - no second workgroup shares a CU, so a second K-tile
+    // copy in flight and a second wave per SIMD hide the latencies instead (640 x 4096 x 4096: 43.2
+    // -> 40.3 us, 1024 x 1024 x 4096: 21.4 -> 19.5 us against the four-wave form with three buffers)
+    if (pl.tile == TILE_128x128 && p->in_dtype != FGE_F32 &&
+        (int64_t)((pr.M + 127) / 128) * ((pr.N + 127) / 128) * pr.batch <= num_cu())
+        pl.tile = TILE_128x128_S3;
     const TileInfo &ti = tile_info(pl.tile);
     pl.tiles_m = (pr.M + ti.bm - 1) / ti.bm;
     pl.tiles_n = (pr.N + ti.bn - 1) / ti.bn;
@@ -462,10 +470,6 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
     a.act = act; a.norm = norm;
     a.tiles_m = pl.tiles_m; a.tiles_n = pl.tiles_n; a.batch = pl.pr.batch;
     a.group_m = pl.tiles_m < 8 ? pl.tiles_m : 8;
-    // 16- and 8-bit 128x128 tiles, no more of them than CUs: no second workgroup shares a CU, so
-    // the variant with three stage buffers hides the copy latency instead
-    a.deep = pl.tile == TILE_128x128 && p->in_dtype != FGE_F32 &&
-             (int64_t)pl.tiles_m * pl.tiles_n * pl.pr.batch <= num_cu();
     // an output of half the last-level cache or more is stored with the streaming hint: little of
     // it would still be cached for a consumer, and on its way out it displaces the operand panels
     // the tiles share (batched K = 512 workload, 128 MiB of output: 3.7 % faster; the headline

@@ -38,7 +38,6 @@ struct TileArgs {
     float alpha, post, lo, hi, eps;
     int act, norm;
     int tiles_m, tiles_n, group_m, batch;
-    int deep;                   // 128x128 tiles, at most one per CU: run the variant with three stage buffers
     // cooperative completion of split rows (coop != 0): persistent grid, the column tiles of a
     // row block run in the same round and finish their rows themselves
     int coop;

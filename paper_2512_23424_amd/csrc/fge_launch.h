@@ -5,7 +5,7 @@
 namespace fge {
 
 enum TileId { TILE_64x64 = 0, TILE_64x512 = 1, TILE_128x128 = 2, TILE_256x256 = 3, TILE_PANEL = 4, TILE_64x128 = 5,
-              TILE_GATED = 6, TILE_128x256 = 7, TILE_256x128 = 8, TILE_128x128_W8 = 9, TILE_COUNT = 10 };
+              TILE_GATED = 6, TILE_128x256 = 7, TILE_256x128 = 8, TILE_128x128_W8 = 9, TILE_128x128_S3 = 10, TILE_COUNT = 11 };
 
 // coop_per_cu: workgroups of this tile's cooperative kernel that are resident on one CU at the
 // same time (from the compiler's register / LDS report; a lower bound is safe), 0 if the tile
@@ -31,6 +31,11 @@ inline const TileInfo &tile_info(int id) {
         // CU) - for problems that give a CU one tile only, where the four-wave form leaves each
         // SIMD a single wave and nothing to run under its stalls
         {128, 128, 512, 4, 1, nullptr, "128x128_w2x4_splitbf16"},
+        // 16- and 8-bit operands, at most one 128x128 tile per CU: eight waves of 64x32 and three
+        // stage buffers (no second workgroup shares the CU, so a second K-tile copy in flight and a
+        // second wave per SIMD hide the latencies instead); the plan puts it in the place of
+        // 128x128_w2x2 wherever that tile is chosen for such a problem
+        {128, 128, 512, 4, 1, "128x128_w2x4_s3", nullptr},
     };
     return t[id];
 }
@@ -130,17 +135,17 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
         if (out_dtype != FGE_F32)  FGE_LAUNCH_COOP1(BM, BN, WM, WN, NarrowT);                   \
         else                       FGE_LAUNCH_COOP1(BM, BN, WM, WN, float);                     \
     } while (0)
-    // 128x128 tiles with three stage buffers (one workgroup per CU), ordinary and cooperative launch
+    // 128x128 tiles on eight waves with three stage buffers (one workgroup per CU), ordinary and cooperative launch
 #define FGE_LAUNCH_DEEP128(OT)                                                                  \
     do {                                                                                        \
         if (a.coop) {                                                                           \
-            auto kern = tile_kernel<InT, OT, 128, 128, 2, 2, true, false, false, false, 3>;     \
-            static const int resident = resident_workgroups(reinterpret_cast<const void *>(kern), 256); \
+            auto kern = tile_kernel<InT, OT, 128, 128, 2, 4, true, false, false, false, 3>;     \
+            static const int resident = resident_workgroups(reinterpret_cast<const void *>(kern), 512); \
             if ((int)grid.x > resident) return hipErrorCooperativeLaunchTooLarge;               \
-            hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, a);                                 \
+            hipLaunchKernelGGL(kern, grid, dim3(512), 0, s, a);                                 \
         } else {                                                                                \
-            hipLaunchKernelGGL((tile_kernel<InT, OT, 128, 128, 2, 2, false, false, false, false, 3>), grid, \
-                               dim3(256), 0, s, a);                                             \
+            hipLaunchKernelGGL((tile_kernel<InT, OT, 128, 128, 2, 4, false, false, false, false, 3>), grid, \
+                               dim3(512), 0, s, a);                                             \
         }                                                                                       \
     } while (0)
     constexpr bool BF = sizeof(InT) <= 2;
@@ -149,15 +154,15 @@ inline hipError_t launch_tile_any(int tile, int out_dtype, dim3 grid, hipStream_
     case TILE_64x512:  FGE_LAUNCH(64, 512, 1, 4); break;
     case TILE_128x128:
         if constexpr (BF || SPLIT) {
-            if constexpr (BF && !SPLIT) {
-                if (a.deep) {
-                    if (out_dtype != FGE_F32) FGE_LAUNCH_DEEP128(NarrowT);
-                    else                      FGE_LAUNCH_DEEP128(float);
-                    break;
-                }
-            }
             if (a.coop) FGE_LAUNCH_COOP(128, 128, 2, 2);
             else        FGE_LAUNCH(128, 128, 2, 2);
+            break;
+        }
+        return hipErrorInvalidValue;
+    case TILE_128x128_S3:
+        if constexpr (BF && !SPLIT) {
+            if (out_dtype != FGE_F32) FGE_LAUNCH_DEEP128(NarrowT);
+            else                      FGE_LAUNCH_DEEP128(float);
             break;
         }
         return hipErrorInvalidValue;
@@ -247,7 +252,7 @@ hipError_t launch_gated_f8(int out_dtype, dim3 grid, hipStream_t s, const TileAr
 inline bool tile_has_coop(int tile, int in_dtype) {
     if (tile == TILE_GATED) return true;
     if (tile == TILE_128x256 || tile == TILE_256x128) return in_dtype != FGE_F32;
-    return in_dtype != FGE_F32 ? (tile == TILE_128x128 || tile == TILE_256x256)
+    return in_dtype != FGE_F32 ? (tile == TILE_128x128 || tile == TILE_128x128_S3 || tile == TILE_256x256)
                                : (tile == TILE_64x128 || tile == TILE_128x128 || tile == TILE_128x128_W8);
 }
 

@@ -154,7 +154,10 @@ def test_forced_tile_configurations():
     assert _call(_params(**f32, flags=tile(6))) == 4 and _call(_params(**f32, flags=tile(14))) == 4
     b16 = dict(f32, in_dtype=1, out_dtype=1)
     assert B.fge_tile_name(True, 2, 2, _params(**b16, flags=tile(3))) == "256x256_w2x4"
-    assert B.fge_tile_name(True, 2, 2, _params(**b16, flags=tile(2))) == "128x128_w2x2"
+    assert B.fge_tile_name(True, 2, 2, _params(**b16, flags=tile(2))) == "128x128_w2x4_s3"    # 32 tiles, at most one per CU: eight waves, three stage buffers
+    big16 = dict(b16, M=8192)
+    assert B.fge_tile_name(True, 2, 2, _params(**big16, flags=tile(2))) == "128x128_w2x2"      # 512 tiles: two four-wave workgroups per CU
+    assert B.fge_tile_name(True, 2, 2, _params(**big16, flags=tile(10))) == "128x128_w2x4_s3"
     assert _call(_params(**b16, flags=tile(5))) == 4           # 64x128: fp32 operands only
     nk = _params(M=100, N=328, K=40, ldx=40, ldw=40, ldo=328, flags=tile(4))
     assert B.fge_tile_name(True, 5, 4, nk) == "panel64x512_w1x8_splitbf16"

@@ -158,11 +158,12 @@ def test_split_rows_one_kernel_and_two_pass(norm, case):
 
 @pytest.mark.parametrize("norm", NORMS)
 @pytest.mark.parametrize("case", [(I.BF16, I.BF16, 2050, 200, 2040), (I.F16, I.F32, 1100, 72, 1288), (I.F8E4M3, I.BF16, 2100, 272, 2064)])
-@pytest.mark.parametrize("tile", [(7, "128x256_w2x4"), (8, "256x128_w4x2")])
+@pytest.mark.parametrize("tile", [(7, "128x256_w2x4"), (8, "256x128_w4x2"), (10, "128x128_w2x4_s3")])
 def test_half_tile_configurations(tile, case, norm):
     """The 128x256 and 256x128 tiles (asked for by flag; the tile choice takes them where its table
-    says so): ragged M / N / K, split rows in the one-kernel form (where the grid is large enough
-    for it) and in the two-pass form, every row op, against the oracle."""
+    says so) and the 128x128 tile on eight waves with three stage buffers (the form of at most one
+    tile per CU, here also on more): ragged M / N / K, split rows in the one-kernel form (where the
+    grid is large enough for it) and in the two-pass form, every row op, against the oracle."""
     tid, tname = tile
     idt, odt, M, K, N = case
     force = (tid + 1) << 8
