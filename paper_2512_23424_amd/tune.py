@@ -397,7 +397,7 @@ def sweep(quick: bool = False, log=print) -> List[Tuple]:
     of the rule's own choice, whether the search's find was confirmed).  The island search proposes;
     its winner replaces the rule's own choice only if a second timing of the two under sustained
     load - alternating, twice each, the same call repeated for 30 ms before three timed blocks -
-    confirms it at more than 4 %: launches of ten microseconds time noisily, a short run flatters
+    confirms it at more than 2.5 %: launches of ten microseconds time noisily, a short run flatters
     the configurations that lose most once the clock has settled, and the table should record
     neither.  (Six rounds of the search instead of the
     paper's three: with the few dozen launch configurations of a sweep point the search then visits
@@ -434,7 +434,7 @@ def sweep(quick: bool = False, log=print) -> List[Tuple]:
                                 a.append(prob.sustained(own_flags))
                                 b_.append(prob.sustained(found["flags"] | B.FLAG_NO_SPLIT_K))
                             t_own, t_found = min(a), min(b_)
-                            confirmed = t_own > 1.04 * t_found
+                            confirmed = t_own > 1.025 * t_found
                         if t_own is None:
                             t_own = t_found = prob.run(own_flags, 30, 3)[1]
                         pick = fd if confirmed else own
@@ -454,7 +454,7 @@ def write_table(rows, path: str = TABLE_PATH) -> None:
                 "// Written by `python -m paper_2512_23424_amd.tune --write-table` on an MI355X: the island search\n"
                 "// of tune.py over every configuration the library accepts, SiLU with and without a row op\n"
                 "// (RMSNorm), bf16 and E4M3 operands, bf16 results; a find replaces the rule's own choice only\n"
-                "// when a second timing confirms it at more than 4 %.  Columns: operand class (0: 16-bit,\n"
+                "// when a second timing confirms it at more than 2.5 %.  Columns: operand class (0: 16-bit,\n"
                 "// 1: 8-bit), row op follows (0 / 1), ceil(M / 256), ceil(N / 256), K, tile id, split rows finished\n"
                 "// by the second pass (0 / 1); the comment gives the time in ms and, for a confirmed find, the\n"
                 "// time of the rule's choice.\n"
