@@ -140,7 +140,9 @@ enum { FGE_FLAG_TWO_PASS = 1, FGE_FLAG_IEEE_FP32 = 2, FGE_FLAG_NO_SPLIT_K = 4, F
 #define FGE_FLAG_TILE(t) ((((int)(t)) + 1) << 8)
 
 /* Tile configurations (rows x columns of one workgroup's output tile).  16-bit and 8-bit
- * operands: 64x64, 64x512, 128x128, 128x256, 256x128, 256x256; fp32 operands: 64x64, 64x512,
+ * operands: 64x64, 64x512, 128x128 (FGE_TILE_128x128_S3, eight waves and three stage buffers,
+ * takes its place for problems with at most one such tile per CU), 128x256, 256x128, 256x256;
+ * fp32 operands: 64x64, 64x512,
  * 64x128, 128x128 (split product only; on four waves, or on eight - FGE_TILE_128x128_W8 - for
  * problems with one tile per CU) and the persistent narrow-K kernel. */
 typedef enum {

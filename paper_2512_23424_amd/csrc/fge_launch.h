@@ -94,7 +94,8 @@ inline int resident_workgroups(const void *kernel, int threads) {
 }
 
 // Which tiles exist for which operand type (tile selection on the host must agree):
-//   bf16, fp16, fp8: 64x64, 64x512, 128x128 (+ cooperative), 256x256 (+ cooperative)
+//   bf16, fp16, fp8: 64x64, 64x512, 128x128 (+ cooperative; four waves, and eight with three
+//         stage buffers for one tile per CU), 256x256 and its halves 128x256, 256x128 (+ cooperative)
 //   fp32: 64x64, 64x512, 64x128 (+ cooperative) - once with the fp32 matrix instruction and once
 //         with the split-bf16 product (SPLIT); 128x128 (+ cooperative; four waves, and eight for one
 //         tile per CU) with the split product only
