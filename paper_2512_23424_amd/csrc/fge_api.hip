@@ -22,6 +22,9 @@ static __device__ __align__(256) unsigned char scratch[FGE_STATIC_SCRATCH_BYTES]
 namespace {
 
 thread_local int g_last_hip = 0;
+// Rows of W that exist when that is fewer than the problem's N (set around the inner call of the
+// repacked path, see run_repacked; 0: N)
+thread_local int g_w_rows = 0;
 
 // Launch counter: its value marks "arrived" in the cooperative form, so marks left in a
 // workspace by earlier launches (or by whatever the memory held before) never match.
@@ -126,18 +129,20 @@ int check_common(const fge_params *p, int act, int norm, bool need_in) {
 // row operation on its own (need_in false: the unfused K3, fge_row_op) needs the row to fit a
 // wave's registers - the fused tile kernels split rows of any width over column tiles.
 // Everything else goes to the element-granular kernels.
+// An operand (row stride ld, stride bs between problems, both in elements) as the tile kernels
+// can stage it where it lies: K, ld and bs whole 16-byte units, and rows less than 8 MiB apart
+// (a row is addressed by a 32-bit byte offset from the first row of its tile, at most 256 rows).
+bool operand_ok(const fge_params *p, int64_t ld, int64_t bs) {
+    const int64_t is = (int64_t)esize(p->in_dtype);
+    constexpr int64_t SPAN = ((int64_t)1 << 31) / 256;
+    return (p->K * is) % 16 == 0 && (ld * is) % 16 == 0 && (bs * is) % 16 == 0 && ld * is < SPAN;
+}
+
 bool vectorisable(const fge_params *p, int norm, bool need_in) {
-    const size_t is = esize(p->in_dtype), os = esize(p->out_dtype);
+    const size_t os = esize(p->out_dtype);
     if ((p->N * os) % 16 || (p->ldo * os) % 16) return false;
     if (p->batch > 1 && (p->batch_stride_o * os) % 16) return false;
-    if (need_in) {
-        if ((p->K * is) % 16 || (p->ldx * is) % 16 || (p->ldw * is) % 16) return false;
-        if (p->batch > 1 && (p->batch_stride_x * is) % 16) return false;
-        // the tile kernels address an operand row by a 32-bit byte offset from the first row of
-        // the tile (at most 256 rows)
-        constexpr int64_t SPAN = ((int64_t)1 << 31) / 256;
-        if (p->ldx * (int64_t)is >= SPAN || p->ldw * (int64_t)is >= SPAN) return false;
-    }
+    if (need_in && (!operand_ok(p, p->ldx, p->batch > 1 ? p->batch_stride_x : 0) || !operand_ok(p, p->ldw, 0))) return false;
     if (norm != FGE_NORM_NONE && !need_in && p->N > MAX_ROWOP_N) return false;
     return true;
 }
@@ -372,6 +377,7 @@ KSplit k_split(const fge_params *p, int norm, const Plan &pl) {
 struct Repack {
     bool use;
     bool odd_out;                // the result is not storable in 16-byte units either
+    bool copy_x, copy_w;         // which operands are copied (one that the tile kernels can stage where it lies is not)
     int Kp, Np;                  // padded contraction length / padded width of the fp32 rows
     int64_t rows, w_rows;        // rows of the padded X / W
     size_t off_w, off_b, off_mid, off_inner, bytes;      // workspace layout; the padded X sits at 0
@@ -465,6 +471,7 @@ TileArgs tile_args(const void *X, const void *W, const float *b, int act, int no
     a.X = X; a.W = W; a.b = b; a.gamma = p->gamma; a.beta = p->beta;
     a.out = out; a.aux = p->aux_out; a.ws = reinterpret_cast<float2 *>(p->workspace);
     a.M = pl.pr.M; a.N = pl.pr.N; a.K = pl.pr.K;
+    a.w_rows = g_w_rows > 0 && g_w_rows < pl.pr.N ? g_w_rows : pl.pr.N;
     a.ldx = pl.pr.ldx; a.ldw = pl.pr.ldw; a.ldo = pl.pr.ldo; a.bsx = pl.pr.bsx; a.bso = pl.pr.bso;
     a.alpha = p->alpha; a.post = p->post_scale; a.lo = clamp_low(p); a.hi = p->clamp_hi; a.eps = p->eps;
     a.act = act; a.norm = norm;
@@ -635,10 +642,16 @@ Repack plan_repack(const fge_params *p, int norm) {
     r.Np = r.odd_out ? (p->N + 3) / 4 * 4 : p->N;
     r.rows = rows;
     r.w_rows = r.Np;
+    // an operand that can be staged where it lies is not copied (odd N with an even K - a
+    // vocabulary of 50257 entries - then costs no copy at all: the padding columns of the fp32
+    // rows are fed from W's last row, see TileArgs::w_rows, and never looked at afterwards)
+    const int64_t bsx = p->batch > 1 ? p->batch_stride_x : 0;
+    r.copy_x = !operand_ok(p, p->ldx, bsx) || (r.odd_out && p->batch > 1 && bsx != (int64_t)p->M * p->ldx);
+    r.copy_w = !operand_ok(p, p->ldw, 0);
     r.inner = *p;
     r.inner.K = r.Kp;
-    r.inner.ldx = r.inner.ldw = r.Kp;
-    r.inner.batch_stride_x = (int64_t)p->M * r.Kp;
+    if (r.copy_x) { r.inner.ldx = r.Kp; r.inner.batch_stride_x = (int64_t)p->M * r.Kp; }
+    if (r.copy_w) r.inner.ldw = r.Kp;
     r.inner.workspace = nullptr;
     r.inner.workspace_bytes = 0;
     if (r.odd_out) {             // one tall problem into dense fp32 rows of padded width
@@ -652,7 +665,7 @@ Repack plan_repack(const fge_params *p, int norm) {
         r.inner.aux_out = nullptr;
     }
     if (!vectorisable(&r.inner, r.odd_out ? FGE_NORM_NONE : norm, true)) return r;     // (cannot happen)
-    const size_t xp = round256((size_t)rows * r.Kp * is), wp = round256((size_t)r.w_rows * r.Kp * is);
+    const size_t xp = r.copy_x ? round256((size_t)rows * r.Kp * is) : 0, wp = r.copy_w ? round256((size_t)r.w_rows * r.Kp * is) : 0;
     r.off_w = xp;
     r.off_b = r.off_w + wp;
     r.off_mid = r.off_b + (r.odd_out ? round256((size_t)r.Np * sizeof(float)) : 0);
@@ -666,14 +679,21 @@ int run_repacked(const void *X, const void *W, const float *b, int act, int norm
                  const Repack &rp, void *out, hipStream_t s) {
     char *ws = static_cast<char *>(p->workspace);
     int rc;
-    const PadArgs ax{X, ws, p->M, p->batch, p->K, rp.Kp, p->ldx, p->batch > 1 ? p->batch_stride_x : 0, rp.rows};
-    if ((rc = hip_status(launch_pad_rows(p->in_dtype, s, ax)))) return rc;
-    const PadArgs aw{W, ws + rp.off_w, p->N, 1, p->K, rp.Kp, p->ldw, 0, rp.w_rows};
-    if ((rc = hip_status(launch_pad_rows(p->in_dtype, s, aw)))) return rc;
+    const void *Xi = X, *Wi = W;
+    if (rp.copy_x) {
+        const PadArgs ax{X, ws, p->M, p->batch, p->K, rp.Kp, p->ldx, p->batch > 1 ? p->batch_stride_x : 0, rp.rows};
+        if ((rc = hip_status(launch_pad_rows(p->in_dtype, s, ax)))) return rc;
+        Xi = ws;
+    }
+    if (rp.copy_w) {
+        const PadArgs aw{W, ws + rp.off_w, p->N, 1, p->K, rp.Kp, p->ldw, 0, rp.w_rows};
+        if ((rc = hip_status(launch_pad_rows(p->in_dtype, s, aw)))) return rc;
+        Wi = ws + rp.off_w;
+    }
     fge_params q = rp.inner;
     q.workspace = ws + rp.off_inner;
     q.workspace_bytes = p->workspace_bytes - rp.off_inner;
-    if (!rp.odd_out) return run_fused(ws, ws + rp.off_w, b, act, norm, &q, out, s);
+    if (!rp.odd_out) return run_fused(Xi, Wi, b, act, norm, &q, out, s);
     const float *bp = nullptr;
     if (b != nullptr) {
         float *dst = reinterpret_cast<float *>(ws + rp.off_b);
@@ -681,7 +701,11 @@ int run_repacked(const void *X, const void *W, const float *b, int act, int norm
         bp = dst;
     }
     void *mid = ws + rp.off_mid;
-    if ((rc = run_fused(ws, ws + rp.off_w, bp, act, FGE_NORM_NONE, &q, mid, s))) return rc;
+    {
+        // W as it lies has N rows, the padded problem Np columns: the tile kernels stop at row N - 1
+        struct Scope { Scope(int n) { g_w_rows = n; } ~Scope() { g_w_rows = 0; } } scope(rp.copy_w ? 0 : p->N);
+        if ((rc = run_fused(Xi, Wi, bp, act, FGE_NORM_NONE, &q, mid, s))) return rc;
+    }
     GenArgs g = gen_args(p);
     g.X = mid; g.ldx = rp.Np; g.bsx = (int64_t)p->M * rp.Np; g.dst = out; g.norm = norm;
     return hip_status(launch_generic_row(FGE_F32, p->out_dtype, s, g));

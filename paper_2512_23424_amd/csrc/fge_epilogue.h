@@ -33,6 +33,8 @@ struct TileArgs {
     float2 *ws;                 // split rows: [batch*M][tiles_n * waves across] strip pairs for the
                                 // second pass, or [batch*M][tiles_n] tile pairs (cooperative form)
     int M, N, K;
+    int w_rows;                 // rows of W that exist (N, or fewer when the columns from there on are padding:
+                                // they are fed from row w_rows - 1 and their results are never looked at)
     int64_t ldx, ldw, ldo, bsx, bso;
     int64_t bsw;                // offset of problem z in W (0: W is shared; a K-split gives each slice its own k range)
     float alpha, post, lo, hi, eps;

@@ -132,6 +132,101 @@ __global__ __launch_bounds__(256) void generic_row_kernel(const GenArgs a) {
     }
 }
 
+// The same row operation for fp32 source rows that start on 16-byte boundaries (the rows of padded
+// width the repacked path produces; ldx and bsx multiples of 4) and a result of any width and
+// stride: one workgroup of four waves per row.  The statistics passes read 16 bytes per lane, four
+// loads in flight per thread; the last pass reads and writes one element per lane, so that a
+// wave's stores are one contiguous run whatever the alignment of the result's rows.  CACHE: the
+// row (at most 64 KB) is parked in LDS by the first pass and read from there afterwards.
+// (The wave-per-row kernel above walks a row with one load in flight per lane: 2048 rows of 50257
+// columns took it 1.0 ms.)
+template <typename OutT, bool CACHE>
+__global__ __launch_bounds__(256) void aligned_src_row_kernel(const GenArgs a) {
+    __shared__ float red[2][4];
+    extern __shared__ __attribute__((aligned(16))) float rowbuf[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t rowg = blockIdx.x;
+    const float *src = row_ptr<float>(a.X, rowg, a.M, a.ldx, a.bsx);
+    OutT *out = const_cast<OutT *>(row_ptr<OutT>(a.dst, rowg, a.M, a.ldd, a.bsd));
+    const int n4 = a.N >> 2;                                     // whole groups of four columns
+    const float inv_n = 1.0f / (float)a.N;
+    int turn = 0;
+    auto block_reduce = [&]<typename Op>(Op, float v) __attribute__((always_inline)) {
+        v = allreduce64<Op>(v);
+        if (lane == 0) red[turn][wave] = v;
+        __syncthreads();
+        const float r = Op::f(Op::f(red[turn][0], red[turn][1]), Op::f(red[turn][2], red[turn][3]));
+        turn ^= 1;
+        return r;
+    };
+    // first pass over the row: f(v) for every valid element, 16 bytes per lane (+ the ragged tail)
+    auto sweep_first = [&](auto &&f) __attribute__((always_inline)) {
+#pragma unroll 4
+        for (int q = tid; q < n4; q += 256) {
+            const floatx4 v = *reinterpret_cast<const floatx4 *>(src + 4 * q);
+            if constexpr (CACHE) *reinterpret_cast<floatx4 *>(rowbuf + 4 * q) = v;
+            f(v[0]); f(v[1]); f(v[2]); f(v[3]);
+        }
+        const int j = 4 * n4 + tid;
+        if (j < a.N) {
+            const float v = src[j];
+            if constexpr (CACHE) rowbuf[j] = v;
+            f(v);
+        }
+        if constexpr (CACHE) __syncthreads();
+    };
+    auto sweep = [&](auto &&f) __attribute__((always_inline)) {
+        const float *r = CACHE ? rowbuf : src;
+#pragma unroll 4
+        for (int q = tid; q < n4; q += 256) {
+            const floatx4 v = *reinterpret_cast<const floatx4 *>(r + 4 * q);
+            f(v[0]); f(v[1]); f(v[2]); f(v[3]);
+        }
+        const int j = 4 * n4 + tid;
+        if (j < a.N) f(r[j]);
+    };
+    // last pass: out[j] = g(j, v[j]), one element per lane and step
+    auto emit = [&](auto &&g) __attribute__((always_inline)) {
+        const float *r = CACHE ? rowbuf : src;
+#pragma unroll 4
+        for (int j = tid; j < a.N; j += 256) Store<OutT>::put(out + j, g(j, r[j]));
+    };
+    if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
+        float m = OpMax::ident();
+        sweep_first([&](float v) __attribute__((always_inline)) { m = max_nc(m, v); });
+        m = block_reduce(OpMax{}, m);
+        const float c = -m * LOG2E;
+        float s = 0.0f;
+        sweep([&](float v) __attribute__((always_inline)) { s += exp_rel(v, c); });
+        s = block_reduce(OpSum{}, s);
+        if (a.norm == FGE_NORM_SOFTMAX) {
+            const float inv = 1.0f / s;
+            emit([&](int, float v) __attribute__((always_inline)) { return exp_rel(v, c) * inv; });
+        } else {
+            if (tid == 0) a.aux[rowg] = m + __logf(s);
+            emit([&](int, float v) __attribute__((always_inline)) { return v; });
+        }
+    } else if (a.norm == FGE_NORM_LAYERNORM) {
+        float s = 0.0f;
+        sweep_first([&](float v) __attribute__((always_inline)) { s += v; });
+        const float mean = block_reduce(OpSum{}, s) * inv_n;
+        float d2 = 0.0f;
+        sweep([&](float v) __attribute__((always_inline)) { d2 += (v - mean) * (v - mean); });
+        const float rstd = rsqrtf(block_reduce(OpSum{}, d2) * inv_n + a.eps);
+        emit([&](int j, float v) __attribute__((always_inline)) {
+            return (v - mean) * rstd * (a.gamma != nullptr ? a.gamma[j] : 1.0f) + (a.beta != nullptr ? a.beta[j] : 0.0f);
+        });
+    } else if (a.norm == FGE_NORM_RMSNORM) {
+        float s = 0.0f;
+        sweep_first([&](float v) __attribute__((always_inline)) { s += v * v; });
+        const float rr = rsqrtf(block_reduce(OpSum{}, s) * inv_n + a.eps);
+        emit([&](int j, float v) __attribute__((always_inline)) { return v * rr * (a.gamma != nullptr ? a.gamma[j] : 1.0f); });
+    } else {
+        sweep_first([&](float) __attribute__((always_inline)) {});
+        emit([&](int, float v) __attribute__((always_inline)) { return v; });
+    }
+}
+
 // K-split product: X holds `K` dense fp32 slices of M x N partial sums, `bsx` elements apart; four
 // neighbouring columns per thread (N is a multiple of 4).  The slices are added in slice order,
 // so the result does not depend on how the launch was scheduled.
@@ -261,6 +356,24 @@ hipError_t launch_generic_act(int dtype, hipStream_t s, const GenArgs &a) {
 hipError_t launch_generic_row(int src_dtype, int out_dtype, hipStream_t s, const GenArgs &a) {
     const int64_t rows = (int64_t)a.batch * a.M;
     const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    if (src_dtype == FGE_F32 && a.X != a.dst && a.ldx % 4 == 0 && a.bsx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & 15) == 0 &&
+        rows <= INT32_MAX) {
+        // source rows on 16-byte boundaries: one workgroup per row; the row parked in LDS when it fits
+        const dim3 g1((unsigned)rows);
+        const size_t row_bytes = ((size_t)a.N * 4 + 15) / 16 * 16;
+#define FGE_ROW(OT)                                                                                       \
+        do {                                                                                               \
+            if (row_bytes <= ((size_t)64 << 10) - 256)                                                     \
+                hipLaunchKernelGGL((aligned_src_row_kernel<OT, true>), g1, block, row_bytes, s, a);        \
+            else                                                                                           \
+                hipLaunchKernelGGL((aligned_src_row_kernel<OT, false>), g1, block, 0, s, a);               \
+        } while (0)
+        if (out_dtype == FGE_BF16)     FGE_ROW(bf16_t);
+        else if (out_dtype == FGE_F16) FGE_ROW(f16_t);
+        else                           FGE_ROW(float);
+#undef FGE_ROW
+        return hipGetLastError();
+    }
     if (src_dtype == FGE_F32) {
         if (out_dtype == FGE_BF16)     hipLaunchKernelGGL((generic_row_kernel<float, bf16_t>), grid, block, 0, s, a);
         else if (out_dtype == FGE_F16) hipLaunchKernelGGL((generic_row_kernel<float, f16_t>), grid, block, 0, s, a);

@@ -85,7 +85,7 @@ void panel_kernel(const TileArgs a) {
     for (int j = 0; j < NB; ++j) {
         const int col = wave_n * WTN + j * 32 + l32;
         binit[j] = (a.b != nullptr && col < a.N) ? a.post * a.b[col] : 0.0f;
-        const float *wr = W + (int64_t)min(col, a.N - 1) * a.ldw;
+        const float *wr = W + (int64_t)min(col, a.w_rows - 1) * a.ldw;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int k0 = 16 * t + 8 * h;

@@ -238,7 +238,7 @@ void tile_kernel(const TileArgs a) {
         rowB[i] = wave_id * 8 * B_LD + i * 8 + ld_r;
         gcB[i] = ld_c ^ swz(rowB[i]);
         const int prow = rowB[i] - (second ? BNO : 0);   // row of W (gated: or of W2) in the tile
-        oB[i] = (uint32_t)((int64_t)(min(n0 + prow, a.N - 1) - n0) * a.ldw + gcB[i] * CW) * (uint32_t)sizeof(InT) + PRE - (i & 3) * 1024;
+        oB[i] = (uint32_t)((int64_t)(min(n0 + prow, a.w_rows - 1) - n0) * a.ldw + gcB[i] * CW) * (uint32_t)sizeof(InT) + PRE - (i & 3) * 1024;
     }
 
     // full tile: asynchronous global -> LDS, no registers involved; completion is tracked by
@@ -313,7 +313,7 @@ void tile_kernel(const TileArgs a) {
         gS[i] = X + (int64_t)min(m0 + it_row + i * (NT / 4), a.M - 1) * a.ldx + it_kg * 8;
 #pragma unroll
     for (int i = 0; i < B_IT; ++i)
-        gS[A_IT + i] = W + (int64_t)min(n0 + it_row + i * (NT / 4), a.N - 1) * a.ldw + it_kg * 8;
+        gS[A_IT + i] = W + (int64_t)min(n0 + it_row + i * (NT / 4), a.w_rows - 1) * a.ldw + it_kg * 8;
     u32x4 sreg[NI][2];
     // GUARD: the tile may reach past K (K is a multiple of 4: chunks are whole)
     auto stage_load = [&]<bool GUARD>(int k0) __attribute__((always_inline)) {

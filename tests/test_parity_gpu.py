@@ -358,6 +358,34 @@ def test_odd_strides_of_a_large_batch_run_repacked():
     assert torch.isnan(outd[:, 150:, :]).all() and torch.isnan(outd[:, :, 515:]).all()
 
 
+@pytest.mark.parametrize("norm", NORMS)
+@pytest.mark.parametrize("case", [(I.BF16, I.BF16, 1, 2050, 1024, 4099), (I.F32, I.F32, 1, 1500, 512, 2051),
+                                  (I.BF16, I.F32, 3, 700, 256, 1031), (I.F8E4M3, I.BF16, 1, 1100, 512, 4097),
+                                  (I.BF16, I.BF16, 1, 300, 256, 16389), (I.F16, I.F16, 1, 260, 128, 16390)])
+def test_odd_width_with_operands_that_need_no_copy(case, norm):
+    """N odd, K and the operands' strides on the 16-byte grid (a vocabulary of 50257 entries is the
+    case that matters): the fp32 rows of padded width are produced straight from X and W as they
+    lie - W ends N rows down, the padding columns are fed from its last row - and the row kernel
+    writes the odd-width result (the last two cases: rows of more than 64 KB, which that kernel
+    re-reads from memory instead of parking them in LDS)."""
+    idt, odt, batch, M, K, N = case
+    w = I.Workload(name=f"oddn{norm}", M=M, K=K, N=N, batch=batch, in_dtype=idt, out_dtype=odt, act=I.ACT_SILU, norm=norm,
+                   alpha=1.0 / K ** 0.5 if idt == I.F8E4M3 else 0.5, post_scale=1.5, eps=1e-5,
+                   dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 1.0 if idt == I.F8E4M3 else 0.1),
+                         "b": ("uniform", -0.5, 0.5), "gamma": ("normal", 1.0, 0.1), "beta": ("normal", 0.0, 0.1)})
+    t = I.generate(w)
+    d = {k: H.to_device(v) for k, v in t.items()}
+    p = B.make_params(d["X"].view(batch, M, K) if batch > 1 else d["X"], d["W"],
+                      torch.empty((batch, M, N) if batch > 1 else (M, N), dtype=H.tdtype(odt), device="cuda"))
+    assert B.fge_tile_name(True, w.act, norm, p) == "repacked_operands"
+    # no copy of either operand: the workspace holds the padded bias, the fp32 rows and the tile kernels' own
+    rows, Np = batch * M, (N + 3) // 4 * 4
+    assert B.fge_workspace_bytes(True, w.act, norm, p) < 256 + Np * 4 + 256 + rows * Np * 4 + (8 << 20)
+    ref, raux = H.oracle_chain(w, t)
+    got, gaux = H.run_gpu(w, t, "fused", dev=d)
+    H.check(w, got, gaux, ref, raux, f"odd width, operands in place {case}")
+
+
 def test_unaligned_strides_and_odd_batches():
     """Aligned extents but row and batch strides that are not multiples of 16 bytes: padding is
     left untouched, results match the oracle."""
