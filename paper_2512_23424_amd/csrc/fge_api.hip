@@ -624,9 +624,10 @@ int run_fused(const void *X, const void *W, const float *b, int act, int norm, c
 // kernel: X and W are copied into dense workspace buffers with K padded by zeros to a whole
 // chunk (the extra terms of every sum are exact zeros), and the padded problem runs on the
 // tile kernels.  When the result's own extents or strides are odd as well, the tile kernel
-// applies the activation and writes fp32 rows of padded width into the workspace (W gets zero
-// rows, b zero entries for the padding columns), and the element-granular row kernel - which
-// walks a row element by element and never looks at the padding - turns them into `out`.
+// applies the activation and writes fp32 rows of padded width into the workspace (a copied W
+// gets zero rows, b zero entries for the padding columns), and a row kernel that stores
+// element by element and never looks at the padding columns turns them into `out`
+// (launch_generic_row: one workgroup per row, since these rows start on 16-byte boundaries).
 // The stage entry points and the unfused sequence keep the element-granular product.
 constexpr double REPACK_MIN_FLOP = 3.0e7;   // below this the element-granular product is as fast as four launches
 
