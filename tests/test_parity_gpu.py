@@ -386,6 +386,23 @@ def test_odd_width_with_operands_that_need_no_copy(case, norm):
     H.check(w, got, gaux, ref, raux, f"odd width, operands in place {case}")
 
 
+@pytest.mark.parametrize("norm", [I.NORM_LAYERNORM, I.NORM_RMSNORM, I.NORM_LOGSUMEXP])
+def test_odd_width_without_bias_and_affine_vectors(norm):
+    """The same path with b, gamma and beta absent (the row kernel behind the fp32 rows then
+    uses ones and zeros), rows below and above the 64 KB it parks in LDS."""
+    for M, K, N in ((900, 256, 2051), (130, 128, 16501)):
+        w = I.Workload(name=f"oddn_plain{norm}", M=M, K=K, N=N, in_dtype=I.BF16, out_dtype=I.F32, act=I.ACT_GELU_TANH, norm=norm,
+                       alpha=0.5, post_scale=1.0, eps=1e-5,
+                       dist={"X": ("normal", 0.0, 1.0), "W": ("normal", 0.0, 0.1), "b": None, "gamma": None, "beta": None})
+        t = I.generate(w)
+        d = {k: H.to_device(v) for k, v in t.items()}
+        p = B.make_params(d["X"], d["W"], torch.empty(M, N, device="cuda"))
+        assert B.fge_tile_name(True, w.act, norm, p) == "repacked_operands"
+        ref, raux = H.oracle_chain(w, t)
+        got, gaux = H.run_gpu(w, t, "fused", dev=d)
+        H.check(w, got, gaux, ref, raux, f"odd width, no bias or affine {(M, K, N)}")
+
+
 def test_unaligned_strides_and_odd_batches():
     """Aligned extents but row and batch strides that are not multiples of 16 bytes: padding is
     left untouched, results match the oracle."""
