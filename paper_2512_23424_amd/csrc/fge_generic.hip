@@ -137,7 +137,9 @@ __global__ __launch_bounds__(256) void generic_row_kernel(const GenArgs a) {
 // stride: one workgroup of four waves per row.  The statistics passes read 16 bytes per lane, four
 // loads in flight per thread; the last pass reads and writes one element per lane, so that a
 // wave's stores are one contiguous run whatever the alignment of the result's rows.  CACHE: the
-// row (at most 64 KB) is parked in LDS by the first pass and read from there afterwards.
+// row (at most 64 KB) is parked in LDS by the first pass and read from there afterwards; longer
+// rows are read from memory by every pass, and softmax / logsumexp take their two statistics in
+// one pass.
 // (The wave-per-row kernel above walks a row with one load in flight per lane: 2048 rows of 50257
 // columns took it 1.0 ms.)
 template <typename OutT, bool CACHE>
@@ -192,13 +194,35 @@ __global__ __launch_bounds__(256) void aligned_src_row_kernel(const GenArgs a) {
         for (int j = tid; j < a.N; j += 256) Store<OutT>::put(out + j, g(j, r[j]));
     };
     if (a.norm == FGE_NORM_SOFTMAX || a.norm == FGE_NORM_LOGSUMEXP) {
-        float m = OpMax::ident();
-        sweep_first([&](float v) __attribute__((always_inline)) { m = max_nc(m, v); });
-        m = block_reduce(OpMax{}, m);
-        const float c = -m * LOG2E;
-        float s = 0.0f;
-        sweep([&](float v) __attribute__((always_inline)) { s += exp_rel(v, c); });
-        s = block_reduce(OpSum{}, s);
+        float m = OpMax::ident(), s = 0.0f, c;
+        if constexpr (CACHE) {
+            sweep_first([&](float v) __attribute__((always_inline)) { m = max_nc(m, v); });
+            m = block_reduce(OpMax{}, m);
+            c = -m * LOG2E;
+            sweep([&](float v) __attribute__((always_inline)) { s += exp_rel(v, c); });
+            s = block_reduce(OpSum{}, s);
+        } else {
+            // a row that is read from memory every time: maximum and sum in one pass - every thread
+            // keeps a running maximum and rescales its sum so far whenever the maximum rises
+            // (a thread without elements ends with 0 * exp2(-inf) = 0)
+#pragma unroll 4
+            for (int q = tid; q < n4; q += 256) {
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(src + 4 * q);
+                const float mn = max_nc(max_nc(max_nc(v[0], v[1]), max_nc(v[2], v[3])), m);
+                const float cn = -mn * LOG2E;
+                s = s * exp_rel(m, cn) + ((exp_rel(v[0], cn) + exp_rel(v[1], cn)) + (exp_rel(v[2], cn) + exp_rel(v[3], cn)));
+                m = mn;
+            }
+            if (const int j = 4 * n4 + tid; j < a.N) {
+                const float v = src[j], mn = max_nc(v, m), cn = -mn * LOG2E;
+                s = s * exp_rel(m, cn) + exp_rel(v, cn);
+                m = mn;
+            }
+            const float mt = m;
+            m = block_reduce(OpMax{}, mt);
+            c = -m * LOG2E;
+            s = block_reduce(OpSum{}, s * exp_rel(mt, c));
+        }
         if (a.norm == FGE_NORM_SOFTMAX) {
             const float inv = 1.0f / s;
             emit([&](int, float v) __attribute__((always_inline)) { return exp_rel(v, c) * inv; });
