@@ -361,13 +361,14 @@ def test_odd_strides_of_a_large_batch_run_repacked():
 @pytest.mark.parametrize("norm", NORMS)
 @pytest.mark.parametrize("case", [(I.BF16, I.BF16, 1, 2050, 1024, 4099), (I.F32, I.F32, 1, 1500, 512, 2051),
                                   (I.BF16, I.F32, 3, 700, 256, 1031), (I.F8E4M3, I.BF16, 1, 1100, 512, 4097),
-                                  (I.BF16, I.BF16, 1, 300, 256, 16389), (I.F16, I.F16, 1, 260, 128, 16390)])
+                                  (I.BF16, I.BF16, 1, 300, 256, 16389), (I.F16, I.F16, 1, 260, 128, 16390),
+                                  (I.BF16, I.BF16, 1, 140, 128, 16319)])
 def test_odd_width_with_operands_that_need_no_copy(case, norm):
     """N odd, K and the operands' strides on the 16-byte grid (a vocabulary of 50257 entries is the
     case that matters): the fp32 rows of padded width are produced straight from X and W as they
     lie - W ends N rows down, the padding columns are fed from its last row - and the row kernel
-    writes the odd-width result (the last two cases: rows of more than 64 KB, which that kernel
-    re-reads from memory instead of parking them in LDS)."""
+    writes the odd-width result (16389 and 16390 columns: rows of more than 64 KB, which that
+    kernel re-reads from memory instead of parking them in LDS; 16319: the longest row it parks)."""
     idt, odt, batch, M, K, N = case
     w = I.Workload(name=f"oddn{norm}", M=M, K=K, N=N, batch=batch, in_dtype=idt, out_dtype=odt, act=I.ACT_SILU, norm=norm,
                    alpha=1.0 / K ** 0.5 if idt == I.F8E4M3 else 0.5, post_scale=1.5, eps=1e-5,
